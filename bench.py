@@ -1,0 +1,258 @@
+#!/usr/bin/env python3
+"""Decode-attention benchmark for libseamdecode on one MI355X.
+
+One step = one pass of the whole hot path over one batch: kv_append of one
+new token per sequence (bf16 workloads), then paged_decode_attention (split-K
+pass + merge pass).  Inputs are synthetic, seeded and resident in HBM before
+the timed region.  Workloads whose K/V pool is small enough to sit in the
+256 MB memory-side cache are rotated over several independent pools.
+
+Prints ONE JSON line: whole-step throughput as algorithmic HBM GB/s, the
+split-K kernel's roofline figures (HIP-event durations recorded by the library
+around its own launches), the read-probe ceiling, and the CPU oracle timed on
+the host cores over a bounded sample of the same workload.
+"""
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published peak, 8 TB/s
+SMALL_POOL_BYTES = 2 << 30  # rotate pools below this footprint
+
+
+def algorithmic_bytes(wl, chunk, include_append):
+    """Bytes one step must move if every operand travels exactly once.
+
+    Split pass (per launch): every attended K and V element once per
+    (sequence, kv head) = sum(L) * token_bytes; q; one table entry per logical
+    page; lengths; fp8 scales; the partials it writes.  Merge pass: partials
+    read back, out written.  Append: rows read and written once.
+    """
+    import numpy as np
+
+    lens = wl.context_lens.astype(np.int64)
+    kv = int(lens.sum()) * wl.token_bytes
+    nb = int(((lens + 15) // 16).sum())
+    chunks = int(((lens + chunk - 1) // chunk).sum())
+    q = wl.batch * wl.num_q_heads * wl.head_dim * 2
+    table = nb * 4 + wl.batch * 4
+    scales = nb * wl.num_kv_heads * 8 if wl.kv_dtype == "fp8" else 0
+    partials = chunks * wl.num_q_heads * (wl.head_dim + 2) * 4
+    out = wl.batch * wl.num_q_heads * wl.head_dim * 4
+    split = kv + q + table + scales + partials
+    merge = partials + out + wl.batch * 4
+    append = 0
+    if include_append and wl.k_new is not None:
+        append = 2 * 2 * wl.k_new.size * 2 + wl.k_new.shape[0] * 12
+    return {"split": split, "merge": merge, "append": append, "step": split + merge + append, "kv": kv}
+
+
+def stored_traffic(kernel_sources, workload_key):
+    """HBM bytes per split launch from the committed counter summary, or None
+    when the kernel source has changed since the counters were taken."""
+    path = os.path.join(ROOT, "profiles", "split_kernel_hbm_traffic.md")
+    try:
+        text = open(path).read()
+    except OSError:
+        return None
+    h = hashlib.sha256()
+    for s in kernel_sources:
+        h.update(open(s, "rb").read())
+    tag = f"source_sha256={h.hexdigest()[:16]}"
+    for line in text.splitlines():
+        if line.startswith("traffic_bytes_per_launch") and tag in line and f"workload={workload_key}" in line:
+            return float(line.split("value=")[1].split()[0])
+    return None
+
+
+def cpu_baseline(cfg, seconds_target=15.0):
+    """The oracle (fp64 build) on the host cores over the first sequences of
+    the same workload, sized to roughly `seconds_target` of CPU work."""
+    import numpy as np
+
+    import oracle
+    import workloads
+
+    oracle.build()
+    nthreads = oracle.num_threads()
+    # calibrate on two sequences, then size the sample
+    probe = workloads.make_config(cfg, batch=2, threads=nthreads)
+    rows = np.int32([(b, h) for b in range(probe.batch) for h in range(probe.num_q_heads)])
+    t0 = time.perf_counter()
+    oracle.attend_rows(probe.q, probe.k_pages, probe.v_pages, probe.block_table, probe.context_lens, probe.scale,
+                       rows, probe.k_scales, probe.v_scales, probe.kv_dtype)
+    dt = time.perf_counter() - t0
+    rate = probe.attended_tokens * probe.num_q_heads / dt  # (token, head) pairs per second
+    full = workloads.make_config(cfg, batch=None, threads=nthreads) if False else None
+    del full
+    lens_all = workloads.make_config(cfg, batch=1, threads=1)  # cheap: only to learn the batch size
+    nb = 2
+    want = rate * seconds_target
+    # lengths are drawn first and independently of the pool, so the prefix of the batch is the same sample
+    import workloads.gen as gen
+    all_lens = _config_lens(cfg)
+    acc = 0
+    for nb in range(1, len(all_lens) + 1):
+        acc += int(all_lens[nb - 1]) * probe.num_q_heads
+        if acc >= want:
+            break
+    wl = workloads.make_config(cfg, batch=nb, threads=nthreads)
+    rows = np.int32([(b, h) for b in range(wl.batch) for h in range(wl.num_q_heads)])
+    t0 = time.perf_counter()
+    oracle.attend_rows(wl.q, wl.k_pages, wl.v_pages, wl.block_table, wl.context_lens, wl.scale, rows,
+                       wl.k_scales, wl.v_scales, wl.kv_dtype)
+    dt = time.perf_counter() - t0
+    gbps = wl.attended_tokens * wl.token_bytes / dt / 1e9
+    return {
+        "value": gbps, "unit": "GB/s", "cores": nthreads, "kind": "oracle",
+        "sample": f"first {nb} of the workload's sequences ({wl.attended_tokens} attended tokens, all query heads), "
+                  f"fp64 oracle, {dt:.1f} s",
+        "attended_kv_tokens_per_s": wl.attended_tokens / dt,
+    }
+
+
+def _config_lens(cfg):
+    import workloads
+
+    # batch=1 still draws the full length vector first; re-draw it the same way
+    import numpy as np
+    from workloads.gen import _rng, _TAG_LENS
+    import math
+
+    r = _rng(0, _TAG_LENS)
+    if cfg == 0:
+        return r.integers(1, 512, size=4, endpoint=True)
+    if cfg == 1:
+        return r.integers(1024, 8192, size=64, endpoint=True)
+    if cfg == 2:
+        return np.clip(np.rint(np.exp(r.normal(math.log(16384.0), 1.0, size=32))).astype(np.int64), 2048, 65536)
+    if cfg == 3:
+        prefix = r.integers(2048, 16384, size=16, endpoint=True)
+        suffix = r.integers(64, 4096, size=256, endpoint=True)
+        return prefix[np.repeat(np.arange(16), 16)] + suffix + 1
+    return r.integers(512, 4096, size=1024, endpoint=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=1, help="workload index (BASELINE configs), default 1")
+    ap.add_argument("--chunk", type=int, default=0, help="split-K chunk override (tokens)")
+    ap.add_argument("--pools", type=int, default=0, help="number of rotating K/V pools (0 = automatic)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-append", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2508_11553_amd as sd
+    import workloads
+    from paper_2508_11553_amd.device import DeviceWorkload
+    from workloads.gen import draw_extra_pool
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    sd.load()
+    torch.cuda.set_device(0)
+    cfg = args.config
+    t_gen = time.perf_counter()
+    do_append = (not args.no_append) and cfg != 4
+    wl = workloads.make_config(cfg, append=do_append)
+    pool_bytes = 2 * wl.k_pages.nbytes
+    npools = args.pools or (4 if pool_bytes < SMALL_POOL_BYTES else 1)
+    dw = DeviceWorkload(wl, chunk_tokens=args.chunk)
+    pools = [(dw.k_pages, dw.v_pages, dw.k_scales, dw.v_scales)]
+    for i in range(1, npools):
+        k, v, ks, vs = draw_extra_pool(wl, seed=1000 + i)
+        dw.set_pool(k, v, ks, vs)
+        pools.append((dw.k_pages, dw.v_pages, dw.k_scales, dw.v_scales))
+    t_gen = time.perf_counter() - t_gen
+    chunk = dw.chunk_tokens()
+    ab = algorithmic_bytes(wl, chunk, do_append)
+    stream = torch.cuda.current_stream()
+
+    def step(i, timer=None):
+        dw.set_pool(*pools[i % npools])
+        if do_append:
+            dw.append(stream)
+        dw.attend(stream, timer)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+
+    # the same steps again with the library's HIP events around each kernel
+    timer = sd.KernelTimer(args.steps)
+    for i in range(args.steps):
+        step(i, timer)
+    torch.cuda.synchronize()
+    split_ms, merge_ms = timer.read()
+    timer.close()
+    split_avg = float(np.mean(split_ms))
+    merge_avg = float(np.mean(merge_ms))
+
+    # read-only probe over the same walk: the ceiling of this access pattern
+    from paper_2508_11553_amd.binding import probe_read, probe_sink_words
+    sink = torch.zeros(probe_sink_words(dw.shape), dtype=torch.int32, device=dw.device)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    nprobe = max(10, min(args.steps, 50))
+    for i in range(5):
+        probe_read(dw.shape, pools[i % npools][0], pools[i % npools][1], dw.block_table, dw.context_lens, sink, stream)
+    ev[0].record(stream)
+    for i in range(nprobe):
+        probe_read(dw.shape, pools[i % npools][0], pools[i % npools][1], dw.block_table, dw.context_lens, sink, stream)
+    ev[1].record(stream)
+    torch.cuda.synchronize()
+    probe_ms = ev[0].elapsed_time(ev[1]) / nprobe
+
+    value = ab["step"] / (ms_per_step * 1e-3) / 1e9
+    achieved = ab["split"] / (split_avg * 1e-3) / 1e9
+    src = [os.path.join(ROOT, "paper_2508_11553_amd", "csrc", f) for f in ("attn_split.hip", "kernels.h")]
+    rec = {
+        "metric": "decode-attention HBM GB/s (% of MI355X peak) + attended KV tokens/sec, 1 GPU",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if wl.kv_dtype == "bf16" else "fp8(e4m3fn KV)->bf16", "data": "synthetic",
+        "config": {
+            "workload": f"configs[{cfg}] {wl.name}", "batch": wl.batch, "q_heads": wl.num_q_heads,
+            "kv_heads": wl.num_kv_heads, "head_dim": wl.head_dim, "page_size": 16, "kv_dtype": wl.kv_dtype,
+            "attended_tokens": wl.attended_tokens, "unique_tokens": wl.unique_tokens, "chunk_tokens": chunk,
+            "pools_rotated": npools, "append_rows_per_step": int(wl.k_new.shape[0]) if do_append else 0, "seed": 0,
+        },
+        "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
+        "attended_kv_tokens_per_s": wl.attended_tokens / (ms_per_step * 1e-3),
+        "step_bytes": ab,
+        "kernel_ms": {"split": split_avg, "merge": merge_avg, "split_p10_p50_p90":
+                      [float(np.percentile(split_ms, p)) for p in (10, 50, 90)]},
+        "probe": {"ms": probe_ms, "GBps": ab["kv"] / (probe_ms * 1e-3) / 1e9,
+                  "what": "read-only walk of the same pages, 16-byte loads"},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": stored_traffic(src, f"configs[{cfg}]"),
+                     "kernel": "split pass (sd::split_*_kernel)", "algorithmic_bytes_per_launch": ab["split"]},
+        "input_generation_s": t_gen,
+    }
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(rec), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,180 @@
+/*
+ * libseamdecode -- paged decode attention for rollout on MI355X (gfx950).
+ *
+ * The paper's framework spends its run time in rollout: batched autoregressive
+ * decoding inside the inference engine (System Overview, engine layer;
+ * Pipeline Bubble Analysis: rollout takes much longer than training).  Each
+ * decode step attends one new query token per sequence over that sequence's
+ * KV cache.  Sequences have different lengths, are paused and resumed from
+ * their stored tokens (Data Plane: Rollout Manager, Trajectory Manager) and
+ * several trajectories of one session continue a common prefix (Trajectory
+ * Manager: longest-prefix matching / prefix tree), so the cache is paged and
+ * a block table maps each sequence's logical pages to physical pages that
+ * may be shared between sequences.
+ *
+ * Conventions for every call below
+ *   - All data pointers are DEVICE pointers owned by the caller and must be
+ *     16-byte aligned.  The library never allocates, frees or retains device
+ *     memory and never synchronises: a call validates its arguments on the
+ *     host, enqueues its kernels on `stream` (a hipStream_t, NULL = default
+ *     stream) and returns.
+ *   - Return value: SD_OK (0) or a negative SD_E* code.  On a validation
+ *     error nothing is enqueued and no output is written.
+ *   - No global state: calls from several host threads are independent.
+ *     Calls that write the same output/workspace/pages must be ordered by the
+ *     caller (same stream or events).
+ *
+ * Memory layouts (P = 16 tokens per page, d = head_dim, row-major, C order)
+ *   q            bf16   [batch][num_q_heads][d]
+ *   k_pages      bf16   [num_pages][num_kv_heads][16][d]     (SD_BF16)
+ *                u8     [num_pages][num_kv_heads][16][d]     (SD_FP8_E4M3: OCP e4m3fn codes)
+ *   v_pages      same shape and type as k_pages, separate pool
+ *   k_scales     f32    [num_pages][num_kv_heads]            (fp8 only: value = code * scale)
+ *   v_scales     f32    [num_pages][num_kv_heads]
+ *   block_table  i32    [batch][max_blocks_per_seq]          physical page of logical page j
+ *   context_lens i32    [batch]
+ *   out          f32    [batch][num_q_heads][d]
+ * Token t of sequence b is stored in page block_table[b][t / 16], slot t % 16.
+ * Query head h uses KV head h / (num_q_heads / num_kv_heads).
+ * Slots at positions >= context_lens[b] and table entries past the last
+ * logical page are never read, whatever they contain.
+ */
+#ifndef SEAMDECODE_H
+#define SEAMDECODE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SD_OK 0
+#define SD_EINVAL (-1)       /* null or misaligned pointer, or a dimension out of range */
+#define SD_EUNSUPPORTED (-2) /* valid request this build has no kernel for */
+#define SD_EWORKSPACE (-3)   /* workspace smaller than sd_workspace_bytes() */
+#define SD_EHIP (-4)         /* a HIP call failed; see sd_last_hip_error() */
+
+#define SD_BF16 0
+#define SD_FP8_E4M3 1
+
+typedef struct {
+    int32_t batch;              /* B >= 0 (0: the call is a no-op) */
+    int32_t num_q_heads;        /* Hq */
+    int32_t num_kv_heads;       /* Hkv; Hq % Hkv == 0 and Hq / Hkv <= 16 */
+    int32_t head_dim;           /* 64 or 128 */
+    int32_t page_size;          /* must be 16 */
+    int32_t num_pages;          /* extent of the pools */
+    int32_t max_blocks_per_seq; /* row stride of block_table */
+    int32_t kv_dtype;           /* SD_BF16 or SD_FP8_E4M3 */
+    int32_t max_context_len;    /* host-known upper bound on context_lens[]; lengths above it
+                                   are treated as max_context_len; <= 16 * max_blocks_per_seq */
+    int32_t chunk_tokens;       /* split-K chunk in tokens: 0 = library default, else a
+                                   multiple of 128 in [128, 65536] */
+} sd_shape;
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int sd_version(void);
+
+/* Static, human-readable text for an SD_* code. */
+const char *sd_strerror(int code);
+
+/* hipError_t (as int) of the last failing HIP call made by this thread; 0 if none. */
+int sd_last_hip_error(void);
+
+/* The split-K chunk (tokens) the library uses for this shape; <= 0 is an SD_E* code. */
+int sd_chunk_tokens(const sd_shape *shape);
+
+/*
+ * Bytes of scratch paged_decode_attention needs for this shape (host-only
+ * arithmetic).  Returns 0 for an invalid shape.
+ */
+size_t sd_workspace_bytes(const sd_shape *shape);
+
+/*
+ * kv_append -- write new tokens' K/V rows into their page slots.
+ *
+ * Advancing a rollout by one token, or resuming a paused trajectory from its
+ * stored tokens (Data Plane: partial rollout resumes from previously produced
+ * tokens), puts rows into the cache: row j of k_new/v_new belongs to sequence
+ * seq_ids[j] at position positions[j] and is copied, for every KV head, to
+ * page block_table[seq_ids[j]][positions[j] / 16], slot positions[j] % 16.
+ *
+ *   k_new, v_new   bf16 [T][num_kv_heads][d]   (device, read)
+ *   seq_ids        i32  [T]                    (device, read) in [0, batch)
+ *   positions      i32  [T]                    (device, read) in [0, 16*max_blocks_per_seq)
+ *   k_pages,v_pages                            (device, written at the addressed slots only)
+ *   block_table                                (device, read)
+ * Only SD_BF16 pools are supported (SD_EUNSUPPORTED otherwise).  context_lens
+ * is not touched: sequence state belongs to the caller.  Two rows that address
+ * the same slot race.  T == 0 is a no-op.
+ */
+int kv_append(const sd_shape *shape, const void *k_new, const void *v_new,
+              const int32_t *seq_ids, const int32_t *positions, int32_t T,
+              void *k_pages, void *v_pages, const int32_t *block_table, void *stream);
+
+/*
+ * paged_decode_attention -- one decode step of attention for every sequence.
+ *
+ * For each sequence b with L = min(context_lens[b], max_context_len) tokens
+ * and each query head h (g = h / G):
+ *     s_t = scale * <q[b][h], K_t>,  p = softmax_t(s),  out[b][h] = sum_t p_t V_t
+ * with K_t, V_t the rows of KV head g at logical position t (fp8: code times
+ * the page's scale).  L == 0 gives a zero row.  Products are accumulated in
+ * fp32 from bf16 operands; softmax weights are rounded to bf16 before the
+ * weighted sum and normalised by the sum of the rounded weights.
+ *
+ * Runs two kernels: a split-K pass over chunks of `chunk_tokens` tokens that
+ * streams every K/V page once per (sequence, KV head) and leaves per-chunk
+ * (max, sum, weighted sum) in `workspace`, and a merge pass that writes `out`.
+ * Results do not depend on the physical placement of pages.
+ *
+ *   k_scales, v_scales  NULL for SD_BF16
+ *   workspace           >= sd_workspace_bytes(shape) bytes, contents ignored on entry
+ */
+int paged_decode_attention(const sd_shape *shape, const void *q,
+                           const void *k_pages, const void *v_pages,
+                           const float *k_scales, const float *v_scales,
+                           const int32_t *block_table, const int32_t *context_lens,
+                           float scale, float *out,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Measurement aids (not part of the decode step).
+ *
+ * sd_timer owns HIP events (host objects; no device memory).  The _timed
+ * variant of the attention call records events around each of its kernels on
+ * `stream`; sd_timer_read waits for them and returns per-call kernel times.
+ */
+typedef struct sd_timer sd_timer;
+sd_timer *sd_timer_create(int32_t max_calls);
+void sd_timer_destroy(sd_timer *t);
+void sd_timer_reset(sd_timer *t);
+/* Fills up to `cap` entries of split_ms[] / merge_ms[] (host arrays); returns the
+   number of recorded calls or an SD_E* code.  Synchronises on the recorded events. */
+int sd_timer_read(sd_timer *t, float *split_ms, float *merge_ms, int32_t cap);
+
+int paged_decode_attention_timed(const sd_shape *shape, const void *q,
+                                 const void *k_pages, const void *v_pages,
+                                 const float *k_scales, const float *v_scales,
+                                 const int32_t *block_table, const int32_t *context_lens,
+                                 float scale, float *out,
+                                 void *workspace, size_t workspace_bytes, void *stream,
+                                 sd_timer *timer);
+
+/*
+ * sd_probe_read -- streams exactly the K and V bytes paged_decode_attention
+ * must read (same block-table walk, same chunking, 16-byte loads), does no
+ * arithmetic on them beyond an XOR fold, and writes one word per workgroup to
+ * `sink` (u32 [sd_probe_sink_words(shape)], device).  Its duration is the
+ * bandwidth ceiling of this access pattern on the machine at hand.
+ */
+size_t sd_probe_sink_words(const sd_shape *shape);
+int sd_probe_read(const sd_shape *shape, const void *k_pages, const void *v_pages,
+                  const int32_t *block_table, const int32_t *context_lens,
+                  uint32_t *sink, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SEAMDECODE_H */

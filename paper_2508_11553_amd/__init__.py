@@ -1,0 +1,23 @@
+"""libseamdecode: paged decode attention for MI355X (gfx950).
+
+Thin ctypes binding over the C ABI in include/seamdecode.h.  Every step of the
+decode path runs in the HIP kernels of libseamdecode.so; Python only marshals
+pointers.  torch supplies device memory and streams.  There is no CPU
+fallback: if the shared library is missing, loading raises.
+"""
+from .binding import (  # noqa: F401
+    SD_BF16,
+    SD_FP8_E4M3,
+    SeamDecodeError,
+    Shape,
+    KernelTimer,
+    chunk_tokens,
+    kv_append,
+    lib_path,
+    load,
+    paged_decode_attention,
+    probe_read,
+    strerror,
+    version,
+    workspace_bytes,
+)

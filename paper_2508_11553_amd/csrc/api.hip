@@ -1,0 +1,294 @@
+// Host side of libseamdecode: argument validation and kernel dispatch behind
+// the C ABI declared in include/seamdecode.h.  No device allocation, no
+// synchronisation (sd_timer_read excepted, which waits on its own events).
+#include "../../include/seamdecode.h"
+#include "kernels.h"
+
+#include <new>
+#include <vector>
+
+namespace {
+
+thread_local int tl_hip_error = 0;
+
+int hip_fail(hipError_t e)
+{
+    tl_hip_error = (int)e;
+    return SD_EHIP;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+bool bad_ptr(const void *p) { return p == nullptr || !aligned16(p); }
+
+// Shape checks common to every entry point.
+int check_shape(const sd_shape *s)
+{
+    if (!s) return SD_EINVAL;
+    if (s->batch < 0 || s->num_q_heads <= 0 || s->num_kv_heads <= 0 || s->num_pages < 0 ||
+        s->max_blocks_per_seq <= 0 || s->max_context_len < 0 || s->head_dim <= 0)
+        return SD_EINVAL;
+    if (s->page_size != sd::kPage) return SD_EINVAL;
+    if (s->num_q_heads % s->num_kv_heads != 0) return SD_EINVAL;
+    if ((int64_t)s->max_context_len > (int64_t)sd::kPage * s->max_blocks_per_seq) return SD_EINVAL;
+    if (s->kv_dtype != SD_BF16 && s->kv_dtype != SD_FP8_E4M3) return SD_EINVAL;
+    if (s->chunk_tokens != 0 &&
+        (s->chunk_tokens < 128 || s->chunk_tokens > 65536 || s->chunk_tokens % 128 != 0))
+        return SD_EINVAL;
+    if (s->head_dim != 64 && s->head_dim != 128) return SD_EUNSUPPORTED;
+    if (s->num_q_heads / s->num_kv_heads > sd::kMaxGroup) return SD_EUNSUPPORTED;
+    return SD_OK;
+}
+
+// Split-K chunk: a function of the shape alone, so that chunk boundaries
+// depend only on logical positions.
+int pick_chunk(const sd_shape *s)
+{
+    if (s->chunk_tokens) return s->chunk_tokens;
+    return 512;
+}
+
+int num_chunks(const sd_shape *s, int chunk)
+{
+    const int n = (s->max_context_len + chunk - 1) / chunk;
+    return n > 0 ? n : 1;
+}
+
+struct WsLayout {
+    size_t m_off, l_off, acc_off, total;
+};
+
+WsLayout ws_layout(const sd_shape *s, int S)
+{
+    const size_t rows = (size_t)s->batch * (size_t)s->num_q_heads * (size_t)S;
+    WsLayout w;
+    w.m_off = 0;
+    w.l_off = (rows * 4 + 255) & ~(size_t)255;
+    w.acc_off = w.l_off + ((rows * 4 + 255) & ~(size_t)255);
+    w.total = w.acc_off + rows * (size_t)s->head_dim * 4;
+    return w;
+}
+
+}  // namespace
+
+struct sd_timer {
+    std::vector<hipEvent_t> ev;  // 3 per call: before split, between, after merge
+    int32_t max_calls = 0, calls = 0;
+};
+
+extern "C" {
+
+int sd_version(void) { return 100; }
+
+const char *sd_strerror(int code)
+{
+    switch (code) {
+    case SD_OK: return "success";
+    case SD_EINVAL: return "invalid argument (null or misaligned pointer, or dimension out of range)";
+    case SD_EUNSUPPORTED: return "shape or dtype not supported by this build";
+    case SD_EWORKSPACE: return "workspace too small; see sd_workspace_bytes()";
+    case SD_EHIP: return "a HIP call failed; see sd_last_hip_error()";
+    default: return "unknown error code";
+    }
+}
+
+int sd_last_hip_error(void) { return tl_hip_error; }
+
+int sd_chunk_tokens(const sd_shape *shape)
+{
+    const int rc = check_shape(shape);
+    if (rc) return rc;
+    return pick_chunk(shape);
+}
+
+size_t sd_workspace_bytes(const sd_shape *shape)
+{
+    if (check_shape(shape)) return 0;
+    const int chunk = pick_chunk(shape);
+    const size_t t = ws_layout(shape, num_chunks(shape, chunk)).total;
+    return t ? t : 256;
+}
+
+int kv_append(const sd_shape *shape, const void *k_new, const void *v_new,
+              const int32_t *seq_ids, const int32_t *positions, int32_t T,
+              void *k_pages, void *v_pages, const int32_t *block_table, void *stream)
+{
+    const int rc = check_shape(shape);
+    if (rc) return rc;
+    if (T < 0) return SD_EINVAL;
+    if (shape->kv_dtype != SD_BF16) return SD_EUNSUPPORTED;
+    if (T == 0) return SD_OK;
+    if (bad_ptr(k_new) || bad_ptr(v_new) || bad_ptr(seq_ids) || bad_ptr(positions) || bad_ptr(k_pages) ||
+        bad_ptr(v_pages) || bad_ptr(block_table))
+        return SD_EINVAL;
+    sd::AppendArgs a;
+    a.k_new = static_cast<const uint4 *>(k_new);
+    a.v_new = static_cast<const uint4 *>(v_new);
+    a.seq_ids = seq_ids;
+    a.positions = positions;
+    a.k_pages = static_cast<uint4 *>(k_pages);
+    a.v_pages = static_cast<uint4 *>(v_pages);
+    a.block_table = block_table;
+    a.T = T;
+    a.Hkv = shape->num_kv_heads;
+    a.max_blocks = shape->max_blocks_per_seq;
+    const hipError_t e = sd::launch_append(a, shape->head_dim, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SD_OK : hip_fail(e);
+}
+
+int paged_decode_attention_timed(const sd_shape *shape, const void *q, const void *k_pages,
+                                 const void *v_pages, const float *k_scales, const float *v_scales,
+                                 const int32_t *block_table, const int32_t *context_lens, float scale,
+                                 float *out, void *workspace, size_t workspace_bytes, void *stream,
+                                 sd_timer *timer)
+{
+    const int rc = check_shape(shape);
+    if (rc) return rc;
+    if (shape->batch == 0) return SD_OK;
+    if (bad_ptr(q) || bad_ptr(k_pages) || bad_ptr(v_pages) || bad_ptr(block_table) || bad_ptr(context_lens) ||
+        bad_ptr(out) || bad_ptr(workspace))
+        return SD_EINVAL;
+    if (shape->kv_dtype == SD_FP8_E4M3 && (bad_ptr(k_scales) || bad_ptr(v_scales))) return SD_EINVAL;
+    if (!(scale == scale)) return SD_EINVAL;
+    const int chunk = pick_chunk(shape);
+    const int S = num_chunks(shape, chunk);
+    const WsLayout w = ws_layout(shape, S);
+    if (workspace_bytes < w.total) return SD_EWORKSPACE;
+    if ((uint64_t)S * (uint64_t)shape->batch * (uint64_t)shape->num_kv_heads > 0x7fffffffull) return SD_EUNSUPPORTED;
+    if (timer && timer->calls >= timer->max_calls) return SD_EINVAL;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    sd::SplitArgs sa;
+    sa.q = static_cast<const uint16_t *>(q);
+    sa.k_pages = k_pages;
+    sa.v_pages = v_pages;
+    sa.k_scales = k_scales;
+    sa.v_scales = v_scales;
+    sa.block_table = block_table;
+    sa.context_lens = context_lens;
+    sa.ws_m = reinterpret_cast<float *>(ws + w.m_off);
+    sa.ws_l = reinterpret_cast<float *>(ws + w.l_off);
+    sa.ws_acc = reinterpret_cast<float *>(ws + w.acc_off);
+    sa.scale_log2e = scale * 1.4426950408889634f;
+    sa.B = shape->batch;
+    sa.Hq = shape->num_q_heads;
+    sa.Hkv = shape->num_kv_heads;
+    sa.G = shape->num_q_heads / shape->num_kv_heads;
+    sa.max_blocks = shape->max_blocks_per_seq;
+    sa.S = S;
+    sa.chunk_tokens = chunk;
+    sa.max_context_len = shape->max_context_len;
+
+    sd::MergeArgs ma;
+    ma.ws_m = sa.ws_m;
+    ma.ws_l = sa.ws_l;
+    ma.ws_acc = sa.ws_acc;
+    ma.context_lens = context_lens;
+    ma.out = out;
+    ma.B = shape->batch;
+    ma.Hq = shape->num_q_heads;
+    ma.S = S;
+    ma.chunk_tokens = chunk;
+    ma.max_context_len = shape->max_context_len;
+
+    hipEvent_t *ev = timer ? &timer->ev[(size_t)timer->calls * 3] : nullptr;
+    hipError_t e;
+    if (ev && (e = hipEventRecord(ev[0], st)) != hipSuccess) return hip_fail(e);
+    if ((e = sd::launch_split(sa, shape->head_dim, shape->kv_dtype, st)) != hipSuccess)
+        return e == hipErrorNotSupported ? SD_EUNSUPPORTED : hip_fail(e);
+    if (ev && (e = hipEventRecord(ev[1], st)) != hipSuccess) return hip_fail(e);
+    if ((e = sd::launch_merge(ma, shape->head_dim, st)) != hipSuccess) return hip_fail(e);
+    if (ev) {
+        if ((e = hipEventRecord(ev[2], st)) != hipSuccess) return hip_fail(e);
+        timer->calls++;
+    }
+    return SD_OK;
+}
+
+int paged_decode_attention(const sd_shape *shape, const void *q, const void *k_pages, const void *v_pages,
+                           const float *k_scales, const float *v_scales, const int32_t *block_table,
+                           const int32_t *context_lens, float scale, float *out, void *workspace,
+                           size_t workspace_bytes, void *stream)
+{
+    return paged_decode_attention_timed(shape, q, k_pages, v_pages, k_scales, v_scales, block_table,
+                                        context_lens, scale, out, workspace, workspace_bytes, stream, nullptr);
+}
+
+sd_timer *sd_timer_create(int32_t max_calls)
+{
+    if (max_calls <= 0) return nullptr;
+    sd_timer *t = new (std::nothrow) sd_timer;
+    if (!t) return nullptr;
+    t->max_calls = max_calls;
+    t->ev.resize((size_t)max_calls * 3, nullptr);
+    for (auto &e : t->ev) {
+        const hipError_t rc = hipEventCreate(&e);
+        if (rc != hipSuccess) {
+            tl_hip_error = (int)rc;
+            sd_timer_destroy(t);
+            return nullptr;
+        }
+    }
+    return t;
+}
+
+void sd_timer_destroy(sd_timer *t)
+{
+    if (!t) return;
+    for (auto e : t->ev)
+        if (e) (void)hipEventDestroy(e);
+    delete t;
+}
+
+void sd_timer_reset(sd_timer *t)
+{
+    if (t) t->calls = 0;
+}
+
+int sd_timer_read(sd_timer *t, float *split_ms, float *merge_ms, int32_t cap)
+{
+    if (!t || !split_ms || !merge_ms || cap < 0) return SD_EINVAL;
+    const int n = t->calls < cap ? t->calls : cap;
+    for (int i = 0; i < n; ++i) {
+        hipEvent_t *ev = &t->ev[(size_t)i * 3];
+        hipError_t e = hipEventSynchronize(ev[2]);
+        if (e == hipSuccess) e = hipEventElapsedTime(&split_ms[i], ev[0], ev[1]);
+        if (e == hipSuccess) e = hipEventElapsedTime(&merge_ms[i], ev[1], ev[2]);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    return n;
+}
+
+size_t sd_probe_sink_words(const sd_shape *shape)
+{
+    if (check_shape(shape)) return 0;
+    const size_t n = (size_t)num_chunks(shape, pick_chunk(shape)) * (size_t)shape->batch * (size_t)shape->num_kv_heads;
+    return n ? n : 1;
+}
+
+int sd_probe_read(const sd_shape *shape, const void *k_pages, const void *v_pages, const int32_t *block_table,
+                  const int32_t *context_lens, uint32_t *sink, void *stream)
+{
+    const int rc = check_shape(shape);
+    if (rc) return rc;
+    if (shape->batch == 0) return SD_OK;
+    if (bad_ptr(k_pages) || bad_ptr(v_pages) || bad_ptr(block_table) || bad_ptr(context_lens) || bad_ptr(sink))
+        return SD_EINVAL;
+    sd::ProbeArgs a;
+    a.k_pages = k_pages;
+    a.v_pages = v_pages;
+    a.block_table = block_table;
+    a.context_lens = context_lens;
+    a.sink = sink;
+    a.B = shape->batch;
+    a.Hkv = shape->num_kv_heads;
+    a.max_blocks = shape->max_blocks_per_seq;
+    a.chunk_tokens = pick_chunk(shape);
+    a.S = num_chunks(shape, a.chunk_tokens);
+    a.max_context_len = shape->max_context_len;
+    a.tile_bytes = sd::kPage * shape->head_dim * (shape->kv_dtype == SD_BF16 ? 2 : 1);
+    const hipError_t e = sd::launch_probe(a, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SD_OK : hip_fail(e);
+}
+
+}  // extern "C"

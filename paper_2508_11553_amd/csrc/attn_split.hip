@@ -1,0 +1,312 @@
+// Split-K pass of paged decode attention for gfx950 (wave64, MFMA).
+//
+// One workgroup (4 waves) owns one (sequence b, KV head g, chunk c of
+// `chunk_tokens` tokens).  All G query heads of the KV head ride in one MFMA
+// tile, so every K/V byte of the chunk is fetched once.  Each wave walks the
+// chunk in 32-token tiles (two pages), software-pipelined one tile ahead:
+//
+//   S^T[token][head] = K_tile[token][d] . Q^T[d][head]      mfma 16x16x32 bf16
+//   online softmax over tokens (base 2; scale*log2e folded into the scores)
+//   O^T[d][head]    += V^T[d][token] . P^T[token][head]      mfma 16x16x32 bf16
+//
+// Computing the transposed products makes the accumulator layout of the first
+// MFMA (lane = head, registers = tokens) exactly the B-operand layout of the
+// second one, so the weights never leave their lanes.  K rows are loaded
+// straight into A-operand layout (lane = token, 16 bytes along d).  V rows
+// are loaded as 8-byte pieces (16 lanes cover 128 contiguous bytes of a row)
+// and transposed 4x4 inside each lane with byte permutes, because the second
+// product contracts over tokens while memory is contiguous along d.
+//
+// The four waves' (max, sum, O) are merged through LDS and written as one
+// partial per (b, head, chunk); the merge kernel finishes the softmax.
+#include "kernels.h"
+
+namespace sd {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+
+#define SD_DEV __device__ __forceinline__
+
+SD_DEV f32x4 mfma_bf16_k32(u32x4 a, u32x4 b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                   __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// (lo16 of x) | (lo16 of y) << 16, or the same with the high halves
+SD_DEV unsigned pack_lo(unsigned x, unsigned y) { return __builtin_amdgcn_perm(y, x, 0x05040100u); }
+SD_DEV unsigned pack_hi(unsigned x, unsigned y) { return __builtin_amdgcn_perm(y, x, 0x07060302u); }
+
+// two floats -> packed bf16 pair, round-to-nearest-even (v_cvt_pk_bf16_f32)
+SD_DEV unsigned cvt_pk_bf16(float lo, float hi)
+{
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    bf16x2 r;
+    r[0] = (__bf16)lo;
+    r[1] = (__bf16)hi;
+    return __builtin_bit_cast(unsigned, r);
+}
+
+// K/V bytes are used once per launch: load them with the non-temporal hint so
+// that they stream through the caches instead of displacing each other.
+template <typename T>
+SD_DEV T stream_load(const T *p) { return __builtin_nontemporal_load(p); }
+
+SD_DEV float xor_max(float x, int mask) { return fmaxf(x, __shfl_xor(x, mask, 64)); }
+SD_DEV float xor_add(float x, int mask) { return x + __shfl_xor(x, mask, 64); }
+
+// Registers of one 32-token tile as they arrive from memory.
+template <int D>
+struct Tile {
+    u32x4 k[2][D / 32];     // [page][step]: K row (lane&15), d = 32*step + 8*(lane>>4) .. +8
+    u32x2 v[2][D / 64][4];  // [page][half][j]: V row 4*(lane>>4)+j, d = 64*half + 4*(lane&15) .. +4
+};
+
+template <int D>
+SD_DEV void load_page_bf16(Tile<D> &r, int pg, const char *kp, const char *vp, int lane)
+{
+    const char *kl = kp + (lane & 15) * (D * 2) + (lane >> 4) * 16;
+#pragma unroll
+    for (int s = 0; s < D / 32; ++s) r.k[pg][s] = stream_load(reinterpret_cast<const u32x4 *>(kl + s * 64));
+    const char *vl = vp + (lane >> 4) * 4 * (D * 2) + (lane & 15) * 8;
+#pragma unroll
+    for (int h = 0; h < D / 64; ++h)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            r.v[pg][h][j] = stream_load(reinterpret_cast<const u32x2 *>(vl + j * (D * 2) + h * 128));
+}
+
+template <int D>
+SD_DEV void zero_page(Tile<D> &r, int pg)
+{
+#pragma unroll
+    for (int s = 0; s < D / 32; ++s) r.k[pg][s] = u32x4{0, 0, 0, 0};
+#pragma unroll
+    for (int h = 0; h < D / 64; ++h)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) r.v[pg][h][j] = u32x2{0, 0};
+}
+
+template <int D>
+struct WaveState {
+    float m;                 // running max of this lane's head (same in the 4 lanes of a head)
+    float l;                 // this lane's share of the weight sum
+    f32x4 acc[D / 64][4];    // acc[h][i][r] = O[head lane&15][d = 64h + 16(lane>>4) + 4r + i]
+};
+
+// One 32-token tile: tokens tok0 .. tok0+31, of which those < t_end are real.
+template <int D>
+SD_DEV void consume_tile(Tile<D> &r, const u32x4 (&qop)[D / 32], WaveState<D> &st,
+                         float scale_log2e, int tok0, int t_end, int lane)
+{
+    const int qd = lane >> 4;
+    f32x4 sa = {0, 0, 0, 0}, sb = {0, 0, 0, 0};
+#pragma unroll
+    for (int s = 0; s < D / 32; ++s) {
+        sa = mfma_bf16_k32(r.k[0][s], qop[s], sa);
+        sb = mfma_bf16_k32(r.k[1][s], qop[s], sb);
+    }
+    // lane holds, for head lane&15, tokens tok0 + 4qd + e (page A) and tok0 + 16 + 4qd + e (page B)
+    float x[8];
+    const bool ragged = tok0 + kTileTokens > t_end;  // wave-uniform
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        x[e] = sa[e] * scale_log2e;
+        x[4 + e] = sb[e] * scale_log2e;
+    }
+    if (ragged) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (tok0 + 4 * qd + e >= t_end) x[e] = -INFINITY;
+            if (tok0 + 16 + 4 * qd + e >= t_end) x[4 + e] = -INFINITY;
+        }
+    }
+    float tmax = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+    tmax = xor_max(xor_max(tmax, 16), 32);
+    const float m_new = fmaxf(st.m, tmax);
+    const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
+    st.m = m_new;
+    unsigned pw[4];
+    float psum = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; e += 2) {
+        const float p0 = __builtin_amdgcn_exp2f(x[e] - m_new);
+        const float p1 = __builtin_amdgcn_exp2f(x[e + 1] - m_new);
+        const unsigned w = cvt_pk_bf16(p0, p1);
+        pw[e >> 1] = w;
+        // the sum runs over the rounded weights, the ones the product below uses
+        psum += __builtin_bit_cast(float, w << 16) + __builtin_bit_cast(float, w & 0xffff0000u);
+    }
+    st.l = st.l * alpha + psum;
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f)) {
+#pragma unroll
+        for (int h = 0; h < D / 64; ++h)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) st.acc[h][i] *= alpha;
+    }
+    const u32x4 pop = {pw[0], pw[1], pw[2], pw[3]};
+
+    auto &v = r.v;
+    if (ragged) {  // slots past the end may hold anything, NaN included: 0 * NaN must not happen
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (tok0 + 16 * pg + 4 * qd + j >= t_end) {
+#pragma unroll
+                    for (int h = 0; h < D / 64; ++h) v[pg][h][j] = u32x2{0, 0};
+                }
+    }
+#pragma unroll
+    for (int h = 0; h < D / 64; ++h) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int w = i >> 1;
+            u32x4 a;
+            if (i & 1) {
+                a[0] = pack_hi(v[0][h][0][w], v[0][h][1][w]);
+                a[1] = pack_hi(v[0][h][2][w], v[0][h][3][w]);
+                a[2] = pack_hi(v[1][h][0][w], v[1][h][1][w]);
+                a[3] = pack_hi(v[1][h][2][w], v[1][h][3][w]);
+            } else {
+                a[0] = pack_lo(v[0][h][0][w], v[0][h][1][w]);
+                a[1] = pack_lo(v[0][h][2][w], v[0][h][3][w]);
+                a[2] = pack_lo(v[1][h][0][w], v[1][h][1][w]);
+                a[3] = pack_lo(v[1][h][2][w], v[1][h][3][w]);
+            }
+            st.acc[h][i] = mfma_bf16_k32(a, pop, st.acc[h][i]);
+        }
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(kWaves * 64, 2) void split_bf16_kernel(SplitArgs a)
+{
+    constexpr int kRow = D + 4;  // padded LDS row: 16 heads x float4 stores hit 64 distinct banks
+    __shared__ __attribute__((aligned(16))) float s_acc[kWaves][kMaxGroup][kRow];
+    __shared__ float s_m[kWaves][kMaxGroup];
+    __shared__ float s_l[kWaves][kMaxGroup];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int item = blockIdx.x;  // (chunk, sequence, kv head), kv head fastest
+    const int g = item % a.Hkv;
+    const int b = (item / a.Hkv) % a.B;
+    const int c = item / (a.Hkv * a.B);
+
+    const int L = min(a.context_lens[b], a.max_context_len);
+    const int t0 = c * a.chunk_tokens;
+    if (t0 >= L) return;
+    const int t1 = min(L, t0 + a.chunk_tokens);
+    const int ntiles = (t1 - t0 + kTileTokens - 1) / kTileTokens;
+
+    // Q^T operand: lane = head n, d = 32*step + 8*(lane>>4) .. +8; heads >= G are zero rows
+    const int n = lane & 15;
+    u32x4 qop[D / 32];
+    {
+        const uint16_t *qrow = a.q + ((int64_t)b * a.Hq + (int64_t)g * a.G + n) * D + (lane >> 4) * 8;
+#pragma unroll
+        for (int s = 0; s < D / 32; ++s)
+            qop[s] = (n < a.G) ? *reinterpret_cast<const u32x4 *>(qrow + s * 32) : u32x4{0, 0, 0, 0};
+    }
+
+    WaveState<D> st;
+    st.m = -INFINITY;
+    st.l = 0.f;
+#pragma unroll
+    for (int h = 0; h < D / 64; ++h)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) st.acc[h][i] = f32x4{0, 0, 0, 0};
+
+    const int32_t *bt = a.block_table + (int64_t)b * a.max_blocks + t0 / kPage;
+    const int64_t tile_bytes = (int64_t)kPage * D * 2;
+    const int64_t page_bytes = tile_bytes * a.Hkv;
+    const char *kbase = static_cast<const char *>(a.k_pages) + g * tile_bytes;
+    const char *vbase = static_cast<const char *>(a.v_pages) + g * tile_bytes;
+
+    auto fetch = [&](Tile<D> &r, int ti) {
+        const int tok0 = t0 + ti * kTileTokens;
+        const int64_t pa = bt[2 * ti];
+        load_page_bf16<D>(r, 0, kbase + pa * page_bytes, vbase + pa * page_bytes, lane);
+        if (tok0 + kPage < t1) {  // wave-uniform: the tile's second page exists
+            const int64_t pb = bt[2 * ti + 1];
+            load_page_bf16<D>(r, 1, kbase + pb * page_bytes, vbase + pb * page_bytes, lane);
+        } else {
+            zero_page<D>(r, 1);
+        }
+    };
+
+    Tile<D> ra, rb;
+    int ti = wave;
+    if (ti < ntiles) fetch(ra, ti);
+    while (ti < ntiles) {
+        int tn = ti + kWaves;
+        if (tn < ntiles) fetch(rb, tn);
+        consume_tile<D>(ra, qop, st, a.scale_log2e, t0 + ti * kTileTokens, t1, lane);
+        ti = tn;
+        if (ti >= ntiles) break;
+        tn = ti + kWaves;
+        if (tn < ntiles) fetch(ra, tn);
+        consume_tile<D>(rb, qop, st, a.scale_log2e, t0 + ti * kTileTokens, t1, lane);
+        ti = tn;
+    }
+
+    // the four lanes of a head hold disjoint shares of the weight sum
+    st.l = xor_add(xor_add(st.l, 16), 32);
+
+    const int qd = lane >> 4;
+    if (qd == 0) {
+        s_m[wave][n] = st.m;
+        s_l[wave][n] = st.l;
+    }
+#pragma unroll
+    for (int h = 0; h < D / 64; ++h)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const f32x4 o = {st.acc[h][0][r], st.acc[h][1][r], st.acc[h][2][r], st.acc[h][3][r]};
+            *reinterpret_cast<f32x4 *>(&s_acc[wave][n][64 * h + 16 * qd + 4 * r]) = o;
+        }
+    __syncthreads();
+
+    // merge the four waves; wave 0 always saw at least one token, so the max is finite
+    const int64_t row0 = (int64_t)b * a.Hq + (int64_t)g * a.G;
+    for (int idx = tid; idx < a.G * D; idx += kWaves * 64) {
+        const int hn = idx / D, dd = idx % D;
+        float M = s_m[0][hn];
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) M = fmaxf(M, s_m[w][hn]);
+        float num = 0.f, den = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const float wt = __builtin_amdgcn_exp2f(s_m[w][hn] - M);
+            num += wt * s_acc[w][hn][dd];
+            den += wt * s_l[w][hn];
+        }
+        const int64_t slot = (row0 + hn) * a.S + c;
+        a.ws_acc[slot * D + dd] = num;
+        if (dd == 0) {
+            a.ws_m[slot] = M;
+            a.ws_l[slot] = den;
+        }
+    }
+}
+
+hipError_t launch_split(const SplitArgs &a, int head_dim, int kv_dtype, hipStream_t stream)
+{
+    const unsigned grid = (unsigned)a.S * (unsigned)a.B * (unsigned)a.Hkv;
+    if (grid == 0) return hipSuccess;
+    if (kv_dtype != 0) return hipErrorNotSupported;
+    if (head_dim == 128)
+        hipLaunchKernelGGL(split_bf16_kernel<128>, dim3(grid), dim3(kWaves * 64), 0, stream, a);
+    else if (head_dim == 64)
+        hipLaunchKernelGGL(split_bf16_kernel<64>, dim3(grid), dim3(kWaves * 64), 0, stream, a);
+    else
+        return hipErrorNotSupported;
+    return hipGetLastError();
+}
+
+}  // namespace sd

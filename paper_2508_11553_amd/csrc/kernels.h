@@ -1,0 +1,60 @@
+// Internal declarations shared by the host entry points and the kernels of
+// libseamdecode.  Not installed; the public interface is include/seamdecode.h.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sd {
+
+constexpr int kPage = 16;           // tokens per page
+constexpr int kWaves = 4;           // waves per workgroup of the split pass
+constexpr int kTileTokens = 32;     // tokens one wave consumes per iteration (two pages)
+constexpr int kMaxGroup = 16;       // query heads per KV head that fit one MFMA tile
+
+// Arguments of the split-K pass (by value, lives in kernel-argument memory).
+struct SplitArgs {
+    const uint16_t *q;           // [B][Hq][D] bf16
+    const void *k_pages;         // [num_pages][Hkv][16][D]
+    const void *v_pages;
+    const float *k_scales;       // [num_pages][Hkv] (fp8) or null
+    const float *v_scales;
+    const int32_t *block_table;  // [B][max_blocks]
+    const int32_t *context_lens; // [B]
+    float *ws_m;                 // [B][Hq][S]   running max, log2 domain
+    float *ws_l;                 // [B][Hq][S]   sum of weights
+    float *ws_acc;               // [B][Hq][S][D] weighted V sum
+    float scale_log2e;           // scale * log2(e)
+    int32_t B, Hq, Hkv, G;
+    int32_t max_blocks, S, chunk_tokens, max_context_len;
+};
+
+struct MergeArgs {
+    const float *ws_m, *ws_l, *ws_acc;
+    const int32_t *context_lens;
+    float *out;                  // [B][Hq][D]
+    int32_t B, Hq, S, chunk_tokens, max_context_len;
+};
+
+struct AppendArgs {
+    const uint4 *k_new, *v_new;  // [T][Hkv][D] bf16 viewed as 16-byte words
+    const int32_t *seq_ids, *positions;
+    uint4 *k_pages, *v_pages;
+    const int32_t *block_table;
+    int32_t T, Hkv, max_blocks;
+};
+
+struct ProbeArgs {
+    const void *k_pages, *v_pages;
+    const int32_t *block_table, *context_lens;
+    uint32_t *sink;
+    int32_t B, Hkv, max_blocks, S, chunk_tokens, max_context_len;
+    int32_t tile_bytes;          // bytes of one (page, head) tile: 16 * D * elem
+};
+
+// Launchers: enqueue on `stream`, return the hipError_t of the launch.
+hipError_t launch_split(const SplitArgs &a, int head_dim, int kv_dtype, hipStream_t stream);
+hipError_t launch_merge(const MergeArgs &a, int head_dim, hipStream_t stream);
+hipError_t launch_append(const AppendArgs &a, int head_dim, hipStream_t stream);
+hipError_t launch_probe(const ProbeArgs &a, hipStream_t stream);
+
+}  // namespace sd

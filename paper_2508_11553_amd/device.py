@@ -1,0 +1,73 @@
+"""Device-side holder for one decode workload: uploads host arrays into torch
+tensors once, sizes the workspace, and forwards to the C ABI.  No arithmetic
+happens here; torch is used for device memory and streams only.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as sd
+
+
+def _to_dev(a: np.ndarray, device) -> torch.Tensor:
+    """numpy -> device tensor with the same bytes (uint16 travels as int16)."""
+    if a.dtype == np.uint16:
+        a = a.view(np.int16)
+    return torch.from_numpy(np.ascontiguousarray(a)).to(device, non_blocking=False)
+
+
+class DeviceWorkload:
+    """Anything with the fields of workloads.Workload can be uploaded."""
+
+    def __init__(self, wl, device="cuda:0", chunk_tokens: int = 0, upload_pools: bool = True):
+        self.wl = wl
+        self.device = torch.device(device)
+        self.shape = sd.Shape(
+            batch=wl.batch, num_q_heads=wl.num_q_heads, num_kv_heads=wl.num_kv_heads, head_dim=wl.head_dim,
+            page_size=wl.page_size, num_pages=wl.num_pages, max_blocks_per_seq=wl.max_blocks_per_seq,
+            kv_dtype=sd.SD_FP8_E4M3 if wl.kv_dtype == "fp8" else sd.SD_BF16,
+            max_context_len=wl.max_context_len, chunk_tokens=chunk_tokens)
+        self.scale = float(wl.scale)
+        self.q = _to_dev(wl.q, self.device)
+        self.block_table = _to_dev(wl.block_table, self.device)
+        self.context_lens = _to_dev(wl.context_lens, self.device)
+        self.k_pages = self.v_pages = self.k_scales = self.v_scales = None
+        if upload_pools:
+            self.set_pool(wl.k_pages, wl.v_pages, wl.k_scales, wl.v_scales)
+        self.k_new = self.v_new = self.seq_ids = self.positions = None
+        self.T = 0
+        if getattr(wl, "k_new", None) is not None:
+            self.k_new, self.v_new = _to_dev(wl.k_new, self.device), _to_dev(wl.v_new, self.device)
+            self.seq_ids, self.positions = _to_dev(wl.seq_ids, self.device), _to_dev(wl.positions, self.device)
+            self.T = int(wl.k_new.shape[0])
+        self.out = torch.empty((wl.batch, wl.num_q_heads, wl.head_dim), dtype=torch.float32, device=self.device)
+        self.ws_bytes = sd.workspace_bytes(self.shape)
+        self.workspace = torch.empty(max(self.ws_bytes, 256), dtype=torch.uint8, device=self.device)
+
+    def set_pool(self, k_pages, v_pages, k_scales=None, v_scales=None):
+        """Upload (numpy) or adopt (torch) a K/V pool."""
+        up = lambda a: a if a is None or isinstance(a, torch.Tensor) else _to_dev(a, self.device)
+        self.k_pages, self.v_pages = up(k_pages), up(v_pages)
+        self.k_scales, self.v_scales = up(k_scales), up(v_scales)
+
+    def chunk_tokens(self) -> int:
+        return sd.chunk_tokens(self.shape)
+
+    def append(self, stream=None):
+        sd.kv_append(self.shape, self.k_new, self.v_new, self.seq_ids, self.positions, self.T,
+                     self.k_pages, self.v_pages, self.block_table, stream)
+
+    def attend(self, stream=None, timer=None, out=None):
+        out = self.out if out is None else out
+        sd.paged_decode_attention(self.shape, self.q, self.k_pages, self.v_pages, self.k_scales, self.v_scales,
+                                  self.block_table, self.context_lens, self.scale, out, self.workspace,
+                                  self.ws_bytes, stream, timer)
+        return out
+
+    def pools_to_host(self):
+        """Pool bytes back as numpy arrays of the workload's dtype."""
+        k, v = self.k_pages.cpu().numpy(), self.v_pages.cpu().numpy()
+        if k.dtype == np.int16:
+            k, v = k.view(np.uint16), v.view(np.uint16)
+        return k, v

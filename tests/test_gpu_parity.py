@@ -1,0 +1,272 @@
+"""Parity of the HIP path against the CPU oracle, through the C ABI (GPU only).
+
+Tolerances for bf16 inputs with fp32 accumulation: max abs error <= 1e-2 and
+mean abs error <= 1e-3 against the fp64 oracle.  Outputs are O(0.05) at these
+lengths, so anything above the alarm level below is treated as a bug even
+though it would pass.  Integer/byte work (kv_append) is compared bit for bit.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, MEAN_ABS = 1e-2, 1e-3
+# Softmax weights are rounded to bf16 (relative error 2^-9 each) before the
+# weighted sum, so a row's error scales with the size of its output: O(1) for
+# a handful of tokens, O(0.05) for thousands.  The alarm follows that.
+ALARM_ABS, ALARM_REL = 3e-4, 2.0 ** -8
+
+
+@pytest.fixture(scope="module")
+def sd():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_2508_11553_amd as m
+    m.load()
+    return m
+
+
+def device_workload(wl, **kw):
+    from paper_2508_11553_amd.device import DeviceWorkload
+    return DeviceWorkload(wl, **kw)
+
+
+def gpu_attend(wl, **kw):
+    import torch
+    dw = device_workload(wl, **kw)
+    out = dw.attend()
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def oracle_full(wl, k_pages=None, v_pages=None):
+    return oracle.paged_decode_attention(wl.q, wl.k_pages if k_pages is None else k_pages,
+                                         wl.v_pages if v_pages is None else v_pages, wl.block_table,
+                                         wl.context_lens, wl.scale, wl.k_scales, wl.v_scales, wl.kv_dtype)
+
+
+def check(got, ref, max_abs=MAX_ABS, mean_abs=MEAN_ABS):
+    assert not np.isnan(got).any(), "NaN in the GPU output"
+    err = np.abs(got.astype(np.float64) - ref)
+    assert err.max() <= max_abs and err.mean() <= mean_abs, (err.max(), err.mean())
+    alarm = ALARM_ABS + ALARM_REL * np.abs(ref).max(axis=-1, keepdims=True)
+    worst = (err / alarm).max()
+    assert worst <= 1.0, f"passes the stated tolerance but is suspiciously large: {worst:.2f} x the alarm level"
+
+
+def test_config0_tiny_paged_decode(sd):
+    wl = workloads.make_config(0)
+    check(gpu_attend(wl), oracle_full(wl))
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("Hq,Hkv", [(1, 1), (4, 1), (8, 2), (28, 4), (16, 2), (32, 2)])
+def test_group_sizes_and_head_dims(sd, Hq, Hkv, d):
+    lens = [1, 2, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 300, 511, 512, 513, 1025]
+    wl = workloads.make_custom(lens, Hq, Hkv, d, seed=100 + Hq + d)
+    check(gpu_attend(wl), oracle_full(wl))
+
+
+@pytest.mark.parametrize("chunk", [128, 256, 512, 1024])
+def test_chunk_sizes_and_ragged_tails(sd, chunk):
+    lens = [chunk - 1, chunk, chunk + 1, 3 * chunk + 7, 2 * chunk, 5, 2 * chunk + 16, 2 * chunk + 17]
+    wl = workloads.make_custom(lens, 8, 2, 128, seed=200 + chunk)
+    check(gpu_attend(wl, chunk_tokens=chunk), oracle_full(wl))
+
+
+def test_results_do_not_depend_on_chunk_beyond_rounding(sd):
+    wl = workloads.make_custom([700, 1500, 64, 4000], 28, 4, 128, seed=7)
+    a, b = gpu_attend(wl, chunk_tokens=128), gpu_attend(wl, chunk_tokens=1024)
+    # different chunkings round the bf16 weights against different running maxima
+    assert np.abs(a - b).max() <= ALARM_ABS + ALARM_REL * np.abs(a).max()
+
+
+def test_two_runs_are_bitwise_equal(sd):
+    wl = workloads.make_custom([700, 1500, 64, 4000], 28, 4, 128, seed=8)
+    assert np.array_equal(gpu_attend(wl), gpu_attend(wl))
+
+
+def test_zero_length_sequences_give_zero_rows(sd):
+    wl = workloads.make_custom([0, 40, 0, 513], 8, 2, 64, seed=9)
+    got = gpu_attend(wl)
+    assert np.array_equal(got[0], np.zeros_like(got[0])) and np.array_equal(got[2], np.zeros_like(got[2]))
+    check(got, oracle_full(wl))
+
+
+def test_length_one_returns_v_row_bit_exact(sd):
+    wl = workloads.make_custom([1, 1, 1, 1, 1], 8, 2, 128, seed=10)
+    got = gpu_attend(wl)
+    V = workloads.bf16_bits_to_f32(wl.v_pages)
+    for b in range(5):
+        for h in range(8):
+            assert np.array_equal(got[b, h], V[wl.block_table[b, 0], h // 4, 0])
+
+
+def test_constant_v_returns_the_constant(sd):
+    wl = workloads.make_custom([1, 5, 33, 200, 1300], 8, 2, 64, seed=11)
+    c = workloads.f32_to_bf16_bits(np.float32([0.37]))[0]
+    keep = wl.v_pages == workloads.BF16_NAN_BITS  # leave the poison where it is
+    wl.v_pages[~keep] = c
+    got = gpu_attend(wl)
+    assert np.abs(got - workloads.bf16_bits_to_f32(np.uint16([c]))[0]).max() <= 1e-6
+
+
+def test_poisoned_slots_and_table_entries_are_never_read(sd):
+    a = workloads.make_custom([3, 47, 130, 512, 529], 8, 2, 128, seed=12, poison=True)
+    c = workloads.make_custom([3, 47, 130, 512, 529], 8, 2, 128, seed=12, poison=False)
+    ga, gc = gpu_attend(a), gpu_attend(c)
+    assert not np.isnan(ga).any() and np.array_equal(ga, gc)
+
+
+def test_permuting_physical_pages_changes_no_bit(sd):
+    lens = [100, 31, 257, 1100]
+    a = workloads.make_custom(lens, 8, 2, 64, seed=13, permute=True)
+    c = workloads.make_custom(lens, 8, 2, 64, seed=13, permute=False)
+    # same logical content?  The generator draws pools in physical order, so rebuild c's pool from a's.
+    k = np.empty_like(c.k_pages); v = np.empty_like(c.v_pages)
+    k[:] = workloads.BF16_NAN_BITS; v[:] = workloads.BF16_NAN_BITS
+    for b, L in enumerate(lens):
+        for j in range((L + 15) // 16):
+            k[c.block_table[b, j]] = a.k_pages[a.block_table[b, j]]
+            v[c.block_table[b, j]] = a.v_pages[a.block_table[b, j]]
+    c.k_pages, c.v_pages, c.q = k, v, a.q
+    assert np.array_equal(gpu_attend(a), gpu_attend(c))
+
+
+def test_shared_prefix_pages_equal_private_copies(sd):
+    lens = np.array([300, 277, 811, 290])
+    wl = workloads.make_custom(lens, 8, 2, 128, seed=14, session_of=[0, 0, 0, 1], prefix_len=[200, 200, 200, 96])
+    shared = gpu_attend(wl)
+    nbs = (lens + 15) // 16
+    table = np.full_like(wl.block_table, -1)
+    nxt = 0
+    for b in range(4):
+        table[b, :nbs[b]] = np.arange(nxt, nxt + nbs[b]); nxt += nbs[b]
+    k = np.zeros((nxt,) + wl.k_pages.shape[1:], wl.k_pages.dtype); v = k.copy()
+    for b in range(4):
+        k[table[b, :nbs[b]]] = wl.k_pages[wl.block_table[b, :nbs[b]]]
+        v[table[b, :nbs[b]]] = wl.v_pages[wl.block_table[b, :nbs[b]]]
+    ref = oracle_full(wl)
+    wl.k_pages, wl.v_pages, wl.block_table, wl.num_pages = k, v, table, nxt
+    private = gpu_attend(wl)
+    assert np.array_equal(shared, private)
+    check(shared, ref)
+
+
+def test_kv_append_is_bit_exact_and_append_then_attend_matches(sd):
+    import torch
+    wl = workloads.make_custom([20, 33, 512, 513, 1, 16, 17], 8, 2, 128, seed=15, append=True)
+    dw = device_workload(wl)
+    dw.append()
+    out = dw.attend()
+    torch.cuda.synchronize()
+    k_gpu, v_gpu = dw.pools_to_host()
+    k_ref, v_ref = wl.k_pages.copy(), wl.v_pages.copy()
+    oracle.kv_append(wl.k_new, wl.v_new, wl.seq_ids, wl.positions, k_ref, v_ref, wl.block_table)
+    assert np.array_equal(k_gpu, k_ref) and np.array_equal(v_gpu, v_ref)
+    check(out.cpu().numpy(), oracle_full(wl, k_ref, v_ref))
+
+
+def test_pool_built_token_by_token_with_kv_append(sd):
+    """Resume: rebuild a paused sequence's cache from its stored rows, then attend."""
+    import torch
+    from paper_2508_11553_amd import binding
+    wl = workloads.make_custom([37, 5, 64], 4, 2, 64, seed=16, poison=False)
+    dw = device_workload(wl)
+    ref = dw.attend().clone()
+    # every valid token as one append row, in one bulk call, into an empty pool
+    rows_k, rows_v, seqs, poss = [], [], [], []
+    for b, L in enumerate(wl.context_lens):
+        for t in range(L):
+            p, s = wl.block_table[b, t // 16], t % 16
+            rows_k.append(wl.k_pages[p, :, s]); rows_v.append(wl.v_pages[p, :, s]); seqs.append(b); poss.append(t)
+    from paper_2508_11553_amd.device import _to_dev
+    kn, vn = _to_dev(np.stack(rows_k), dw.device), _to_dev(np.stack(rows_v), dw.device)
+    si, po = _to_dev(np.int32(seqs), dw.device), _to_dev(np.int32(poss), dw.device)
+    dw.k_pages.zero_(); dw.v_pages.zero_()
+    binding.kv_append(dw.shape, kn, vn, si, po, len(seqs), dw.k_pages, dw.v_pages, dw.block_table)
+    out = dw.attend()
+    torch.cuda.synchronize()
+    assert torch.equal(out, ref)
+
+
+def test_workspace_too_small_and_bad_arguments_on_device(sd):
+    import ctypes
+    wl = workloads.make_custom([40], 8, 2, 64, seed=17)
+    dw = device_workload(wl)
+    with pytest.raises(sd.SeamDecodeError) as e:
+        sd.paged_decode_attention(dw.shape, dw.q, dw.k_pages, dw.v_pages, None, None, dw.block_table,
+                                  dw.context_lens, dw.scale, dw.out, dw.workspace, dw.ws_bytes - 1)
+    assert e.value.code == -3
+    with pytest.raises(sd.SeamDecodeError) as e:
+        sd.paged_decode_attention(dw.shape, dw.q, dw.k_pages, None, None, None, dw.block_table,
+                                  dw.context_lens, dw.scale, dw.out, dw.workspace, dw.ws_bytes)
+    assert e.value.code == -1
+
+
+def test_runs_on_a_side_stream(sd):
+    import torch
+    wl = workloads.make_custom([700, 64], 8, 2, 128, seed=18)
+    dw = device_workload(wl)
+    ref = dw.attend().clone()
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    out2 = torch.zeros_like(ref)
+    with torch.cuda.stream(s):
+        dw.attend(stream=s, out=out2)
+    s.synchronize()
+    assert torch.equal(out2, ref)
+
+
+def test_kernel_timer_reports_both_kernels(sd):
+    wl = workloads.make_custom([700, 64], 8, 2, 128, seed=19)
+    dw = device_workload(wl)
+    t = sd.KernelTimer(4)
+    for _ in range(3):
+        dw.attend(timer=t)
+    split, merge = t.read()
+    assert len(split) == 3 and all(x > 0 for x in split) and all(x > 0 for x in merge)
+    t.close()
+
+
+# ---------------------------------------------------------------- full-size configurations
+def sampled_rows(wl, n, seed=0):
+    """Deterministic sample of (b, h) rows: shortest, longest, and random ones."""
+    rng = np.random.default_rng(seed)
+    lens = wl.context_lens
+    rows = {(int(np.argmin(lens)), 0), (int(np.argmax(lens)), wl.num_q_heads - 1)}
+    while len(rows) < n:
+        rows.add((int(rng.integers(wl.batch)), int(rng.integers(wl.num_q_heads))))
+    return np.int32(sorted(rows))
+
+
+@pytest.mark.parametrize("cfg", [1, 2])
+def test_full_size_config_sampled_rows(sd, cfg):
+    wl = workloads.make_config(cfg)
+    got = gpu_attend(wl)
+    assert not np.isnan(got).any()
+    rows = sampled_rows(wl, 96)
+    ref = oracle.attend_rows(wl.q, wl.k_pages, wl.v_pages, wl.block_table, wl.context_lens, wl.scale, rows)
+    check(got[rows[:, 0], rows[:, 1]], ref)
+
+
+def test_full_size_branching_mix_with_append(sd):
+    import torch
+    wl = workloads.make_config(3)
+    dw = device_workload(wl)
+    dw.append()
+    out = dw.attend()
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    k_ref, v_ref = wl.k_pages, wl.v_pages  # append in place on the host copy
+    oracle.kv_append(wl.k_new, wl.v_new, wl.seq_ids, wl.positions, k_ref, v_ref, wl.block_table)
+    k_gpu, v_gpu = dw.pools_to_host()
+    assert np.array_equal(k_gpu, k_ref) and np.array_equal(v_gpu, v_ref)
+    rows = sampled_rows(wl, 96)
+    ref = oracle.attend_rows(wl.q, k_ref, v_ref, wl.block_table, wl.context_lens, wl.scale, rows)
+    check(got[rows[:, 0], rows[:, 1]], ref)
+    # branches of a session see the same prefix: rows of all 256 sequences are finite and bounded by max|V|
+    assert np.abs(got).max() <= 6.0
