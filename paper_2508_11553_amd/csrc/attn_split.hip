@@ -11,10 +11,11 @@
 //
 // Computing the transposed products makes the accumulator layout of the first
 // MFMA (lane = head, registers = tokens) exactly the B-operand layout of the
-// second one, so the weights never leave their lanes.  K rows are loaded
-// straight into A-operand layout (lane = token, 16 bytes along d).  V rows
-// are loaded as 8-byte pieces (16 lanes cover 128 contiguous bytes of a row)
-// and transposed 4x4 inside each lane with byte permutes, because the second
+// second one, so the weights never leave their lanes.  K tiles are loaded as
+// a plain memory image (16 bytes per lane, fully coalesced) and turned into
+// A-operand layout (lane = token) through a per-wave LDS scratch.  V rows are
+// loaded as 8-byte pieces (16 lanes cover 128 contiguous bytes of a row) and
+// transposed 4x4 inside each lane with byte permutes, because the second
 // product contracts over tokens while memory is contiguous along d.
 //
 // The four waves' (max, sum, O) are merged through LDS and written as one
@@ -55,22 +56,38 @@ SD_DEV unsigned cvt_pk_bf16(float lo, float hi)
 template <typename T>
 SD_DEV T stream_load(const T *p) { return __builtin_nontemporal_load(p); }
 
-SD_DEV float xor_max(float x, int mask) { return fmaxf(x, __shfl_xor(x, mask, 64)); }
-SD_DEV float xor_add(float x, int mask) { return x + __shfl_xor(x, mask, 64); }
+// Reductions over the four lanes {n, n+16, n+32, n+48} that share a head.
+// v_permlane16_swap exchanges rows 1<->0' and 3<->2' of its two operands and
+// v_permlane32_swap the upper half of one with the lower half of the other;
+// fed the same value twice they return (x, x from the partner row/half).
+SD_DEV float head_max(float x)
+{
+    const unsigned u = __builtin_bit_cast(unsigned, x);
+    const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    const float y = fmaxf(__builtin_bit_cast(float, a[0]), __builtin_bit_cast(float, a[1]));
+    const unsigned w = __builtin_bit_cast(unsigned, y);
+    const auto b = __builtin_amdgcn_permlane32_swap(w, w, false, false);
+    return fmaxf(__builtin_bit_cast(float, b[0]), __builtin_bit_cast(float, b[1]));
+}
+SD_DEV float head_sum(float x)
+{
+    x += __shfl_xor(x, 16, 64);
+    return x + __shfl_xor(x, 32, 64);
+}
 
 // Registers of one 32-token tile as they arrive from memory.
 template <int D>
 struct Tile {
-    u32x4 k[2][D / 32];     // [page][step]: K row (lane&15), d = 32*step + 8*(lane>>4) .. +8
+    u32x4 k[2][D / 32];     // [page][j]: 16 bytes at byte offset 1024*j + 16*lane of the K tile
     u32x2 v[2][D / 64][4];  // [page][half][j]: V row 4*(lane>>4)+j, d = 64*half + 4*(lane&15) .. +4
 };
 
 template <int D>
 SD_DEV void load_page_bf16(Tile<D> &r, int pg, const char *kp, const char *vp, int lane)
 {
-    const char *kl = kp + (lane & 15) * (D * 2) + (lane >> 4) * 16;
+    const char *kl = kp + lane * 16;
 #pragma unroll
-    for (int s = 0; s < D / 32; ++s) r.k[pg][s] = stream_load(reinterpret_cast<const u32x4 *>(kl + s * 64));
+    for (int j = 0; j < D / 32; ++j) r.k[pg][j] = stream_load(reinterpret_cast<const u32x4 *>(kl + j * 1024));
     const char *vl = vp + (lane >> 4) * 4 * (D * 2) + (lane & 15) * 8;
 #pragma unroll
     for (int h = 0; h < D / 64; ++h)
@@ -80,34 +97,64 @@ SD_DEV void load_page_bf16(Tile<D> &r, int pg, const char *kp, const char *vp, i
 }
 
 template <int D>
-SD_DEV void zero_page(Tile<D> &r, int pg)
-{
-#pragma unroll
-    for (int s = 0; s < D / 32; ++s) r.k[pg][s] = u32x4{0, 0, 0, 0};
-#pragma unroll
-    for (int h = 0; h < D / 64; ++h)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) r.v[pg][h][j] = u32x2{0, 0};
-}
-
-template <int D>
 struct WaveState {
     float m;                 // running max of this lane's head (same in the 4 lanes of a head)
     float l;                 // this lane's share of the weight sum
     f32x4 acc[D / 64][4];    // acc[h][i][r] = O[head lane&15][d = 64h + 16(lane>>4) + 4r + i]
 };
 
+// K tiles arrive as a plain image of memory (lane = 16 consecutive bytes), the
+// only pattern in which a wave's load touches each cache line once.  The MFMA
+// wants lane = token, so each K tile takes a round trip through this wave's
+// own LDS scratch: written as it lies in memory, read back row-per-lane.
+// 16-byte pieces of row r are stored at piece index (c ^ r) so that both the
+// writes (16 lanes = one row) and the reads (16 lanes = one piece column of 16
+// rows) spread over all banks.  Only the owning wave touches its scratch and
+// LDS operations of one wave execute in order, so no barrier is needed; the
+// fences keep the compiler from moving reads above writes.
+template <int D>
+SD_DEV void k_tile_to_operands(const Tile<D> &r, char *scratch, int lane, u32x4 (&ka)[D / 32], u32x4 (&kb)[D / 32])
+{
+    constexpr int kPieces = D / 8;            // 16-byte pieces per K row
+    constexpr int kRowsPerLoad = 64 / kPieces;  // rows one 1024-byte load covers
+    constexpr int kTile = kPage * D * 2;      // bytes of one (page, head) K tile
+#pragma unroll
+    for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+        for (int j = 0; j < D / 32; ++j) {
+            const int row = j * kRowsPerLoad + lane / kPieces;
+            const int piece = (lane % kPieces) ^ (row % kPieces);
+            *reinterpret_cast<u32x4 *>(scratch + pg * kTile + row * (D * 2) + piece * 16) = r.k[pg][j];
+        }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const int t = lane & 15, kg = lane >> 4;
+#pragma unroll
+    for (int s = 0; s < D / 32; ++s) {
+        const int piece = (4 * s + kg) ^ (t % kPieces);
+        ka[s] = *reinterpret_cast<const u32x4 *>(scratch + t * (D * 2) + piece * 16);
+        kb[s] = *reinterpret_cast<const u32x4 *>(scratch + kTile + t * (D * 2) + piece * 16);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 // One 32-token tile: tokens tok0 .. tok0+31, of which those < t_end are real.
 template <int D>
 SD_DEV void consume_tile(Tile<D> &r, const u32x4 (&qop)[D / 32], WaveState<D> &st,
-                         float scale_log2e, int tok0, int t_end, int lane)
+                         float scale_log2e, int tok0, int t_end, int lane, char *scratch)
 {
     const int qd = lane >> 4;
     f32x4 sa = {0, 0, 0, 0}, sb = {0, 0, 0, 0};
+    {
+        u32x4 ka[D / 32], kb[D / 32];  // K row (lane&15), d = 32*s + 8*(lane>>4) .. +8
+        k_tile_to_operands<D>(r, scratch, lane, ka, kb);
 #pragma unroll
-    for (int s = 0; s < D / 32; ++s) {
-        sa = mfma_bf16_k32(r.k[0][s], qop[s], sa);
-        sb = mfma_bf16_k32(r.k[1][s], qop[s], sb);
+        for (int s = 0; s < D / 32; ++s) {
+            sa = mfma_bf16_k32(ka[s], qop[s], sa);
+            sb = mfma_bf16_k32(kb[s], qop[s], sb);
+        }
     }
     // lane holds, for head lane&15, tokens tok0 + 4qd + e (page A) and tok0 + 16 + 4qd + e (page B)
     float x[8];
@@ -125,7 +172,7 @@ SD_DEV void consume_tile(Tile<D> &r, const u32x4 (&qop)[D / 32], WaveState<D> &s
         }
     }
     float tmax = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-    tmax = xor_max(xor_max(tmax, 16), 32);
+    tmax = head_max(tmax);
     const float m_new = fmaxf(st.m, tmax);
     const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
     st.m = m_new;
@@ -187,6 +234,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void split_bf16_kernel(SplitArgs a)
 {
     constexpr int kRow = D + 4;  // padded LDS row: 16 heads x float4 stores hit 64 distinct banks
     __shared__ __attribute__((aligned(16))) float s_acc[kWaves][kMaxGroup][kRow];
+    __shared__ __attribute__((aligned(16))) char s_k[kWaves][2 * kPage * D * 2];  // per-wave K transposition scratch
     __shared__ float s_m[kWaves][kMaxGroup];
     __shared__ float s_l[kWaves][kMaxGroup];
 
@@ -228,35 +276,51 @@ __global__ __launch_bounds__(kWaves * 64, 2) void split_bf16_kernel(SplitArgs a)
     const char *kbase = static_cast<const char *>(a.k_pages) + g * tile_bytes;
     const char *vbase = static_cast<const char *>(a.v_pages) + g * tile_bytes;
 
-    auto fetch = [&](Tile<D> &r, int ti) {
-        const int tok0 = t0 + ti * kTileTokens;
-        const int64_t pa = bt[2 * ti];
-        load_page_bf16<D>(r, 0, kbase + pa * page_bytes, vbase + pa * page_bytes, lane);
-        if (tok0 + kPage < t1) {  // wave-uniform: the tile's second page exists
-            const int64_t pb = bt[2 * ti + 1];
-            load_page_bf16<D>(r, 1, kbase + pb * page_bytes, vbase + pb * page_bytes, lane);
-        } else {
-            zero_page<D>(r, 1);
-        }
+    // This wave's tiles are wave, wave+4, ... : nt of them.  Loads for tile i+1 are
+    // issued before tile i is consumed, and the page ids of tile i+2 are fetched
+    // (scalar loads) one step earlier still.  Everything inside the loop is
+    // unconditional so that the wait counters stay exact; a tile's missing
+    // second page re-reads the first (its tokens are masked by position).
+    const int nt = ntiles > wave ? (ntiles - wave + kWaves - 1) / kWaves : 0;
+    const int last_page = (t1 - t0 + kPage - 1) / kPage - 1;
+    auto page_ids = [&](int i, int &pa, int &pb) {
+        const int ti = wave + kWaves * min(i, nt - 1);
+        pa = bt[2 * ti];
+        pb = bt[min(2 * ti + 1, last_page)];
     };
-
-    Tile<D> ra, rb;
-    int ti = wave;
-    if (ti < ntiles) fetch(ra, ti);
-    while (ti < ntiles) {
-        int tn = ti + kWaves;
-        if (tn < ntiles) fetch(rb, tn);
-        consume_tile<D>(ra, qop, st, a.scale_log2e, t0 + ti * kTileTokens, t1, lane);
-        ti = tn;
-        if (ti >= ntiles) break;
-        tn = ti + kWaves;
-        if (tn < ntiles) fetch(ra, tn);
-        consume_tile<D>(rb, qop, st, a.scale_log2e, t0 + ti * kTileTokens, t1, lane);
-        ti = tn;
+    auto issue = [&](Tile<D> &r, int pa, int pb) {
+        load_page_bf16<D>(r, 0, kbase + pa * page_bytes, vbase + pa * page_bytes, lane);
+        load_page_bf16<D>(r, 1, kbase + pb * page_bytes, vbase + pb * page_bytes, lane);
+    };
+    auto consume = [&](Tile<D> &r, int i) {
+        consume_tile<D>(r, qop, st, a.scale_log2e, t0 + (wave + kWaves * i) * kTileTokens, t1, lane, s_k[wave]);
+    };
+    if (nt > 0) {
+        Tile<D> ra, rb;
+        int pa, pb;
+        page_ids(0, pa, pb);
+        issue(ra, pa, pb);
+        page_ids(1, pa, pb);
+        int i = 0;
+        for (; i + 2 < nt; i += 2) {
+            issue(rb, pa, pb);
+            page_ids(i + 2, pa, pb);
+            consume(ra, i);
+            issue(ra, pa, pb);
+            page_ids(i + 3, pa, pb);
+            consume(rb, i + 1);
+        }
+        if (i + 1 < nt) {
+            issue(rb, pa, pb);
+            consume(ra, i);
+            consume(rb, i + 1);
+        } else {
+            consume(ra, i);
+        }
     }
 
     // the four lanes of a head hold disjoint shares of the weight sum
-    st.l = xor_add(xor_add(st.l, 16), 32);
+    st.l = head_sum(st.l);
 
     const int qd = lane >> 4;
     if (qd == 0) {
