@@ -143,8 +143,10 @@ int paged_decode_attention(const sd_shape *shape, const void *q,
  * Measurement aids (not part of the decode step).
  *
  * sd_timer owns HIP events (host objects; no device memory).  The _timed
- * variant of the attention call records events around each of its kernels on
- * `stream`; sd_timer_read waits for them and returns per-call kernel times.
+ * variant of the attention call binds a begin and an end event to each of its
+ * two kernel launches on `stream` (the kernels' own start/stop timestamps, so
+ * launch latency is not included); sd_timer_read waits for them and returns
+ * the per-call kernel durations.
  */
 typedef struct sd_timer sd_timer;
 sd_timer *sd_timer_create(int32_t max_calls);

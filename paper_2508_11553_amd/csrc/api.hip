@@ -44,6 +44,17 @@ int check_shape(const sd_shape *s)
 int pick_chunk(const sd_shape *s)
 {
     if (s->chunk_tokens) return s->chunk_tokens;
+    // Longer chunks amortise a workgroup's start-up and its partial write, but
+    // the grid must still hold several workgroups per CU slot (256 CUs x 2).
+    // With few (sequence, kv head) pairs take the longest chunk that leaves
+    // >= 2048 grid entries; with many pairs the pairs alone fill the machine.
+    const int64_t pairs = (int64_t)s->batch * s->num_kv_heads;
+    if (pairs < 1024) {
+        for (int chunk = 4096; chunk >= 1024; chunk /= 2) {
+            const int64_t entries = pairs * ((s->max_context_len + chunk - 1) / chunk);
+            if (entries >= 2048) return chunk;
+        }
+    }
     return 512;
 }
 
@@ -71,7 +82,7 @@ WsLayout ws_layout(const sd_shape *s, int S)
 }  // namespace
 
 struct sd_timer {
-    std::vector<hipEvent_t> ev;  // 3 per call: before split, between, after merge
+    std::vector<hipEvent_t> ev;  // 4 per call: split begin/end, merge begin/end
     int32_t max_calls = 0, calls = 0;
 };
 
@@ -191,17 +202,13 @@ int paged_decode_attention_timed(const sd_shape *shape, const void *q, const voi
     ma.chunk_tokens = chunk;
     ma.max_context_len = shape->max_context_len;
 
-    hipEvent_t *ev = timer ? &timer->ev[(size_t)timer->calls * 3] : nullptr;
+    hipEvent_t none[4] = {nullptr, nullptr, nullptr, nullptr};
+    hipEvent_t *ev = timer ? &timer->ev[(size_t)timer->calls * 4] : none;
     hipError_t e;
-    if (ev && (e = hipEventRecord(ev[0], st)) != hipSuccess) return hip_fail(e);
-    if ((e = sd::launch_split(sa, shape->head_dim, shape->kv_dtype, st)) != hipSuccess)
+    if ((e = sd::launch_split(sa, shape->head_dim, shape->kv_dtype, st, ev[0], ev[1])) != hipSuccess)
         return e == hipErrorNotSupported ? SD_EUNSUPPORTED : hip_fail(e);
-    if (ev && (e = hipEventRecord(ev[1], st)) != hipSuccess) return hip_fail(e);
-    if ((e = sd::launch_merge(ma, shape->head_dim, st)) != hipSuccess) return hip_fail(e);
-    if (ev) {
-        if ((e = hipEventRecord(ev[2], st)) != hipSuccess) return hip_fail(e);
-        timer->calls++;
-    }
+    if ((e = sd::launch_merge(ma, shape->head_dim, st, ev[2], ev[3])) != hipSuccess) return hip_fail(e);
+    if (timer) timer->calls++;
     return SD_OK;
 }
 
@@ -220,7 +227,7 @@ sd_timer *sd_timer_create(int32_t max_calls)
     sd_timer *t = new (std::nothrow) sd_timer;
     if (!t) return nullptr;
     t->max_calls = max_calls;
-    t->ev.resize((size_t)max_calls * 3, nullptr);
+    t->ev.resize((size_t)max_calls * 4, nullptr);
     for (auto &e : t->ev) {
         const hipError_t rc = hipEventCreate(&e);
         if (rc != hipSuccess) {
@@ -250,10 +257,10 @@ int sd_timer_read(sd_timer *t, float *split_ms, float *merge_ms, int32_t cap)
     if (!t || !split_ms || !merge_ms || cap < 0) return SD_EINVAL;
     const int n = t->calls < cap ? t->calls : cap;
     for (int i = 0; i < n; ++i) {
-        hipEvent_t *ev = &t->ev[(size_t)i * 3];
-        hipError_t e = hipEventSynchronize(ev[2]);
+        hipEvent_t *ev = &t->ev[(size_t)i * 4];
+        hipError_t e = hipEventSynchronize(ev[3]);
         if (e == hipSuccess) e = hipEventElapsedTime(&split_ms[i], ev[0], ev[1]);
-        if (e == hipSuccess) e = hipEventElapsedTime(&merge_ms[i], ev[1], ev[2]);
+        if (e == hipSuccess) e = hipEventElapsedTime(&merge_ms[i], ev[2], ev[3]);
         if (e != hipSuccess) return hip_fail(e);
     }
     return n;

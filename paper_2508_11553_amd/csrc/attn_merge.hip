@@ -34,14 +34,14 @@ __global__ __launch_bounds__(D) void merge_kernel(MergeArgs a)
     o[d] = num / den;
 }
 
-hipError_t launch_merge(const MergeArgs &a, int head_dim, hipStream_t stream)
+hipError_t launch_merge(const MergeArgs &a, int head_dim, hipStream_t stream, hipEvent_t start, hipEvent_t stop)
 {
     const unsigned grid = (unsigned)a.B * (unsigned)a.Hq;
     if (grid == 0) return hipSuccess;
     if (head_dim == 128)
-        hipLaunchKernelGGL(merge_kernel<128>, dim3(grid), dim3(128), 0, stream, a);
+        hipExtLaunchKernelGGL(merge_kernel<128>, dim3(grid), dim3(128), 0, stream, start, stop, 0, a);
     else if (head_dim == 64)
-        hipLaunchKernelGGL(merge_kernel<64>, dim3(grid), dim3(64), 0, stream, a);
+        hipExtLaunchKernelGGL(merge_kernel<64>, dim3(grid), dim3(64), 0, stream, start, stop, 0, a);
     else
         return hipErrorNotSupported;
     return hipGetLastError();

@@ -359,15 +359,16 @@ __global__ __launch_bounds__(kWaves * 64, 2) void split_bf16_kernel(SplitArgs a)
     }
 }
 
-hipError_t launch_split(const SplitArgs &a, int head_dim, int kv_dtype, hipStream_t stream)
+hipError_t launch_split(const SplitArgs &a, int head_dim, int kv_dtype, hipStream_t stream,
+                        hipEvent_t start, hipEvent_t stop)
 {
     const unsigned grid = (unsigned)a.S * (unsigned)a.B * (unsigned)a.Hkv;
     if (grid == 0) return hipSuccess;
     if (kv_dtype != 0) return hipErrorNotSupported;
     if (head_dim == 128)
-        hipLaunchKernelGGL(split_bf16_kernel<128>, dim3(grid), dim3(kWaves * 64), 0, stream, a);
+        hipExtLaunchKernelGGL(split_bf16_kernel<128>, dim3(grid), dim3(kWaves * 64), 0, stream, start, stop, 0, a);
     else if (head_dim == 64)
-        hipLaunchKernelGGL(split_bf16_kernel<64>, dim3(grid), dim3(kWaves * 64), 0, stream, a);
+        hipExtLaunchKernelGGL(split_bf16_kernel<64>, dim3(grid), dim3(kWaves * 64), 0, stream, start, stop, 0, a);
     else
         return hipErrorNotSupported;
     return hipGetLastError();

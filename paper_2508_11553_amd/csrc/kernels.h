@@ -2,6 +2,7 @@
 // libseamdecode.  Not installed; the public interface is include/seamdecode.h.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 namespace sd {
@@ -51,9 +52,14 @@ struct ProbeArgs {
     int32_t tile_bytes;          // bytes of one (page, head) tile: 16 * D * elem
 };
 
-// Launchers: enqueue on `stream`, return the hipError_t of the launch.
-hipError_t launch_split(const SplitArgs &a, int head_dim, int kv_dtype, hipStream_t stream);
-hipError_t launch_merge(const MergeArgs &a, int head_dim, hipStream_t stream);
+// Launchers: enqueue on `stream`, return the hipError_t of the launch.  When
+// `start`/`stop` are given they are bound to the kernel's own begin and end
+// timestamps (hipExtLaunchKernelGGL), so their elapsed time is the kernel's
+// duration without launch latency.
+hipError_t launch_split(const SplitArgs &a, int head_dim, int kv_dtype, hipStream_t stream,
+                        hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
+hipError_t launch_merge(const MergeArgs &a, int head_dim, hipStream_t stream,
+                        hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
 hipError_t launch_append(const AppendArgs &a, int head_dim, hipStream_t stream);
 hipError_t launch_probe(const ProbeArgs &a, hipStream_t stream);
 

@@ -1,18 +1,23 @@
 // Read-only probe: walks the block table exactly like the split pass (same
-// grid, same chunking, one workgroup per (chunk, sequence, kv head)) and loads
-// every K and V byte of its chunk with 16-byte non-temporal loads, folding them
-// with XOR.
-// It measures what the memory system delivers for this access pattern: tiles
-// of `tile_bytes` contiguous bytes at random page addresses.
+// grid, same chunking, one workgroup per (chunk, sequence, kv head), each wave
+// taking every fourth 32-token tile, one tile prefetched ahead) and loads
+// every K and V byte of its chunk with coalesced 16-byte non-temporal loads,
+// folding them with XOR.  No arithmetic, no LDS: its duration is what the
+// memory system delivers for this access pattern (tiles of `tile_bytes`
+// contiguous bytes at random page addresses), i.e. the ceiling for the split
+// pass on the machine at hand.
 #include "kernels.h"
 
 namespace sd {
 
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
+template <int NL>  // 1024-byte loads per (page, head) tile and pool
 __global__ __launch_bounds__(kWaves * 64, 2) void probe_kernel(ProbeArgs a)
 {
     const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int item = blockIdx.x;
     const int g = item % a.Hkv;
     const int b = (item / a.Hkv) % a.B;
@@ -21,27 +26,64 @@ __global__ __launch_bounds__(kWaves * 64, 2) void probe_kernel(ProbeArgs a)
     const int t0 = c * a.chunk_tokens;
     if (t0 >= L) return;
     const int t1 = min(L, t0 + a.chunk_tokens);
-    const int npages = (t1 - t0 + kPage - 1) / kPage;
+    const int ntiles = (t1 - t0 + kTileTokens - 1) / kTileTokens;
+    const int last_page = (t1 - t0 + kPage - 1) / kPage - 1;
     const int32_t *bt = a.block_table + (int64_t)b * a.max_blocks + t0 / kPage;
-    const int words = a.tile_bytes / 16;              // 16-byte words per tile (128 or 256 or 64)
-    const int64_t page_words = (int64_t)words * a.Hkv;
-    const u32x4 *k = static_cast<const u32x4 *>(a.k_pages) + (int64_t)g * words;
-    const u32x4 *v = static_cast<const u32x4 *>(a.v_pages) + (int64_t)g * words;
-    // a tile is `words` 16-byte words; 256 threads cover 256/words tiles per step
-    const int per_step = (kWaves * 64) / words;
-    const int sub = tid / words, w = tid % words;
+    const int64_t tile_bytes = a.tile_bytes;
+    const int64_t page_bytes = tile_bytes * a.Hkv;
+    const char *k = static_cast<const char *>(a.k_pages) + g * tile_bytes + lane * 16;
+    const char *v = static_cast<const char *>(a.v_pages) + g * tile_bytes + lane * 16;
+
+    struct Tile {
+        u32x4 w[2][2][NL];  // [page][K or V][load]
+    };
+    const int nt = ntiles > wave ? (ntiles - wave + kWaves - 1) / kWaves : 0;
+    auto page_ids = [&](int i, int &pa, int &pb) {
+        const int ti = wave + kWaves * min(i, nt - 1);
+        pa = bt[2 * ti];
+        pb = bt[min(2 * ti + 1, last_page)];
+    };
+    auto issue = [&](Tile &r, int pa, int pb) {
+#pragma unroll
+        for (int j = 0; j < NL; ++j) {
+            r.w[0][0][j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(k + pa * page_bytes + j * 1024));
+            r.w[0][1][j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(v + pa * page_bytes + j * 1024));
+            r.w[1][0][j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(k + pb * page_bytes + j * 1024));
+            r.w[1][1][j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(v + pb * page_bytes + j * 1024));
+        }
+    };
     u32x4 acc = {0, 0, 0, 0};
-#pragma unroll 4
-    for (int p = sub; p < npages; p += per_step) {
-        const int64_t page = bt[p];
-        const u32x4 x = __builtin_nontemporal_load(k + page * page_words + w);
-        const u32x4 y = __builtin_nontemporal_load(v + page * page_words + w);
-        acc ^= x ^ y;
+    auto consume = [&](const Tile &r) {
+#pragma unroll
+        for (int j = 0; j < NL; ++j) acc ^= r.w[0][0][j] ^ r.w[0][1][j] ^ r.w[1][0][j] ^ r.w[1][1][j];
+    };
+    if (nt > 0) {
+        Tile ra, rb;
+        int pa, pb;
+        page_ids(0, pa, pb);
+        issue(ra, pa, pb);
+        page_ids(1, pa, pb);
+        int i = 0;
+        for (; i + 2 < nt; i += 2) {
+            issue(rb, pa, pb);
+            page_ids(i + 2, pa, pb);
+            consume(ra);
+            issue(ra, pa, pb);
+            page_ids(i + 3, pa, pb);
+            consume(rb);
+        }
+        if (i + 1 < nt) {
+            issue(rb, pa, pb);
+            consume(ra);
+            consume(rb);
+        } else {
+            consume(ra);
+        }
     }
     unsigned f = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
     for (int off = 32; off > 0; off >>= 1) f ^= __shfl_xor(f, off, 64);
     __shared__ unsigned s[kWaves];
-    if ((tid & 63) == 0) s[tid >> 6] = f;
+    if (lane == 0) s[wave] = f;
     __syncthreads();
     if (tid == 0) a.sink[item] = s[0] ^ s[1] ^ s[2] ^ s[3];
 }
@@ -50,7 +92,12 @@ hipError_t launch_probe(const ProbeArgs &a, hipStream_t stream)
 {
     const unsigned grid = (unsigned)a.S * (unsigned)a.B * (unsigned)a.Hkv;
     if (grid == 0) return hipSuccess;
-    hipLaunchKernelGGL(probe_kernel, dim3(grid), dim3(kWaves * 64), 0, stream, a);
+    switch (a.tile_bytes) {
+    case 4096: hipLaunchKernelGGL(probe_kernel<4>, dim3(grid), dim3(kWaves * 64), 0, stream, a); break;
+    case 2048: hipLaunchKernelGGL(probe_kernel<2>, dim3(grid), dim3(kWaves * 64), 0, stream, a); break;
+    case 1024: hipLaunchKernelGGL(probe_kernel<1>, dim3(grid), dim3(kWaves * 64), 0, stream, a); break;
+    default: return hipErrorNotSupported;
+    }
     return hipGetLastError();
 }
 
