@@ -62,7 +62,7 @@ typedef struct {
     int32_t batch;              /* B >= 0 (0: the call is a no-op) */
     int32_t num_q_heads;        /* Hq */
     int32_t num_kv_heads;       /* Hkv; Hq % Hkv == 0 and Hq / Hkv <= 16 */
-    int32_t head_dim;           /* 64 or 128 */
+    int32_t head_dim;           /* 64 or 128 (fp8 pools: 128 only) */
     int32_t page_size;          /* must be 16 */
     int32_t num_pages;          /* extent of the pools */
     int32_t max_blocks_per_seq; /* row stride of block_table */

@@ -35,6 +35,7 @@ int check_shape(const sd_shape *s)
         (s->chunk_tokens < 128 || s->chunk_tokens > 65536 || s->chunk_tokens % 128 != 0))
         return SD_EINVAL;
     if (s->head_dim != 64 && s->head_dim != 128) return SD_EUNSUPPORTED;
+    if (s->kv_dtype == SD_FP8_E4M3 && s->head_dim != 128) return SD_EUNSUPPORTED;
     if (s->num_q_heads / s->num_kv_heads > sd::kMaxGroup) return SD_EUNSUPPORTED;
     return SD_OK;
 }
@@ -44,18 +45,25 @@ int check_shape(const sd_shape *s)
 int pick_chunk(const sd_shape *s)
 {
     if (s->chunk_tokens) return s->chunk_tokens;
-    // Longer chunks amortise a workgroup's start-up and its partial write, but
-    // the grid must still hold several workgroups per CU slot (256 CUs x 2).
-    // With few (sequence, kv head) pairs take the longest chunk that leaves
-    // >= 2048 grid entries; with many pairs the pairs alone fill the machine.
+    // A chunk costs one partial per query head (written, then read by the merge
+    // pass): about 2 * G / (chunk * elem_bytes) of the chunk's K/V bytes.  Keep
+    // that near 1 %: chunk * elem_bytes >= 200 * G.
+    const int G = s->num_q_heads / s->num_kv_heads;
+    const int elem = s->kv_dtype == SD_BF16 ? 2 : 1;
+    int base = 512;
+    while (base * elem < 200 * G && base < 4096) base *= 2;
+    // Longer chunks also amortise a workgroup's start-up, but the grid must
+    // still hold several workgroups per CU slot (256 CUs x 2).  With few
+    // (sequence, kv head) pairs take the longest chunk that leaves >= 2048 grid
+    // entries; with many pairs the pairs alone fill the machine.
     const int64_t pairs = (int64_t)s->batch * s->num_kv_heads;
     if (pairs < 1024) {
-        for (int chunk = 4096; chunk >= 1024; chunk /= 2) {
+        for (int chunk = 4096; chunk > base; chunk /= 2) {
             const int64_t entries = pairs * ((s->max_context_len + chunk - 1) / chunk);
             if (entries >= 2048) return chunk;
         }
     }
-    return 512;
+    return base;
 }
 
 int num_chunks(const sd_shape *s, int chunk)

@@ -14,9 +14,14 @@
 // second one, so the weights never leave their lanes.  K tiles are loaded as
 // a plain memory image (16 bytes per lane, fully coalesced) and turned into
 // A-operand layout (lane = token) through a per-wave LDS scratch.  V rows are
-// loaded as 8-byte pieces (16 lanes cover 128 contiguous bytes of a row) and
-// transposed 4x4 inside each lane with byte permutes, because the second
-// product contracts over tokens while memory is contiguous along d.
+// loaded in pieces of which 16 lanes cover 128 contiguous bytes of a row, and
+// the token-major operand is formed inside each lane (byte permutes for bf16,
+// the fp8->bf16 conversion itself for fp8), because the second product
+// contracts over tokens while memory is contiguous along d.
+//
+// fp8 pools (OCP e4m3fn codes with one fp32 scale per page and head) are
+// converted to bf16 in registers, which is exact; the K scale multiplies the
+// page's scores and the V scale multiplies the page's weights.
 //
 // The four waves' (max, sum, O) are merged through LDS and written as one
 // partial per (b, head, chunk); the merge kernel finishes the softmax.
@@ -25,7 +30,9 @@
 namespace sd {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
@@ -44,11 +51,19 @@ SD_DEV unsigned pack_hi(unsigned x, unsigned y) { return __builtin_amdgcn_perm(y
 // two floats -> packed bf16 pair, round-to-nearest-even (v_cvt_pk_bf16_f32)
 SD_DEV unsigned cvt_pk_bf16(float lo, float hi)
 {
-    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
     bf16x2 r;
     r[0] = (__bf16)lo;
     r[1] = (__bf16)hi;
     return __builtin_bit_cast(unsigned, r);
+}
+
+// two e4m3fn codes (one 16-bit half of w) -> packed bf16 pair, exact.  The
+// instruction applies only the power-of-two part of its scale operand; 1.0
+// leaves the values as they are.
+template <bool HI>
+SD_DEV unsigned cvt_pk_bf16_fp8(unsigned w)
+{
+    return __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, HI));
 }
 
 // K/V bytes are used once per launch: load them with the non-temporal hint so
@@ -75,96 +90,31 @@ SD_DEV float head_sum(float x)
     return x + __shfl_xor(x, 32, 64);
 }
 
-// Registers of one 32-token tile as they arrive from memory.
-template <int D>
-struct Tile {
-    u32x4 k[2][D / 32];     // [page][j]: 16 bytes at byte offset 1024*j + 16*lane of the K tile
-    u32x2 v[2][D / 64][4];  // [page][half][j]: V row 4*(lane>>4)+j, d = 64*half + 4*(lane&15) .. +4
-};
-
-template <int D>
-SD_DEV void load_page_bf16(Tile<D> &r, int pg, const char *kp, const char *vp, int lane)
+// Keeps the compiler from moving this wave's LDS reads above its LDS writes
+// (and the other way round).  Only the owning wave touches its scratch and the
+// LDS operations of one wave execute in order, so no workgroup barrier is needed.
+SD_DEV void wave_lds_fence()
 {
-    const char *kl = kp + lane * 16;
-#pragma unroll
-    for (int j = 0; j < D / 32; ++j) r.k[pg][j] = stream_load(reinterpret_cast<const u32x4 *>(kl + j * 1024));
-    const char *vl = vp + (lane >> 4) * 4 * (D * 2) + (lane & 15) * 8;
-#pragma unroll
-    for (int h = 0; h < D / 64; ++h)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            r.v[pg][h][j] = stream_load(reinterpret_cast<const u32x2 *>(vl + j * (D * 2) + h * 128));
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 template <int D>
 struct WaveState {
-    float m;                 // running max of this lane's head (same in the 4 lanes of a head)
-    float l;                 // this lane's share of the weight sum
-    f32x4 acc[D / 64][4];    // acc[h][i][r] = O[head lane&15][d = 64h + 16(lane>>4) + 4r + i]
+    float m;             // running max of this lane's head (same in the 4 lanes of a head)
+    float l;             // this lane's share of the weight sum
+    f32x4 acc[D / 16];   // O^T accumulators; which d each one holds is the path's business
 };
 
-// K tiles arrive as a plain image of memory (lane = 16 consecutive bytes), the
-// only pattern in which a wave's load touches each cache line once.  The MFMA
-// wants lane = token, so each K tile takes a round trip through this wave's
-// own LDS scratch: written as it lies in memory, read back row-per-lane.
-// 16-byte pieces of row r are stored at piece index (c ^ r) so that both the
-// writes (16 lanes = one row) and the reads (16 lanes = one piece column of 16
-// rows) spread over all banks.  Only the owning wave touches its scratch and
-// LDS operations of one wave execute in order, so no barrier is needed; the
-// fences keep the compiler from moving reads above writes.
+// Scores of one tile -> weights.  x holds, for head lane&15, the scaled scores
+// of tokens tok0 + 4qd + e (e < 4, first page) and tok0 + 16 + 4qd + e - 4
+// (second page).  Updates the running max and rescales the accumulators when
+// some head's max moved.  Returns exp2(x - m) in p.
 template <int D>
-SD_DEV void k_tile_to_operands(const Tile<D> &r, char *scratch, int lane, u32x4 (&ka)[D / 32], u32x4 (&kb)[D / 32])
+SD_DEV void online_softmax(float (&x)[8], float (&p)[8], WaveState<D> &st, bool ragged, int tok0, int t_end, int qd)
 {
-    constexpr int kPieces = D / 8;            // 16-byte pieces per K row
-    constexpr int kRowsPerLoad = 64 / kPieces;  // rows one 1024-byte load covers
-    constexpr int kTile = kPage * D * 2;      // bytes of one (page, head) K tile
-#pragma unroll
-    for (int pg = 0; pg < 2; ++pg)
-#pragma unroll
-        for (int j = 0; j < D / 32; ++j) {
-            const int row = j * kRowsPerLoad + lane / kPieces;
-            const int piece = (lane % kPieces) ^ (row % kPieces);
-            *reinterpret_cast<u32x4 *>(scratch + pg * kTile + row * (D * 2) + piece * 16) = r.k[pg][j];
-        }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    const int t = lane & 15, kg = lane >> 4;
-#pragma unroll
-    for (int s = 0; s < D / 32; ++s) {
-        const int piece = (4 * s + kg) ^ (t % kPieces);
-        ka[s] = *reinterpret_cast<const u32x4 *>(scratch + t * (D * 2) + piece * 16);
-        kb[s] = *reinterpret_cast<const u32x4 *>(scratch + kTile + t * (D * 2) + piece * 16);
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-}
-
-// One 32-token tile: tokens tok0 .. tok0+31, of which those < t_end are real.
-template <int D>
-SD_DEV void consume_tile(Tile<D> &r, const u32x4 (&qop)[D / 32], WaveState<D> &st,
-                         float scale_log2e, int tok0, int t_end, int lane, char *scratch)
-{
-    const int qd = lane >> 4;
-    f32x4 sa = {0, 0, 0, 0}, sb = {0, 0, 0, 0};
-    {
-        u32x4 ka[D / 32], kb[D / 32];  // K row (lane&15), d = 32*s + 8*(lane>>4) .. +8
-        k_tile_to_operands<D>(r, scratch, lane, ka, kb);
-#pragma unroll
-        for (int s = 0; s < D / 32; ++s) {
-            sa = mfma_bf16_k32(ka[s], qop[s], sa);
-            sb = mfma_bf16_k32(kb[s], qop[s], sb);
-        }
-    }
-    // lane holds, for head lane&15, tokens tok0 + 4qd + e (page A) and tok0 + 16 + 4qd + e (page B)
-    float x[8];
-    const bool ragged = tok0 + kTileTokens > t_end;  // wave-uniform
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        x[e] = sa[e] * scale_log2e;
-        x[4 + e] = sb[e] * scale_log2e;
-    }
-    if (ragged) {
+    if (ragged) {  // mask by position, never by content
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             if (tok0 + 4 * qd + e >= t_end) x[e] = -INFINITY;
@@ -176,65 +126,299 @@ SD_DEV void consume_tile(Tile<D> &r, const u32x4 (&qop)[D / 32], WaveState<D> &s
     const float m_new = fmaxf(st.m, tmax);
     const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
     st.m = m_new;
-    unsigned pw[4];
-    float psum = 0.f;
 #pragma unroll
-    for (int e = 0; e < 8; e += 2) {
-        const float p0 = __builtin_amdgcn_exp2f(x[e] - m_new);
-        const float p1 = __builtin_amdgcn_exp2f(x[e + 1] - m_new);
-        const unsigned w = cvt_pk_bf16(p0, p1);
-        pw[e >> 1] = w;
-        // the sum runs over the rounded weights, the ones the product below uses
-        psum += __builtin_bit_cast(float, w << 16) + __builtin_bit_cast(float, w & 0xffff0000u);
-    }
-    st.l = st.l * alpha + psum;
+    for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(x[e] - m_new);
+    st.l *= alpha;
     if (__builtin_amdgcn_ballot_w64(alpha != 1.0f)) {
 #pragma unroll
-        for (int h = 0; h < D / 64; ++h)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) st.acc[h][i] *= alpha;
-    }
-    const u32x4 pop = {pw[0], pw[1], pw[2], pw[3]};
-
-    auto &v = r.v;
-    if (ragged) {  // slots past the end may hold anything, NaN included: 0 * NaN must not happen
-#pragma unroll
-        for (int pg = 0; pg < 2; ++pg)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if (tok0 + 16 * pg + 4 * qd + j >= t_end) {
-#pragma unroll
-                    for (int h = 0; h < D / 64; ++h) v[pg][h][j] = u32x2{0, 0};
-                }
-    }
-#pragma unroll
-    for (int h = 0; h < D / 64; ++h) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int w = i >> 1;
-            u32x4 a;
-            if (i & 1) {
-                a[0] = pack_hi(v[0][h][0][w], v[0][h][1][w]);
-                a[1] = pack_hi(v[0][h][2][w], v[0][h][3][w]);
-                a[2] = pack_hi(v[1][h][0][w], v[1][h][1][w]);
-                a[3] = pack_hi(v[1][h][2][w], v[1][h][3][w]);
-            } else {
-                a[0] = pack_lo(v[0][h][0][w], v[0][h][1][w]);
-                a[1] = pack_lo(v[0][h][2][w], v[0][h][3][w]);
-                a[2] = pack_lo(v[1][h][0][w], v[1][h][1][w]);
-                a[3] = pack_lo(v[1][h][2][w], v[1][h][3][w]);
-            }
-            st.acc[h][i] = mfma_bf16_k32(a, pop, st.acc[h][i]);
-        }
+        for (int i = 0; i < D / 16; ++i) st.acc[i] *= alpha;
     }
 }
 
+// ---------------------------------------------------------------------------
+// bf16 pools
+// ---------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(kWaves * 64, 2) void split_bf16_kernel(SplitArgs a)
+struct Bf16Path {
+    static constexpr int kDim = D;
+    static constexpr int kTileBytes = kPage * D * 2;     // one (page, head) tile
+    static constexpr int kScratchBytes = 2 * kTileBytes;  // K transposition scratch per wave
+    static constexpr int kPieces = D / 8;                 // 16-byte pieces per K row
+    static constexpr int kRowsPerLoad = 64 / kPieces;     // K rows one 1024-byte load covers
+
+    struct Tile {
+        u32x4 k[2][D / 32];     // [page][j]: 16 bytes at byte offset 1024*j + 16*lane of the K tile
+        u32x2 v[2][D / 64][4];  // [page][half][j]: V row 4*(lane>>4)+j, d = 64*half + 4*(lane&15) .. +4
+    };
+
+    // Q^T operand of step s: head lane&15, d = 32*s + 8*(lane>>4) .. +8
+    SD_DEV static int q_offset(int s, int lane) { return 32 * s + 8 * (lane >> 4); }
+
+    SD_DEV static void load_page(Tile &r, int pg, const char *kp, const char *vp, const float *, const float *, int64_t, int lane)
+    {
+        const char *kl = kp + lane * 16;
+#pragma unroll
+        for (int j = 0; j < D / 32; ++j) r.k[pg][j] = stream_load(reinterpret_cast<const u32x4 *>(kl + j * 1024));
+        const char *vl = vp + (lane >> 4) * 4 * (D * 2) + (lane & 15) * 8;
+#pragma unroll
+        for (int h = 0; h < D / 64; ++h)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                r.v[pg][h][j] = stream_load(reinterpret_cast<const u32x2 *>(vl + j * (D * 2) + h * 128));
+    }
+
+    // K tiles through the wave's LDS scratch: written as they lie in memory,
+    // read back one row per lane.  Piece c of row r sits at piece index c ^ r so
+    // that the writes (16 lanes = one row) and the reads (16 lanes = one piece
+    // column over 16 rows) both spread over all banks.
+    SD_DEV static void k_operands(const Tile &r, char *scratch, int lane, u32x4 (&ka)[D / 32], u32x4 (&kb)[D / 32])
+    {
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+            for (int j = 0; j < D / 32; ++j) {
+                const int row = j * kRowsPerLoad + lane / kPieces;
+                const int piece = (lane % kPieces) ^ (row % kPieces);
+                *reinterpret_cast<u32x4 *>(scratch + pg * kTileBytes + row * (D * 2) + piece * 16) = r.k[pg][j];
+            }
+        wave_lds_fence();
+        const int t = lane & 15, kg = lane >> 4;
+#pragma unroll
+        for (int s = 0; s < D / 32; ++s) {
+            const int piece = (4 * s + kg) ^ (t % kPieces);
+            ka[s] = *reinterpret_cast<const u32x4 *>(scratch + t * (D * 2) + piece * 16);
+            kb[s] = *reinterpret_cast<const u32x4 *>(scratch + kTileBytes + t * (D * 2) + piece * 16);
+        }
+        wave_lds_fence();
+    }
+
+    // One 32-token tile: tokens tok0 .. tok0+31, of which those < t_end are real.
+    SD_DEV static void consume(Tile &r, const u32x4 (&qop)[D / 32], WaveState<D> &st, float scale_log2e,
+                               int tok0, int t_end, int lane, char *scratch)
+    {
+        const int qd = lane >> 4;
+        f32x4 sa = {0, 0, 0, 0}, sb = {0, 0, 0, 0};
+        {
+            u32x4 ka[D / 32], kb[D / 32];  // K row (lane&15), d = 32*s + 8*(lane>>4) .. +8
+            k_operands(r, scratch, lane, ka, kb);
+#pragma unroll
+            for (int s = 0; s < D / 32; ++s) {
+                sa = mfma_bf16_k32(ka[s], qop[s], sa);
+                sb = mfma_bf16_k32(kb[s], qop[s], sb);
+            }
+        }
+        const bool ragged = tok0 + kTileTokens > t_end;  // wave-uniform
+        float x[8], p[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            x[e] = sa[e] * scale_log2e;
+            x[4 + e] = sb[e] * scale_log2e;
+        }
+        online_softmax<D>(x, p, st, ragged, tok0, t_end, qd);
+        u32x4 pop;
+        float psum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+            const unsigned w = cvt_pk_bf16(p[e], p[e + 1]);
+            pop[e >> 1] = w;
+            // the sum runs over the rounded weights, the ones the product below uses
+            psum += __builtin_bit_cast(float, w << 16) + __builtin_bit_cast(float, w & 0xffff0000u);
+        }
+        st.l += psum;
+
+        auto &v = r.v;
+        if (ragged) {  // slots past the end may hold anything, NaN included: 0 * NaN must not happen
+#pragma unroll
+            for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (tok0 + 16 * pg + 4 * qd + j >= t_end) {
+#pragma unroll
+                        for (int h = 0; h < D / 64; ++h) v[pg][h][j] = u32x2{0, 0};
+                    }
+        }
+        // acc[4h + i][r] = O[head lane&15][d = 64h + 16qd + 4r + i]
+#pragma unroll
+        for (int h = 0; h < D / 64; ++h) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int w = i >> 1;
+                u32x4 a;
+                if (i & 1) {
+                    a[0] = pack_hi(v[0][h][0][w], v[0][h][1][w]);
+                    a[1] = pack_hi(v[0][h][2][w], v[0][h][3][w]);
+                    a[2] = pack_hi(v[1][h][0][w], v[1][h][1][w]);
+                    a[3] = pack_hi(v[1][h][2][w], v[1][h][3][w]);
+                } else {
+                    a[0] = pack_lo(v[0][h][0][w], v[0][h][1][w]);
+                    a[1] = pack_lo(v[0][h][2][w], v[0][h][3][w]);
+                    a[2] = pack_lo(v[1][h][0][w], v[1][h][1][w]);
+                    a[3] = pack_lo(v[1][h][2][w], v[1][h][3][w]);
+                }
+                st.acc[4 * h + i] = mfma_bf16_k32(a, pop, st.acc[4 * h + i]);
+            }
+        }
+    }
+
+    // this lane's accumulators -> row `dst` ([D] floats) of its head
+    SD_DEV static void store_acc(const WaveState<D> &st, float *dst, int qd)
+    {
+#pragma unroll
+        for (int h = 0; h < D / 64; ++h)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const f32x4 o = {st.acc[4 * h][r], st.acc[4 * h + 1][r], st.acc[4 * h + 2][r], st.acc[4 * h + 3][r]};
+                *reinterpret_cast<f32x4 *>(dst + 64 * h + 16 * qd + 4 * r) = o;
+            }
+    }
+};
+
+// ---------------------------------------------------------------------------
+// fp8 e4m3fn pools, head_dim 128: rows of 128 bytes, tiles of 2 KB
+// ---------------------------------------------------------------------------
+struct Fp8Path {
+    static constexpr int D = 128;
+    static constexpr int kDim = D;
+    static constexpr int kTileBytes = kPage * D;
+    static constexpr int kScratchBytes = 2 * kTileBytes;
+
+    struct Tile {
+        u32x4 k[2][2];  // [page][j]: 16 bytes at byte offset 1024*j + 16*lane of the K tile
+        u32x2 v[2][4];  // [page][j]: V row 4*(lane>>4)+j, d = 8*(lane&15) .. +8
+        float ks[2], vs[2];
+    };
+
+    // Step s of the first product uses the 8 codes at d = 16*(kg + 4*(s>>1)) + 8*(s&1)
+    // of the lane's K row (kg = lane>>4): each lane converts two 16-byte pieces.
+    SD_DEV static int q_offset(int s, int lane) { return 16 * ((lane >> 4) + 4 * (s >> 1)) + 8 * (s & 1); }
+
+    SD_DEV static void load_page(Tile &r, int pg, const char *kp, const char *vp, const float *ks, const float *vs, int64_t si, int lane)
+    {
+        const char *kl = kp + lane * 16;
+        r.k[pg][0] = stream_load(reinterpret_cast<const u32x4 *>(kl));
+        r.k[pg][1] = stream_load(reinterpret_cast<const u32x4 *>(kl + 1024));
+        const char *vl = vp + (lane >> 4) * 4 * D + (lane & 15) * 8;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) r.v[pg][j] = stream_load(reinterpret_cast<const u32x2 *>(vl + j * D));
+        r.ks[pg] = ks[si];
+        r.vs[pg] = vs[si];
+    }
+
+    // Rows are 128 bytes = 8 pieces; piece c of row r sits at c ^ (r >> 1), and
+    // odd rows start half a bank cycle later, so 16 lanes never share a bank.
+    SD_DEV static void k_operands(const Tile &r, char *scratch, int lane, u32x4 (&ka)[4], u32x4 (&kb)[4])
+    {
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int row = 8 * j + (lane >> 3);
+                const int piece = (lane & 7) ^ ((row >> 1) & 7);
+                *reinterpret_cast<u32x4 *>(scratch + pg * kTileBytes + row * D + piece * 16) = r.k[pg][j];
+            }
+        wave_lds_fence();
+        const int t = lane & 15, kg = lane >> 4;
+        u32x4 raw[2][2];
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+                const int piece = (kg + 4 * hh) ^ ((t >> 1) & 7);
+                raw[pg][hh] = *reinterpret_cast<const u32x4 *>(scratch + pg * kTileBytes + t * D + piece * 16);
+            }
+        wave_lds_fence();
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int hh = s >> 1, lo = 2 * (s & 1);
+            ka[s] = u32x4{cvt_pk_bf16_fp8<false>(raw[0][hh][lo]), cvt_pk_bf16_fp8<true>(raw[0][hh][lo]),
+                          cvt_pk_bf16_fp8<false>(raw[0][hh][lo + 1]), cvt_pk_bf16_fp8<true>(raw[0][hh][lo + 1])};
+            kb[s] = u32x4{cvt_pk_bf16_fp8<false>(raw[1][hh][lo]), cvt_pk_bf16_fp8<true>(raw[1][hh][lo]),
+                          cvt_pk_bf16_fp8<false>(raw[1][hh][lo + 1]), cvt_pk_bf16_fp8<true>(raw[1][hh][lo + 1])};
+        }
+    }
+
+    SD_DEV static void consume(Tile &r, const u32x4 (&qop)[4], WaveState<D> &st, float scale_log2e,
+                               int tok0, int t_end, int lane, char *scratch)
+    {
+        const int qd = lane >> 4;
+        f32x4 sa = {0, 0, 0, 0}, sb = {0, 0, 0, 0};
+        {
+            u32x4 ka[4], kb[4];
+            k_operands(r, scratch, lane, ka, kb);
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                sa = mfma_bf16_k32(ka[s], qop[s], sa);
+                sb = mfma_bf16_k32(kb[s], qop[s], sb);
+            }
+        }
+        const bool ragged = tok0 + kTileTokens > t_end;
+        const float ca = scale_log2e * r.ks[0], cb = scale_log2e * r.ks[1];
+        float x[8], p[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            x[e] = sa[e] * ca;
+            x[4 + e] = sb[e] * cb;
+        }
+        online_softmax<D>(x, p, st, ragged, tok0, t_end, qd);
+        // the weight sum takes the unscaled weights; the product takes them times the page's V scale
+        st.l += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+        u32x4 pop;
+        pop[0] = cvt_pk_bf16(p[0] * r.vs[0], p[1] * r.vs[0]);
+        pop[1] = cvt_pk_bf16(p[2] * r.vs[0], p[3] * r.vs[0]);
+        pop[2] = cvt_pk_bf16(p[4] * r.vs[1], p[5] * r.vs[1]);
+        pop[3] = cvt_pk_bf16(p[6] * r.vs[1], p[7] * r.vs[1]);
+
+        auto &v = r.v;
+        if (ragged) {
+#pragma unroll
+            for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (tok0 + 16 * pg + 4 * qd + j >= t_end) v[pg][j] = u32x2{0, 0};
+        }
+        // acc[i][r] = O[head lane&15][d = 8*(4qd + r) + i]: codes i, i+1 of four tokens at a time;
+        // converting to f32 and packing two tokens' values per register is the transposition.
+#pragma unroll
+        for (int w = 0; w < 2; ++w) {
+#pragma unroll
+            for (int hi = 0; hi < 2; ++hi) {
+                f32x2 f[2][4];
+#pragma unroll
+                for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        f[pg][j] = hi ? __builtin_amdgcn_cvt_pk_f32_fp8(v[pg][j][w], true)
+                                      : __builtin_amdgcn_cvt_pk_f32_fp8(v[pg][j][w], false);
+#pragma unroll
+                for (int ii = 0; ii < 2; ++ii) {
+                    const int i = 4 * w + 2 * hi + ii;
+                    const u32x4 a = {cvt_pk_bf16(f[0][0][ii], f[0][1][ii]), cvt_pk_bf16(f[0][2][ii], f[0][3][ii]),
+                                     cvt_pk_bf16(f[1][0][ii], f[1][1][ii]), cvt_pk_bf16(f[1][2][ii], f[1][3][ii])};
+                    st.acc[i] = mfma_bf16_k32(a, pop, st.acc[i]);
+                }
+            }
+        }
+    }
+
+    SD_DEV static void store_acc(const WaveState<D> &st, float *dst, int qd)
+    {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const f32x4 lo = {st.acc[0][r], st.acc[1][r], st.acc[2][r], st.acc[3][r]};
+            const f32x4 hi = {st.acc[4][r], st.acc[5][r], st.acc[6][r], st.acc[7][r]};
+            *reinterpret_cast<f32x4 *>(dst + 32 * qd + 8 * r) = lo;
+            *reinterpret_cast<f32x4 *>(dst + 32 * qd + 8 * r + 4) = hi;
+        }
+    }
+};
+
+template <class P>
+__global__ __launch_bounds__(kWaves * 64, 2) void split_kernel(SplitArgs a)
 {
+    constexpr int D = P::kDim;
     constexpr int kRow = D + 4;  // padded LDS row: 16 heads x float4 stores hit 64 distinct banks
     __shared__ __attribute__((aligned(16))) float s_acc[kWaves][kMaxGroup][kRow];
-    __shared__ __attribute__((aligned(16))) char s_k[kWaves][2 * kPage * D * 2];  // per-wave K transposition scratch
+    __shared__ __attribute__((aligned(16))) char s_k[kWaves][P::kScratchBytes];
     __shared__ float s_m[kWaves][kMaxGroup];
     __shared__ float s_l[kWaves][kMaxGroup];
 
@@ -252,29 +436,26 @@ __global__ __launch_bounds__(kWaves * 64, 2) void split_bf16_kernel(SplitArgs a)
     const int t1 = min(L, t0 + a.chunk_tokens);
     const int ntiles = (t1 - t0 + kTileTokens - 1) / kTileTokens;
 
-    // Q^T operand: lane = head n, d = 32*step + 8*(lane>>4) .. +8; heads >= G are zero rows
+    // Q^T operand: lane = head n; heads >= G are zero rows
     const int n = lane & 15;
     u32x4 qop[D / 32];
     {
-        const uint16_t *qrow = a.q + ((int64_t)b * a.Hq + (int64_t)g * a.G + n) * D + (lane >> 4) * 8;
+        const uint16_t *qrow = a.q + ((int64_t)b * a.Hq + (int64_t)g * a.G + n) * D;
 #pragma unroll
         for (int s = 0; s < D / 32; ++s)
-            qop[s] = (n < a.G) ? *reinterpret_cast<const u32x4 *>(qrow + s * 32) : u32x4{0, 0, 0, 0};
+            qop[s] = (n < a.G) ? *reinterpret_cast<const u32x4 *>(qrow + P::q_offset(s, lane)) : u32x4{0, 0, 0, 0};
     }
 
     WaveState<D> st;
     st.m = -INFINITY;
     st.l = 0.f;
 #pragma unroll
-    for (int h = 0; h < D / 64; ++h)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) st.acc[h][i] = f32x4{0, 0, 0, 0};
+    for (int i = 0; i < D / 16; ++i) st.acc[i] = f32x4{0, 0, 0, 0};
 
     const int32_t *bt = a.block_table + (int64_t)b * a.max_blocks + t0 / kPage;
-    const int64_t tile_bytes = (int64_t)kPage * D * 2;
-    const int64_t page_bytes = tile_bytes * a.Hkv;
-    const char *kbase = static_cast<const char *>(a.k_pages) + g * tile_bytes;
-    const char *vbase = static_cast<const char *>(a.v_pages) + g * tile_bytes;
+    const int64_t page_bytes = (int64_t)P::kTileBytes * a.Hkv;
+    const char *kbase = static_cast<const char *>(a.k_pages) + g * P::kTileBytes;
+    const char *vbase = static_cast<const char *>(a.v_pages) + g * P::kTileBytes;
 
     // This wave's tiles are wave, wave+4, ... : nt of them.  Loads for tile i+1 are
     // issued before tile i is consumed, and the page ids of tile i+2 are fetched
@@ -288,15 +469,17 @@ __global__ __launch_bounds__(kWaves * 64, 2) void split_bf16_kernel(SplitArgs a)
         pa = bt[2 * ti];
         pb = bt[min(2 * ti + 1, last_page)];
     };
-    auto issue = [&](Tile<D> &r, int pa, int pb) {
-        load_page_bf16<D>(r, 0, kbase + pa * page_bytes, vbase + pa * page_bytes, lane);
-        load_page_bf16<D>(r, 1, kbase + pb * page_bytes, vbase + pb * page_bytes, lane);
+    auto issue = [&](typename P::Tile &r, int pa, int pb) {
+        P::load_page(r, 0, kbase + pa * page_bytes, vbase + pa * page_bytes, a.k_scales, a.v_scales,
+                     (int64_t)pa * a.Hkv + g, lane);
+        P::load_page(r, 1, kbase + pb * page_bytes, vbase + pb * page_bytes, a.k_scales, a.v_scales,
+                     (int64_t)pb * a.Hkv + g, lane);
     };
-    auto consume = [&](Tile<D> &r, int i) {
-        consume_tile<D>(r, qop, st, a.scale_log2e, t0 + (wave + kWaves * i) * kTileTokens, t1, lane, s_k[wave]);
+    auto consume = [&](typename P::Tile &r, int i) {
+        P::consume(r, qop, st, a.scale_log2e, t0 + (wave + kWaves * i) * kTileTokens, t1, lane, s_k[wave]);
     };
     if (nt > 0) {
-        Tile<D> ra, rb;
+        typename P::Tile ra, rb;
         int pa, pb;
         page_ids(0, pa, pb);
         issue(ra, pa, pb);
@@ -327,13 +510,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void split_bf16_kernel(SplitArgs a)
         s_m[wave][n] = st.m;
         s_l[wave][n] = st.l;
     }
-#pragma unroll
-    for (int h = 0; h < D / 64; ++h)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const f32x4 o = {st.acc[h][0][r], st.acc[h][1][r], st.acc[h][2][r], st.acc[h][3][r]};
-            *reinterpret_cast<f32x4 *>(&s_acc[wave][n][64 * h + 16 * qd + 4 * r]) = o;
-        }
+    P::store_acc(st, &s_acc[wave][n][0], qd);
     __syncthreads();
 
     // merge the four waves; wave 0 always saw at least one token, so the max is finite
@@ -364,11 +541,13 @@ hipError_t launch_split(const SplitArgs &a, int head_dim, int kv_dtype, hipStrea
 {
     const unsigned grid = (unsigned)a.S * (unsigned)a.B * (unsigned)a.Hkv;
     if (grid == 0) return hipSuccess;
-    if (kv_dtype != 0) return hipErrorNotSupported;
-    if (head_dim == 128)
-        hipExtLaunchKernelGGL(split_bf16_kernel<128>, dim3(grid), dim3(kWaves * 64), 0, stream, start, stop, 0, a);
-    else if (head_dim == 64)
-        hipExtLaunchKernelGGL(split_bf16_kernel<64>, dim3(grid), dim3(kWaves * 64), 0, stream, start, stop, 0, a);
+    const dim3 g(grid), b(kWaves * 64);
+    if (kv_dtype == 0 && head_dim == 128)
+        hipExtLaunchKernelGGL(split_kernel<Bf16Path<128>>, g, b, 0, stream, start, stop, 0, a);
+    else if (kv_dtype == 0 && head_dim == 64)
+        hipExtLaunchKernelGGL(split_kernel<Bf16Path<64>>, g, b, 0, stream, start, stop, 0, a);
+    else if (kv_dtype == 1 && head_dim == 128)
+        hipExtLaunchKernelGGL(split_kernel<Fp8Path>, g, b, 0, stream, start, stop, 0, a);
     else
         return hipErrorNotSupported;
     return hipGetLastError();

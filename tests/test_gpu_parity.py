@@ -270,3 +270,90 @@ def test_full_size_branching_mix_with_append(sd):
     check(got[rows[:, 0], rows[:, 1]], ref)
     # branches of a session see the same prefix: rows of all 256 sequences are finite and bounded by max|V|
     assert np.abs(got).max() <= 6.0
+
+
+# ---------------------------------------------------------------- fp8 e4m3fn KV
+# Tolerance for fp8 KV: max abs error <= 5e-2 against the oracle that applies
+# the same dequantisation (code * scale).  The device decodes the codes
+# exactly, so the same alarm as for bf16 applies on top.
+FP8_MAX_ABS = 5e-2
+
+
+def check_fp8(got, ref):
+    assert not np.isnan(got).any()
+    err = np.abs(got.astype(np.float64) - ref)
+    assert err.max() <= FP8_MAX_ABS, err.max()
+    alarm = ALARM_ABS + 2 * ALARM_REL * np.abs(ref).max(axis=-1, keepdims=True)
+    assert (err / alarm).max() <= 1.0, f"suspiciously large: {(err / alarm).max():.2f} x the alarm level"
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(8, 1), (8, 2), (64, 8), (28, 4), (16, 1)])
+def test_fp8_small_shapes(sd, Hq, Hkv):
+    lens = [1, 2, 15, 16, 17, 31, 32, 33, 64, 65, 127, 129, 300, 511, 512, 513, 1025, 2049]
+    wl = workloads.make_custom(lens, Hq, Hkv, 128, "fp8", seed=300 + Hq)
+    check_fp8(gpu_attend(wl), oracle_full(wl))
+
+
+@pytest.mark.parametrize("chunk", [128, 512, 2048])
+def test_fp8_chunk_sizes(sd, chunk):
+    lens = [chunk - 1, chunk, chunk + 1, 3 * chunk + 7, 5, 2 * chunk + 17]
+    wl = workloads.make_custom(lens, 16, 2, 128, "fp8", seed=320 + chunk)
+    check_fp8(gpu_attend(wl, chunk_tokens=chunk), oracle_full(wl))
+
+
+def test_fp8_every_code_decodes_exactly_on_the_device(sd):
+    """Length-1 sequences return their V row: with power-of-two scales the
+    output must equal code * scale bit for bit, for all 254 finite codes.
+    This pins the fp8 flavour (OCP e4m3fn, not fnuz) on the device."""
+    wl = workloads.make_custom([1, 1, 1, 1], 2, 2, 128, "fp8", seed=330, poison=False)
+    codes = np.arange(256, dtype=np.uint8)
+    codes[0x7F] = 0; codes[0xFF] = 0x80  # the two NaN codes
+    for b in range(4):
+        p = wl.block_table[b, 0]
+        wl.v_pages[p, 0, 0, :] = codes[:128] if b % 2 == 0 else codes[128:]
+        wl.v_pages[p, 1, 0, :] = codes[128:] if b % 2 == 0 else codes[:128]
+    wl.v_scales[:] = np.float32(2.0 ** -5); wl.k_scales[:] = np.float32(0.25)
+    got = gpu_attend(wl)
+    table = np.array([oracle.e4m3fn_to_float(int(c)) for c in codes], dtype=np.float32) * np.float32(2.0 ** -5)
+    for b in range(4):
+        lo, hi = (table[:128], table[128:]) if b % 2 == 0 else (table[128:], table[:128])
+        assert np.array_equal(got[b, 0], lo) and np.array_equal(got[b, 1], hi)
+
+
+def test_fp8_k_codes_decode_like_the_oracle(sd):
+    """Two tokens with one-hot queries: the weights are a logistic of the
+    difference of two decoded K codes, for every pair of adjacent codes."""
+    B = 126
+    wl = workloads.make_custom([2] * B, 1, 1, 128, "fp8", seed=331, poison=False)
+    q = np.zeros((B, 1, 128), np.float32); q[:, 0, 5] = 1.0
+    wl.q = workloads.f32_to_bf16_bits(q)
+    wl.scale = 1.0
+    for b in range(B):
+        p = wl.block_table[b, 0]
+        wl.k_pages[p, 0, 0, 5] = b; wl.k_pages[p, 0, 1, 5] = b + 1  # codes 0..126, positive range
+        wl.k_scales[p, 0] = np.float32(2.0 ** -4)
+    check_fp8(gpu_attend(wl), oracle_full(wl))
+
+
+def test_fp8_poison_is_never_read(sd):
+    a = workloads.make_custom([3, 47, 130, 512, 529], 16, 2, 128, "fp8", seed=332, poison=True)
+    c = workloads.make_custom([3, 47, 130, 512, 529], 16, 2, 128, "fp8", seed=332, poison=False)
+    ga, gc = gpu_attend(a), gpu_attend(c)
+    assert not np.isnan(ga).any() and np.array_equal(ga, gc)
+
+
+def test_fp8_head_dim_64_is_reported_unsupported(sd):
+    import ctypes
+    s = sd.Shape(batch=1, num_q_heads=2, num_kv_heads=1, head_dim=64, page_size=16, num_pages=4,
+                 max_blocks_per_seq=2, kv_dtype=sd.SD_FP8_E4M3, max_context_len=32, chunk_tokens=0)
+    assert sd.load().sd_chunk_tokens(ctypes.byref(s)) == -2
+
+
+def test_full_size_fp8_large_batch(sd):
+    wl = workloads.make_config(4)
+    got = gpu_attend(wl)
+    assert not np.isnan(got).any()
+    rows = sampled_rows(wl, 128)
+    ref = oracle.attend_rows(wl.q, wl.k_pages, wl.v_pages, wl.block_table, wl.context_lens, wl.scale, rows,
+                             wl.k_scales, wl.v_scales, "fp8")
+    check_fp8(got[rows[:, 0], rows[:, 1]], ref)

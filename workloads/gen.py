@@ -45,7 +45,7 @@ from .formats import (
 
 PAGE = 16
 _TAG_LENS, _TAG_Q, _TAG_PERM, _TAG_K, _TAG_V, _TAG_APPEND, _TAG_MISC = range(7)
-_CHUNK_PAGES = 2048  # pages drawn per random stream chunk
+_CHUNK_PAGES = 256  # pages drawn per random stream chunk (small enough to stay in cache)
 
 
 def _rng(seed, tag, idx=0):
