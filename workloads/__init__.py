@@ -17,6 +17,7 @@ from .gen import (  # noqa: F401
     Workload,
     CONFIG_NAMES,
     make_config,
+    config_lengths,
     make_custom,
     build_paged,
 )

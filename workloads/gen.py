@@ -290,41 +290,52 @@ CONFIG_NAMES = {
 }
 
 
-def make_config(idx: int, seed: int = 0, append: Optional[bool] = None, threads=None, batch: Optional[int] = None):
-    """The five benchmark workloads.  `batch` (optional) keeps only the first
-    `batch` sequences' lengths, for bounded CPU timing samples and tests."""
+_CONFIG_SHAPES = {  # (Hq, Hkv, d, kv_dtype)
+    0: (8, 2, 64, "bf16"),
+    1: (28, 4, 128, "bf16"),
+    2: (64, 8, 128, "bf16"),
+    3: (32, 8, 128, "bf16"),
+    4: (64, 8, 128, "fp8"),
+}
+
+
+def config_lengths(idx: int, seed: int = 0):
+    """Context lengths of workload `idx` (and, for the branching mix, the
+    session of each sequence and its shared prefix length)."""
     r = _rng(seed, _TAG_LENS)
     if idx == 0:
-        lens = r.integers(1, 512, size=4, endpoint=True)
-        Hq, Hkv, d, dt = 8, 2, 64, "bf16"
-    elif idx == 1:
-        lens = r.integers(1024, 8192, size=64, endpoint=True)
-        Hq, Hkv, d, dt = 28, 4, 128, "bf16"
-    elif idx == 2:
+        return r.integers(1, 512, size=4, endpoint=True), None, None
+    if idx == 1:
+        return r.integers(1024, 8192, size=64, endpoint=True), None, None
+    if idx == 2:
         lens = np.rint(np.exp(r.normal(math.log(16384.0), 1.0, size=32))).astype(np.int64)
-        lens = np.clip(lens, 2048, 65536)
-        Hq, Hkv, d, dt = 64, 8, 128, "bf16"
-    elif idx == 3:
+        return np.clip(lens, 2048, 65536), None, None
+    if idx == 3:
         nsess, nbr = 16, 16
         prefix = r.integers(2048, 16384, size=nsess, endpoint=True)
         suffix = r.integers(64, 4096, size=nsess * nbr, endpoint=True)
         session_of = np.repeat(np.arange(nsess), nbr)
         prefix_len = prefix[session_of]
-        lens = prefix_len + suffix + 1  # +1: the token the append writes
-        if batch is not None:
-            lens, session_of, prefix_len = lens[:batch], session_of[:batch], prefix_len[:batch]
-        return build_paged(CONFIG_NAMES[3], lens, 32, 8, 128, "bf16", seed=seed, session_of=session_of,
-                           prefix_len=prefix_len, append=True if append is None else append, threads=threads)
-    elif idx == 4:
-        lens = r.integers(512, 4096, size=1024, endpoint=True)
-        Hq, Hkv, d, dt = 64, 8, 128, "fp8"
-    else:
-        raise ValueError(f"no config {idx}")
+        return prefix_len + suffix + 1, session_of, prefix_len  # +1: the token the append writes
+    if idx == 4:
+        return r.integers(512, 4096, size=1024, endpoint=True), None, None
+    raise ValueError(f"no config {idx}")
+
+
+def make_config(idx: int, seed: int = 0, append: Optional[bool] = None, threads=None, batch: Optional[int] = None):
+    """The five benchmark workloads.  `batch` (optional) keeps only the first
+    `batch` sequences, for bounded CPU timing samples and tests.  The branching
+    mix stages its one-token append by default; the others on request."""
+    lens, session_of, prefix_len = config_lengths(idx, seed)
     if batch is not None:
         lens = lens[:batch]
+        if session_of is not None:
+            session_of, prefix_len = session_of[:batch], prefix_len[:batch]
+    Hq, Hkv, d, dt = _CONFIG_SHAPES[idx]
     if append is None:
-        append = False
-    return build_paged(CONFIG_NAMES[idx], lens, Hq, Hkv, d, dt, seed=seed, append=append, threads=threads)
+        append = idx == 3
+    return build_paged(CONFIG_NAMES[idx], lens, Hq, Hkv, d, dt, seed=seed, session_of=session_of,
+                       prefix_len=prefix_len, append=append, threads=threads)
 
 
 def make_custom(lens, Hq, Hkv, d, kv_dtype="bf16", seed=0, **kw):
