@@ -27,8 +27,12 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published peak, 8 TB/s
 SMALL_POOL_BYTES = 2 << 30  # rotate pools below this footprint
 
 
-def algorithmic_bytes(wl, chunk, include_append):
+def algorithmic_bytes(wl, chunk, include_append, unique=False):
     """Bytes one step must move if every operand travels exactly once.
+
+    With unique=True pages shared by several sequences count once (what a
+    prefix-aware pass has to read); otherwise once per sequence that attends
+    them (the logical figure).
 
     Split pass (per launch): every attended K and V element once per
     (sequence, kv head) = sum(L) * token_bytes; q; one table entry per logical
@@ -38,7 +42,7 @@ def algorithmic_bytes(wl, chunk, include_append):
     import numpy as np
 
     lens = wl.context_lens.astype(np.int64)
-    kv = int(lens.sum()) * wl.token_bytes
+    kv = (wl.unique_tokens if unique else int(lens.sum())) * wl.token_bytes
     nb = int(((lens + 15) // 16).sum())
     chunks = int(((lens + chunk - 1) // chunk).sum())
     q = wl.batch * wl.num_q_heads * wl.head_dim * 2
@@ -122,6 +126,8 @@ def main():
     ap.add_argument("--pools", type=int, default=0, help="number of rotating K/V pools (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-append", action="store_true")
+    ap.add_argument("--no-prefix", action="store_true",
+                    help="branching workloads: use the plain entry point instead of the shared-prefix aware one")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a device copy of known size (counter calibration for profiler runs)")
     args = ap.parse_args()
@@ -154,14 +160,19 @@ def main():
         pools.append((dw.k_pages, dw.v_pages, dw.k_scales, dw.v_scales))
     t_gen = time.perf_counter() - t_gen
     chunk = dw.chunk_tokens()
-    ab = algorithmic_bytes(wl, chunk, do_append)
+    prefix_aware = wl.group_start is not None and not args.no_prefix
+    ab = algorithmic_bytes(wl, chunk, do_append, unique=prefix_aware)
+    ab_logical = algorithmic_bytes(wl, chunk, do_append, unique=False)
     stream = torch.cuda.current_stream()
 
     def step(i, timer=None):
         dw.set_pool(*pools[i % npools])
         if do_append:
             dw.append(stream)
-        dw.attend(stream, timer)
+        if prefix_aware:
+            dw.attend_prefix(stream, timer)
+        else:
+            dw.attend(stream, timer)
 
     for i in range(args.warmup):
         step(i)
@@ -219,11 +230,12 @@ def main():
             "workload": f"configs[{cfg}] {wl.name}", "batch": wl.batch, "q_heads": wl.num_q_heads,
             "kv_heads": wl.num_kv_heads, "head_dim": wl.head_dim, "page_size": 16, "kv_dtype": wl.kv_dtype,
             "attended_tokens": wl.attended_tokens, "unique_tokens": wl.unique_tokens, "chunk_tokens": chunk,
-            "pools_rotated": npools, "append_rows_per_step": int(wl.k_new.shape[0]) if do_append else 0, "seed": 0,
+            "pools_rotated": npools, "entry_point": "paged_decode_attention_prefix" if prefix_aware else
+            "paged_decode_attention", "append_rows_per_step": int(wl.k_new.shape[0]) if do_append else 0, "seed": 0,
         },
         "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
         "attended_kv_tokens_per_s": wl.attended_tokens / (ms_per_step * 1e-3),
-        "step_bytes": ab,
+        "step_bytes": ab, "logical_GBps": ab_logical["step"] / (ms_per_step * 1e-3) / 1e9,
         "kernel_ms": {"split": split_avg, "merge": merge_avg, "split_p10_p50_p90":
                       [float(np.percentile(split_ms, p)) for p in (10, 50, 90)]},
         "probe": {"ms": probe_ms, "GBps": ab["kv"] / (probe_ms * 1e-3) / 1e9,

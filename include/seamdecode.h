@@ -140,6 +140,46 @@ int paged_decode_attention(const sd_shape *shape, const void *q,
                            void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * paged_decode_attention_prefix -- the same result as paged_decode_attention
+ * for batches in which groups of sequences share the physical pages of a
+ * common prefix.
+ *
+ * One session may branch into several trajectories that continue a common
+ * prefix (Trajectory Manager: a per-session prefix tree built by
+ * longest-prefix matching), so the block-table rows of a group start with the
+ * same physical pages.  This entry point reads such pages from HBM once per
+ * group and KV head instead of once per sequence: the query rows of the
+ * group's sequences are stacked into the dense tiles of the shared chunks.
+ * Tokens past the shared prefix are handled as in paged_decode_attention and
+ * the same merge pass produces `out`.
+ *
+ *   group_start   i32 [num_groups + 1] (device): group j is the sequences
+ *                 group_start[j] .. group_start[j+1]-1; groups need not cover
+ *                 the batch, sequences outside every group need shared_len 0
+ *   shared_len    i32 [batch] (device): tokens (from position 0) whose pages the
+ *                 sequence shares with every sequence of its group; equal within
+ *                 a group, <= context_lens of each member, 0 for ungrouped
+ *                 sequences.  Only whole chunks (sd_chunk_tokens) inside it are
+ *                 read once; the remainder is read per sequence.
+ *   num_groups, max_group_size, max_shared_len: host-known; upper bounds on the
+ *                 group sizes and on shared_len[] (max_shared_len <= max_context_len)
+ *   timer         NULL or an sd_timer (see below)
+ * The caller guarantees that block_table[b][j] is the same for all b of a
+ * group for j < shared_len/16; the library reads the first member's row.
+ * num_groups == 0 makes the call identical to paged_decode_attention.
+ */
+struct sd_timer;
+int paged_decode_attention_prefix(const sd_shape *shape, const void *q,
+                                  const void *k_pages, const void *v_pages,
+                                  const float *k_scales, const float *v_scales,
+                                  const int32_t *block_table, const int32_t *context_lens,
+                                  const int32_t *group_start, const int32_t *shared_len,
+                                  int32_t num_groups, int32_t max_group_size, int32_t max_shared_len,
+                                  float scale, float *out,
+                                  void *workspace, size_t workspace_bytes, void *stream,
+                                  struct sd_timer *timer);
+
+/*
  * Measurement aids (not part of the decode step).
  *
  * sd_timer owns HIP events (host objects; no device memory).  The _timed

@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     lib_path,
     load,
     paged_decode_attention,
+    paged_decode_attention_prefix,
     probe_read,
     strerror,
     version,

@@ -67,6 +67,9 @@ def load():
     L.paged_decode_attention.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, sz, vp]
     L.paged_decode_attention_timed.restype = ctypes.c_int
     L.paged_decode_attention_timed.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, sz, vp, vp]
+    L.paged_decode_attention_prefix.restype = ctypes.c_int
+    L.paged_decode_attention_prefix.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, vp, vp, sz,
+                                                vp, vp]
     L.sd_timer_create.restype = vp
     L.sd_timer_create.argtypes = [i32]
     L.sd_timer_destroy.restype = None
@@ -179,6 +182,18 @@ def paged_decode_attention(shape: Shape, q, k_pages, v_pages, k_scales, v_scales
                                             float(scale), _ptr(out), _ptr(workspace), int(workspace_nbytes),
                                             _stream(stream), timer._h)
     _check(rc, "paged_decode_attention")
+
+
+def paged_decode_attention_prefix(shape: Shape, q, k_pages, v_pages, k_scales, v_scales, block_table, context_lens,
+                                  group_start, shared_len, num_groups: int, max_group_size: int,
+                                  max_shared_len: int, scale: float, out, workspace, workspace_nbytes: int,
+                                  stream=None, timer: Optional[KernelTimer] = None):
+    rc = load().paged_decode_attention_prefix(
+        ctypes.byref(shape), _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(k_scales), _ptr(v_scales), _ptr(block_table),
+        _ptr(context_lens), _ptr(group_start), _ptr(shared_len), int(num_groups), int(max_group_size),
+        int(max_shared_len), float(scale), _ptr(out), _ptr(workspace), int(workspace_nbytes), _stream(stream),
+        timer._h if timer is not None else None)
+    _check(rc, "paged_decode_attention_prefix")
 
 
 def probe_read(shape: Shape, k_pages, v_pages, block_table, context_lens, sink, stream=None):

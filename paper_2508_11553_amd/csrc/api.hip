@@ -154,25 +154,28 @@ int kv_append(const sd_shape *shape, const void *k_new, const void *v_new,
     return e == hipSuccess ? SD_OK : hip_fail(e);
 }
 
-int paged_decode_attention_timed(const sd_shape *shape, const void *q, const void *k_pages,
-                                 const void *v_pages, const float *k_scales, const float *v_scales,
-                                 const int32_t *block_table, const int32_t *context_lens, float scale,
-                                 float *out, void *workspace, size_t workspace_bytes, void *stream,
-                                 sd_timer *timer)
+int paged_decode_attention_prefix(const sd_shape *shape, const void *q, const void *k_pages,
+                                  const void *v_pages, const float *k_scales, const float *v_scales,
+                                  const int32_t *block_table, const int32_t *context_lens,
+                                  const int32_t *group_start, const int32_t *shared_len, int32_t num_groups,
+                                  int32_t max_group_size, int32_t max_shared_len, float scale, float *out,
+                                  void *workspace, size_t workspace_bytes, void *stream, sd_timer *timer)
 {
     const int rc = check_shape(shape);
     if (rc) return rc;
+    if (num_groups < 0 || max_group_size < 0 || max_shared_len < 0 || max_shared_len > shape->max_context_len)
+        return SD_EINVAL;
     if (shape->batch == 0) return SD_OK;
     if (bad_ptr(q) || bad_ptr(k_pages) || bad_ptr(v_pages) || bad_ptr(block_table) || bad_ptr(context_lens) ||
         bad_ptr(out) || bad_ptr(workspace))
         return SD_EINVAL;
     if (shape->kv_dtype == SD_FP8_E4M3 && (bad_ptr(k_scales) || bad_ptr(v_scales))) return SD_EINVAL;
+    if (num_groups > 0 && (bad_ptr(group_start) || bad_ptr(shared_len) || max_group_size < 1)) return SD_EINVAL;
     if (!(scale == scale)) return SD_EINVAL;
     const int chunk = pick_chunk(shape);
     const int S = num_chunks(shape, chunk);
     const WsLayout w = ws_layout(shape, S);
     if (workspace_bytes < w.total) return SD_EWORKSPACE;
-    if ((uint64_t)S * (uint64_t)shape->batch * (uint64_t)shape->num_kv_heads > 0x7fffffffull) return SD_EUNSUPPORTED;
     if (timer && timer->calls >= timer->max_calls) return SD_EINVAL;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -197,6 +200,17 @@ int paged_decode_attention_timed(const sd_shape *shape, const void *q, const voi
     sa.S = S;
     sa.chunk_tokens = chunk;
     sa.max_context_len = shape->max_context_len;
+    // shared-prefix items: whole chunks of each group's shared prefix, 4 waves x (16 / G) sequences per workgroup
+    const int shared_chunks = num_groups > 0 ? max_shared_len / chunk : 0;
+    const int seqs_per_wg = sd::kWaves * (sa.G <= sd::kMaxGroup / 2 ? sd::kMaxGroup / sa.G : 1);
+    sa.group_start = shared_chunks ? group_start : nullptr;
+    sa.shared_len = shared_chunks ? shared_len : nullptr;
+    sa.num_groups = shared_chunks ? num_groups : 0;
+    sa.group_subs = shared_chunks ? (max_group_size + seqs_per_wg - 1) / seqs_per_wg : 0;
+    const uint64_t group_items = (uint64_t)shared_chunks * (uint64_t)sa.num_groups * (uint64_t)sa.group_subs * (uint64_t)sa.Hkv;
+    const uint64_t plain_items = (uint64_t)S * (uint64_t)shape->batch * (uint64_t)shape->num_kv_heads;
+    if (group_items + plain_items > 0x7fffffffull) return SD_EUNSUPPORTED;
+    sa.group_items = (uint32_t)group_items;
 
     sd::MergeArgs ma;
     ma.ws_m = sa.ws_m;
@@ -220,13 +234,25 @@ int paged_decode_attention_timed(const sd_shape *shape, const void *q, const voi
     return SD_OK;
 }
 
+int paged_decode_attention_timed(const sd_shape *shape, const void *q, const void *k_pages,
+                                 const void *v_pages, const float *k_scales, const float *v_scales,
+                                 const int32_t *block_table, const int32_t *context_lens, float scale,
+                                 float *out, void *workspace, size_t workspace_bytes, void *stream,
+                                 sd_timer *timer)
+{
+    return paged_decode_attention_prefix(shape, q, k_pages, v_pages, k_scales, v_scales, block_table,
+                                         context_lens, nullptr, nullptr, 0, 0, 0, scale, out, workspace,
+                                         workspace_bytes, stream, timer);
+}
+
 int paged_decode_attention(const sd_shape *shape, const void *q, const void *k_pages, const void *v_pages,
                            const float *k_scales, const float *v_scales, const int32_t *block_table,
                            const int32_t *context_lens, float scale, float *out, void *workspace,
                            size_t workspace_bytes, void *stream)
 {
-    return paged_decode_attention_timed(shape, q, k_pages, v_pages, k_scales, v_scales, block_table,
-                                        context_lens, scale, out, workspace, workspace_bytes, stream, nullptr);
+    return paged_decode_attention_prefix(shape, q, k_pages, v_pages, k_scales, v_scales, block_table,
+                                         context_lens, nullptr, nullptr, 0, 0, 0, scale, out, workspace,
+                                         workspace_bytes, stream, nullptr);
 }
 
 sd_timer *sd_timer_create(int32_t max_calls)

@@ -66,10 +66,17 @@ SD_DEV unsigned cvt_pk_bf16_fp8(unsigned w)
     return __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, HI));
 }
 
-// K/V bytes are used once per launch: load them with the non-temporal hint so
-// that they stream through the caches instead of displacing each other.
-template <typename T>
-SD_DEV T stream_load(const T *p) { return __builtin_nontemporal_load(p); }
+// K/V bytes that one wave uses once per launch are loaded with the
+// non-temporal hint, so that they stream through the caches instead of
+// displacing each other (STREAM = true).  Bytes that the four waves of a
+// workgroup all read (shared-prefix items) take ordinary loads: the first wave
+// to ask brings a line in and the caches serve the other three.
+template <bool STREAM, typename T>
+SD_DEV T kv_load(const T *p)
+{
+    if (STREAM) return __builtin_nontemporal_load(p);
+    return *p;
+}
 
 // Reductions over the four lanes {n, n+16, n+32, n+48} that share a head.
 // v_permlane16_swap exchanges rows 1<->0' and 3<->2' of its two operands and
@@ -154,17 +161,18 @@ struct Bf16Path {
     // Q^T operand of step s: head lane&15, d = 32*s + 8*(lane>>4) .. +8
     SD_DEV static int q_offset(int s, int lane) { return 32 * s + 8 * (lane >> 4); }
 
+    template <bool STREAM>
     SD_DEV static void load_page(Tile &r, int pg, const char *kp, const char *vp, const float *, const float *, int64_t, int lane)
     {
         const char *kl = kp + lane * 16;
 #pragma unroll
-        for (int j = 0; j < D / 32; ++j) r.k[pg][j] = stream_load(reinterpret_cast<const u32x4 *>(kl + j * 1024));
+        for (int j = 0; j < D / 32; ++j) r.k[pg][j] = kv_load<STREAM>(reinterpret_cast<const u32x4 *>(kl + j * 1024));
         const char *vl = vp + (lane >> 4) * 4 * (D * 2) + (lane & 15) * 8;
 #pragma unroll
         for (int h = 0; h < D / 64; ++h)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                r.v[pg][h][j] = stream_load(reinterpret_cast<const u32x2 *>(vl + j * (D * 2) + h * 128));
+                r.v[pg][h][j] = kv_load<STREAM>(reinterpret_cast<const u32x2 *>(vl + j * (D * 2) + h * 128));
     }
 
     // K tiles through the wave's LDS scratch: written as they lie in memory,
@@ -292,14 +300,15 @@ struct Fp8Path {
     // of the lane's K row (kg = lane>>4): each lane converts two 16-byte pieces.
     SD_DEV static int q_offset(int s, int lane) { return 16 * ((lane >> 4) + 4 * (s >> 1)) + 8 * (s & 1); }
 
+    template <bool STREAM>
     SD_DEV static void load_page(Tile &r, int pg, const char *kp, const char *vp, const float *ks, const float *vs, int64_t si, int lane)
     {
         const char *kl = kp + lane * 16;
-        r.k[pg][0] = stream_load(reinterpret_cast<const u32x4 *>(kl));
-        r.k[pg][1] = stream_load(reinterpret_cast<const u32x4 *>(kl + 1024));
+        r.k[pg][0] = kv_load<STREAM>(reinterpret_cast<const u32x4 *>(kl));
+        r.k[pg][1] = kv_load<STREAM>(reinterpret_cast<const u32x4 *>(kl + 1024));
         const char *vl = vp + (lane >> 4) * 4 * D + (lane & 15) * 8;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) r.v[pg][j] = stream_load(reinterpret_cast<const u32x2 *>(vl + j * D));
+        for (int j = 0; j < 4; ++j) r.v[pg][j] = kv_load<STREAM>(reinterpret_cast<const u32x2 *>(vl + j * D));
         r.ks[pg] = ks[si];
         r.vs[pg] = vs[si];
     }
@@ -412,6 +421,117 @@ struct Fp8Path {
     }
 };
 
+// Streams the tiles first, first+stride, ... of the chunk [t0, t1) through this
+// wave.  Loads for tile i+1 are issued before tile i is consumed, and the page
+// ids of tile i+2 are fetched (scalar loads) one step earlier still.
+// Everything inside the loop is unconditional so that the wait counters stay
+// exact; a tile's missing second page re-reads the first (its tokens are
+// masked by position).  `bt` points at the table entry of the chunk's first page.
+template <class P, bool STREAM>
+SD_DEV void stream_tiles(const SplitArgs &a, const int32_t *bt, int g, int t0, int t1, int first, int stride,
+                         const u32x4 (&qop)[P::kDim / 32], WaveState<P::kDim> &st, char *scratch, int lane)
+{
+    const int ntiles = (t1 - t0 + kTileTokens - 1) / kTileTokens;
+    const int nt = ntiles > first ? (ntiles - first + stride - 1) / stride : 0;
+    if (nt <= 0) return;
+    const int last_page = (t1 - t0 + kPage - 1) / kPage - 1;
+    const int64_t page_bytes = (int64_t)P::kTileBytes * a.Hkv;
+    const char *kbase = static_cast<const char *>(a.k_pages) + g * P::kTileBytes;
+    const char *vbase = static_cast<const char *>(a.v_pages) + g * P::kTileBytes;
+    auto page_ids = [&](int i, int &pa, int &pb) {
+        const int ti = first + stride * min(i, nt - 1);
+        pa = bt[2 * ti];
+        pb = bt[min(2 * ti + 1, last_page)];
+    };
+    auto issue = [&](typename P::Tile &r, int pa, int pb) {
+        P::template load_page<STREAM>(r, 0, kbase + pa * page_bytes, vbase + pa * page_bytes, a.k_scales, a.v_scales,
+                     (int64_t)pa * a.Hkv + g, lane);
+        P::template load_page<STREAM>(r, 1, kbase + pb * page_bytes, vbase + pb * page_bytes, a.k_scales, a.v_scales,
+                     (int64_t)pb * a.Hkv + g, lane);
+    };
+    auto consume = [&](typename P::Tile &r, int i) {
+        P::consume(r, qop, st, a.scale_log2e, t0 + (first + stride * i) * kTileTokens, t1, lane, scratch);
+    };
+    typename P::Tile ra, rb;
+    int pa, pb;
+    page_ids(0, pa, pb);
+    issue(ra, pa, pb);
+    page_ids(1, pa, pb);
+    int i = 0;
+    for (; i + 2 < nt; i += 2) {
+        issue(rb, pa, pb);
+        page_ids(i + 2, pa, pb);
+        consume(ra, i);
+        issue(ra, pa, pb);
+        page_ids(i + 3, pa, pb);
+        consume(rb, i + 1);
+    }
+    if (i + 1 < nt) {
+        issue(rb, pa, pb);
+        consume(ra, i);
+        consume(rb, i + 1);
+    } else {
+        consume(ra, i);
+    }
+}
+
+template <int D>
+SD_DEV void reset(WaveState<D> &st)
+{
+    st.m = -INFINITY;
+    st.l = 0.f;
+#pragma unroll
+    for (int i = 0; i < D / 16; ++i) st.acc[i] = f32x4{0, 0, 0, 0};
+}
+
+// Shared-prefix item: one workgroup owns one (chunk of a group's shared prefix,
+// sub-group of its sequences, KV head).  The pages are the same for every
+// sequence of the group, so each wave takes 16 query rows (16/G sequences x G
+// heads) and walks ALL tiles of the chunk; the four waves read the same bytes
+// at almost the same time, so they reach HBM once.  Every wave writes the
+// partials of its own rows; there is nothing to merge across waves.
+template <class P>
+SD_DEV void group_item(const SplitArgs &a, unsigned item, char *scratch, int lane, int wave)
+{
+    constexpr int D = P::kDim;
+    const int g = item % a.Hkv;
+    const int sub = (item / a.Hkv) % a.group_subs;
+    const int grp = (item / (a.Hkv * a.group_subs)) % a.num_groups;
+    const int c = item / (a.Hkv * a.group_subs * a.num_groups);
+    const int gs = a.group_start[grp], ge = a.group_start[grp + 1];
+    const int spw = a.G <= kMaxGroup / 2 ? kMaxGroup / a.G : 1;  // sequences per wave
+    const int s0 = gs + (sub * kWaves + wave) * spw;              // this wave's first sequence
+    if (s0 >= ge) return;
+    const int shared = min(min(a.shared_len[gs], a.context_lens[gs]), a.max_context_len);
+    const int t0 = c * a.chunk_tokens;
+    if (t0 + a.chunk_tokens > shared) return;  // only whole chunks inside the shared prefix
+    const int t1 = t0 + a.chunk_tokens;
+
+    const int n = lane & 15;
+    const int seq = s0 + n / a.G, head = g * a.G + n % a.G;
+    const bool row_ok = n / a.G < spw && seq < ge;
+    u32x4 qop[D / 32];
+    {
+        const uint16_t *qrow = a.q + ((int64_t)seq * a.Hq + head) * D;
+#pragma unroll
+        for (int s = 0; s < D / 32; ++s)
+            qop[s] = row_ok ? *reinterpret_cast<const u32x4 *>(qrow + P::q_offset(s, lane)) : u32x4{0, 0, 0, 0};
+    }
+    WaveState<D> st;
+    reset(st);
+    const int32_t *bt = a.block_table + (int64_t)gs * a.max_blocks + t0 / kPage;
+    stream_tiles<P, false>(a, bt, g, t0, t1, 0, 1, qop, st, scratch, lane);
+    st.l = head_sum(st.l);
+    if (row_ok) {
+        const int64_t slot = ((int64_t)seq * a.Hq + head) * a.S + c;
+        P::store_acc(st, a.ws_acc + slot * D, lane >> 4);
+        if ((lane >> 4) == 0) {
+            a.ws_m[slot] = st.m;
+            a.ws_l[slot] = st.l;
+        }
+    }
+}
+
 template <class P>
 __global__ __launch_bounds__(kWaves * 64, 2) void split_kernel(SplitArgs a)
 {
@@ -425,7 +545,11 @@ __global__ __launch_bounds__(kWaves * 64, 2) void split_kernel(SplitArgs a)
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int item = blockIdx.x;  // (chunk, sequence, kv head), kv head fastest
+    if (blockIdx.x < a.group_items) {  // shared-prefix items come first in the grid
+        group_item<P>(a, blockIdx.x, s_k[wave], lane, wave);
+        return;
+    }
+    const unsigned item = blockIdx.x - a.group_items;  // (chunk, sequence, kv head), kv head fastest
     const int g = item % a.Hkv;
     const int b = (item / a.Hkv) % a.B;
     const int c = item / (a.Hkv * a.B);
@@ -433,8 +557,9 @@ __global__ __launch_bounds__(kWaves * 64, 2) void split_kernel(SplitArgs a)
     const int L = min(a.context_lens[b], a.max_context_len);
     const int t0 = c * a.chunk_tokens;
     if (t0 >= L) return;
+    // whole chunks inside a shared prefix belong to the shared-prefix items
+    if (a.shared_len && t0 + a.chunk_tokens <= min(a.shared_len[b], L)) return;
     const int t1 = min(L, t0 + a.chunk_tokens);
-    const int ntiles = (t1 - t0 + kTileTokens - 1) / kTileTokens;
 
     // Q^T operand: lane = head n; heads >= G are zero rows
     const int n = lane & 15;
@@ -447,60 +572,9 @@ __global__ __launch_bounds__(kWaves * 64, 2) void split_kernel(SplitArgs a)
     }
 
     WaveState<D> st;
-    st.m = -INFINITY;
-    st.l = 0.f;
-#pragma unroll
-    for (int i = 0; i < D / 16; ++i) st.acc[i] = f32x4{0, 0, 0, 0};
-
+    reset(st);
     const int32_t *bt = a.block_table + (int64_t)b * a.max_blocks + t0 / kPage;
-    const int64_t page_bytes = (int64_t)P::kTileBytes * a.Hkv;
-    const char *kbase = static_cast<const char *>(a.k_pages) + g * P::kTileBytes;
-    const char *vbase = static_cast<const char *>(a.v_pages) + g * P::kTileBytes;
-
-    // This wave's tiles are wave, wave+4, ... : nt of them.  Loads for tile i+1 are
-    // issued before tile i is consumed, and the page ids of tile i+2 are fetched
-    // (scalar loads) one step earlier still.  Everything inside the loop is
-    // unconditional so that the wait counters stay exact; a tile's missing
-    // second page re-reads the first (its tokens are masked by position).
-    const int nt = ntiles > wave ? (ntiles - wave + kWaves - 1) / kWaves : 0;
-    const int last_page = (t1 - t0 + kPage - 1) / kPage - 1;
-    auto page_ids = [&](int i, int &pa, int &pb) {
-        const int ti = wave + kWaves * min(i, nt - 1);
-        pa = bt[2 * ti];
-        pb = bt[min(2 * ti + 1, last_page)];
-    };
-    auto issue = [&](typename P::Tile &r, int pa, int pb) {
-        P::load_page(r, 0, kbase + pa * page_bytes, vbase + pa * page_bytes, a.k_scales, a.v_scales,
-                     (int64_t)pa * a.Hkv + g, lane);
-        P::load_page(r, 1, kbase + pb * page_bytes, vbase + pb * page_bytes, a.k_scales, a.v_scales,
-                     (int64_t)pb * a.Hkv + g, lane);
-    };
-    auto consume = [&](typename P::Tile &r, int i) {
-        P::consume(r, qop, st, a.scale_log2e, t0 + (wave + kWaves * i) * kTileTokens, t1, lane, s_k[wave]);
-    };
-    if (nt > 0) {
-        typename P::Tile ra, rb;
-        int pa, pb;
-        page_ids(0, pa, pb);
-        issue(ra, pa, pb);
-        page_ids(1, pa, pb);
-        int i = 0;
-        for (; i + 2 < nt; i += 2) {
-            issue(rb, pa, pb);
-            page_ids(i + 2, pa, pb);
-            consume(ra, i);
-            issue(ra, pa, pb);
-            page_ids(i + 3, pa, pb);
-            consume(rb, i + 1);
-        }
-        if (i + 1 < nt) {
-            issue(rb, pa, pb);
-            consume(ra, i);
-            consume(rb, i + 1);
-        } else {
-            consume(ra, i);
-        }
-    }
+    stream_tiles<P, true>(a, bt, g, t0, t1, wave, kWaves, qop, st, s_k[wave], lane);
 
     // the four lanes of a head hold disjoint shares of the weight sum
     st.l = head_sum(st.l);
@@ -539,7 +613,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void split_kernel(SplitArgs a)
 hipError_t launch_split(const SplitArgs &a, int head_dim, int kv_dtype, hipStream_t stream,
                         hipEvent_t start, hipEvent_t stop)
 {
-    const unsigned grid = (unsigned)a.S * (unsigned)a.B * (unsigned)a.Hkv;
+    const unsigned grid = a.group_items + (unsigned)a.S * (unsigned)a.B * (unsigned)a.Hkv;
     if (grid == 0) return hipSuccess;
     const dim3 g(grid), b(kWaves * 64);
     if (kv_dtype == 0 && head_dim == 128)

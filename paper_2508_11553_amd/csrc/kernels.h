@@ -27,6 +27,11 @@ struct SplitArgs {
     float scale_log2e;           // scale * log2(e)
     int32_t B, Hq, Hkv, G;
     int32_t max_blocks, S, chunk_tokens, max_context_len;
+    // shared-prefix groups (all zero / null when the call has none)
+    const int32_t *group_start;  // [num_groups + 1] first sequence of each group
+    const int32_t *shared_len;   // [B] tokens whose pages the sequence shares with its whole group
+    int32_t num_groups, group_subs;  // group_subs: workgroups needed to cover the largest group's sequences
+    uint32_t group_items;        // grid entries that serve shared prefixes (they come first)
 };
 
 struct MergeArgs {

@@ -41,6 +41,13 @@ class DeviceWorkload:
             self.k_new, self.v_new = _to_dev(wl.k_new, self.device), _to_dev(wl.v_new, self.device)
             self.seq_ids, self.positions = _to_dev(wl.seq_ids, self.device), _to_dev(wl.positions, self.device)
             self.T = int(wl.k_new.shape[0])
+        self.group_start = self.shared_len = None
+        self.num_groups = self.max_group_size = self.max_shared_len = 0
+        if getattr(wl, "group_start", None) is not None:
+            self.group_start, self.shared_len = _to_dev(wl.group_start, self.device), _to_dev(wl.shared_len, self.device)
+            self.num_groups = int(len(wl.group_start) - 1)
+            self.max_group_size = int(np.diff(wl.group_start).max())
+            self.max_shared_len = int(wl.shared_len.max())
         self.out = torch.empty((wl.batch, wl.num_q_heads, wl.head_dim), dtype=torch.float32, device=self.device)
         self.ws_bytes = sd.workspace_bytes(self.shape)
         self.workspace = torch.empty(max(self.ws_bytes, 256), dtype=torch.uint8, device=self.device)
@@ -63,6 +70,15 @@ class DeviceWorkload:
         sd.paged_decode_attention(self.shape, self.q, self.k_pages, self.v_pages, self.k_scales, self.v_scales,
                                   self.block_table, self.context_lens, self.scale, out, self.workspace,
                                   self.ws_bytes, stream, timer)
+        return out
+
+    def attend_prefix(self, stream=None, timer=None, out=None):
+        """Shared-prefix aware call (needs the workload's group_start / shared_len)."""
+        out = self.out if out is None else out
+        sd.paged_decode_attention_prefix(self.shape, self.q, self.k_pages, self.v_pages, self.k_scales, self.v_scales,
+                                         self.block_table, self.context_lens, self.group_start, self.shared_len,
+                                         self.num_groups, self.max_group_size, self.max_shared_len, self.scale, out,
+                                         self.workspace, self.ws_bytes, stream, timer)
         return out
 
     def pools_to_host(self):

@@ -357,3 +357,66 @@ def test_full_size_fp8_large_batch(sd):
     ref = oracle.attend_rows(wl.q, wl.k_pages, wl.v_pages, wl.block_table, wl.context_lens, wl.scale, rows,
                              wl.k_scales, wl.v_scales, "fp8")
     check_fp8(got[rows[:, 0], rows[:, 1]], ref)
+
+
+# ---------------------------------------------------------------- shared-prefix aware entry point
+def gpu_attend_prefix(wl, **kw):
+    import torch
+    dw = device_workload(wl, **kw)
+    out = dw.attend_prefix()
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+@pytest.mark.parametrize("Hq,Hkv,d", [(8, 2, 128), (28, 4, 128), (8, 1, 64), (16, 1, 128), (3, 1, 128)])
+@pytest.mark.parametrize("chunk", [128, 512])
+def test_prefix_entry_point_matches_oracle(sd, Hq, Hkv, d, chunk):
+    """Groups of 1, 2, 5, 16 and 19 sequences; shared prefixes that are shorter than a chunk, end inside
+    a chunk, end on a chunk boundary, and cover a whole sequence."""
+    sizes = [1, 2, 5, 16, 19, 3]
+    prefix = [300, 3 * chunk, chunk + 77, 2 * chunk + 16, 40, 4 * chunk]
+    session_of = np.repeat(np.arange(len(sizes)), sizes)
+    prefix_len = np.repeat(prefix, sizes)
+    rng = np.random.default_rng(chunk + Hq)
+    lens = prefix_len + rng.integers(0, 2 * chunk, size=len(session_of), endpoint=True)
+    lens[7] = prefix_len[7]  # one sequence is nothing but its shared prefix
+    wl = workloads.make_custom(lens, Hq, Hkv, d, seed=400 + Hq + chunk, session_of=session_of, prefix_len=prefix_len)
+    got = gpu_attend_prefix(wl, chunk_tokens=chunk)
+    check(got, oracle_full(wl))
+    plain = gpu_attend(wl, chunk_tokens=chunk)
+    assert np.abs(got - plain).max() <= ALARM_ABS + ALARM_REL * np.abs(plain).max()
+
+
+def test_prefix_entry_point_fp8(sd):
+    sizes = [4, 16, 1]
+    session_of = np.repeat(np.arange(3), sizes)
+    prefix_len = np.repeat([1024, 2048 + 512, 512], sizes)  # multiples of 16: fp8 tails are not copied
+    lens = prefix_len + np.random.default_rng(5).integers(1, 700, size=len(session_of))
+    wl = workloads.make_custom(lens, 16, 2, 128, "fp8", seed=410, session_of=session_of, prefix_len=prefix_len)
+    check_fp8(gpu_attend_prefix(wl, chunk_tokens=512), oracle_full(wl))
+
+
+def test_prefix_entry_point_without_groups_is_the_plain_call(sd):
+    import torch
+    wl = workloads.make_custom([700, 1500, 64], 8, 2, 128, seed=420)
+    dw = device_workload(wl)
+    a = dw.attend().clone()
+    b = torch.zeros_like(a)
+    sd.paged_decode_attention_prefix(dw.shape, dw.q, dw.k_pages, dw.v_pages, None, None, dw.block_table,
+                                     dw.context_lens, None, None, 0, 0, 0, dw.scale, b, dw.workspace, dw.ws_bytes)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+
+
+def test_full_size_branching_mix_prefix_aware(sd):
+    import torch
+    wl = workloads.make_config(3)
+    dw = device_workload(wl)
+    dw.append()
+    out = dw.attend_prefix()
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    oracle.kv_append(wl.k_new, wl.v_new, wl.seq_ids, wl.positions, wl.k_pages, wl.v_pages, wl.block_table)
+    rows = sampled_rows(wl, 96)
+    ref = oracle.attend_rows(wl.q, wl.k_pages, wl.v_pages, wl.block_table, wl.context_lens, wl.scale, rows)
+    check(got[rows[:, 0], rows[:, 1]], ref)

@@ -76,6 +76,10 @@ class Workload:
     v_new: Optional[np.ndarray] = None
     seq_ids: Optional[np.ndarray] = None  # int32 [T]
     positions: Optional[np.ndarray] = None  # int32 [T]
+    # sessions whose branches share prefix pages: group j = sequences group_start[j] .. group_start[j+1]-1,
+    # shared_len[b] = leading tokens of b whose pages all members of its group share (a multiple of 16)
+    group_start: Optional[np.ndarray] = None  # int32 [num_groups + 1]
+    shared_len: Optional[np.ndarray] = None  # int32 [B]
     # bookkeeping for reports
     unique_tokens: int = 0
     seed: int = 0
@@ -240,6 +244,11 @@ def build_paged(
     )
     uniq = int(valid.astype(np.int64).sum())
     wl.unique_tokens = uniq
+    if session_of is not None:
+        change = np.nonzero(np.diff(session_of))[0] + 1
+        assert len(set(session_of.tolist())) == len(change) + 1, "sequences of a session must be consecutive"
+        wl.group_start = np.concatenate([[0], change, [B]]).astype(np.int32)
+        wl.shared_len = (shared_pages * PAGE).astype(np.int32)
 
     if append:
         assert kv_dtype == "bf16", "the staged append is bf16 only"
