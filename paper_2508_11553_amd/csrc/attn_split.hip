@@ -484,54 +484,22 @@ SD_DEV void reset(WaveState<D> &st)
     for (int i = 0; i < D / 16; ++i) st.acc[i] = f32x4{0, 0, 0, 0};
 }
 
-// Shared-prefix item: one workgroup owns one (chunk of a group's shared prefix,
-// sub-group of its sequences, KV head).  The pages are the same for every
-// sequence of the group, so each wave takes 16 query rows (16/G sequences x G
-// heads) and walks ALL tiles of the chunk; the four waves read the same bytes
-// at almost the same time, so they reach HBM once.  Every wave writes the
-// partials of its own rows; there is nothing to merge across waves.
-template <class P>
-SD_DEV void group_item(const SplitArgs &a, unsigned item, char *scratch, int lane, int wave)
-{
-    constexpr int D = P::kDim;
-    const int g = item % a.Hkv;
-    const int sub = (item / a.Hkv) % a.group_subs;
-    const int grp = (item / (a.Hkv * a.group_subs)) % a.num_groups;
-    const int c = item / (a.Hkv * a.group_subs * a.num_groups);
-    const int gs = a.group_start[grp], ge = a.group_start[grp + 1];
-    const int spw = a.G <= kMaxGroup / 2 ? kMaxGroup / a.G : 1;  // sequences per wave
-    const int s0 = gs + (sub * kWaves + wave) * spw;              // this wave's first sequence
-    if (s0 >= ge) return;
-    const int shared = min(min(a.shared_len[gs], a.context_lens[gs]), a.max_context_len);
-    const int t0 = c * a.chunk_tokens;
-    if (t0 + a.chunk_tokens > shared) return;  // only whole chunks inside the shared prefix
-    const int t1 = t0 + a.chunk_tokens;
-
-    const int n = lane & 15;
-    const int seq = s0 + n / a.G, head = g * a.G + n % a.G;
-    const bool row_ok = n / a.G < spw && seq < ge;
-    u32x4 qop[D / 32];
-    {
-        const uint16_t *qrow = a.q + ((int64_t)seq * a.Hq + head) * D;
-#pragma unroll
-        for (int s = 0; s < D / 32; ++s)
-            qop[s] = row_ok ? *reinterpret_cast<const u32x4 *>(qrow + P::q_offset(s, lane)) : u32x4{0, 0, 0, 0};
-    }
-    WaveState<D> st;
-    reset(st);
-    const int32_t *bt = a.block_table + (int64_t)gs * a.max_blocks + t0 / kPage;
-    stream_tiles<P, false>(a, bt, g, t0, t1, 0, 1, qop, st, scratch, lane);
-    st.l = head_sum(st.l);
-    if (row_ok) {
-        const int64_t slot = ((int64_t)seq * a.Hq + head) * a.S + c;
-        P::store_acc(st, a.ws_acc + slot * D, lane >> 4);
-        if ((lane >> 4) == 0) {
-            a.ws_m[slot] = st.m;
-            a.ws_l[slot] = st.l;
-        }
-    }
-}
-
+// One workgroup = one item = 16 query rows (of one KV head) x one chunk of tokens.
+//
+// Plain item: the rows are the G query heads of one sequence (rows >= G idle);
+// the chunk may be ragged at the sequence's end; K/V bytes are read by nobody
+// else, so they stream (non-temporal loads).
+//
+// Shared-prefix item: the rows are G heads each of 16/G consecutive sequences
+// of a group, over a whole chunk of the group's shared prefix, whose pages are
+// the same for every member (the first member's table row is read).  The
+// column blocks of one (chunk, group, KV head) sit next to each other in the
+// grid, 8 entries apart when there are 8 KV heads, so that they run at the
+// same time on the same XCD and all but the first find the bytes in L2; their
+// loads are ordinary (cached) loads for that reason.
+//
+// Either way the four waves take every fourth 32-token tile, merge through
+// LDS, and write one partial per row.
 template <class P>
 __global__ __launch_bounds__(kWaves * 64, 2) void split_kernel(SplitArgs a)
 {
@@ -545,38 +513,60 @@ __global__ __launch_bounds__(kWaves * 64, 2) void split_kernel(SplitArgs a)
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    if (blockIdx.x < a.group_items) {  // shared-prefix items come first in the grid
-        group_item<P>(a, blockIdx.x, s_k[wave], lane, wave);
-        return;
+
+    int g, c, t0, t1, seq0, seq_end, seqs_per_item, table_seq;
+    const bool shared_item = blockIdx.x < a.group_items;  // shared-prefix items come first in the grid
+    if (shared_item) {
+        const unsigned item = blockIdx.x;  // (chunk, group, column block, kv head), kv head fastest
+        g = item % a.Hkv;
+        const int cb = (item / a.Hkv) % a.group_subs;
+        const int grp = (item / (a.Hkv * a.group_subs)) % a.num_groups;
+        c = item / (a.Hkv * a.group_subs * a.num_groups);
+        const int gs = a.group_start[grp];
+        seq_end = a.group_start[grp + 1];
+        seqs_per_item = a.G <= kMaxGroup / 2 ? kMaxGroup / a.G : 1;
+        seq0 = gs + cb * seqs_per_item;
+        if (seq0 >= seq_end) return;
+        table_seq = gs;
+        const int shared = min(min(a.shared_len[gs], a.context_lens[gs]), a.max_context_len);
+        t0 = c * a.chunk_tokens;
+        t1 = t0 + a.chunk_tokens;
+        if (t1 > shared) return;  // only whole chunks inside the shared prefix
+    } else {
+        const unsigned item = blockIdx.x - a.group_items;  // (chunk, sequence, kv head), kv head fastest
+        g = item % a.Hkv;
+        const int b = (item / a.Hkv) % a.B;
+        c = item / (a.Hkv * a.B);
+        const int L = min(a.context_lens[b], a.max_context_len);
+        t0 = c * a.chunk_tokens;
+        if (t0 >= L) return;
+        // whole chunks inside a shared prefix belong to the shared-prefix items
+        if (a.shared_len && t0 + a.chunk_tokens <= min(a.shared_len[b], L)) return;
+        t1 = min(L, t0 + a.chunk_tokens);
+        seq0 = table_seq = b;
+        seq_end = b + 1;
+        seqs_per_item = 1;
     }
-    const unsigned item = blockIdx.x - a.group_items;  // (chunk, sequence, kv head), kv head fastest
-    const int g = item % a.Hkv;
-    const int b = (item / a.Hkv) % a.B;
-    const int c = item / (a.Hkv * a.B);
 
-    const int L = min(a.context_lens[b], a.max_context_len);
-    const int t0 = c * a.chunk_tokens;
-    if (t0 >= L) return;
-    // whole chunks inside a shared prefix belong to the shared-prefix items
-    if (a.shared_len && t0 + a.chunk_tokens <= min(a.shared_len[b], L)) return;
-    const int t1 = min(L, t0 + a.chunk_tokens);
-
-    // Q^T operand: lane = head n; heads >= G are zero rows
+    // Q^T operand: lane&15 = row n -> (sequence seq0 + n / G, head g*G + n % G); idle rows are zero
     const int n = lane & 15;
+    const int row_seq = seq0 + n / a.G;
+    const int64_t row = (int64_t)row_seq * a.Hq + g * a.G + n % a.G;  // index into q / out / partial rows
+    const bool row_ok = n / a.G < seqs_per_item && row_seq < seq_end;
     u32x4 qop[D / 32];
-    {
-        const uint16_t *qrow = a.q + ((int64_t)b * a.Hq + (int64_t)g * a.G + n) * D;
 #pragma unroll
-        for (int s = 0; s < D / 32; ++s)
-            qop[s] = (n < a.G) ? *reinterpret_cast<const u32x4 *>(qrow + P::q_offset(s, lane)) : u32x4{0, 0, 0, 0};
-    }
+    for (int s = 0; s < D / 32; ++s)
+        qop[s] = row_ok ? *reinterpret_cast<const u32x4 *>(a.q + row * D + P::q_offset(s, lane)) : u32x4{0, 0, 0, 0};
 
     WaveState<D> st;
     reset(st);
-    const int32_t *bt = a.block_table + (int64_t)b * a.max_blocks + t0 / kPage;
-    stream_tiles<P, true>(a, bt, g, t0, t1, wave, kWaves, qop, st, s_k[wave], lane);
+    const int32_t *bt = a.block_table + (int64_t)table_seq * a.max_blocks + t0 / kPage;
+    if (shared_item)
+        stream_tiles<P, false>(a, bt, g, t0, t1, wave, kWaves, qop, st, s_k[wave], lane);
+    else
+        stream_tiles<P, true>(a, bt, g, t0, t1, wave, kWaves, qop, st, s_k[wave], lane);
 
-    // the four lanes of a head hold disjoint shares of the weight sum
+    // the four lanes of a row hold disjoint shares of the weight sum
     st.l = head_sum(st.l);
 
     const int qd = lane >> 4;
@@ -588,20 +578,21 @@ __global__ __launch_bounds__(kWaves * 64, 2) void split_kernel(SplitArgs a)
     __syncthreads();
 
     // merge the four waves; wave 0 always saw at least one token, so the max is finite
-    const int64_t row0 = (int64_t)b * a.Hq + (int64_t)g * a.G;
-    for (int idx = tid; idx < a.G * D; idx += kWaves * 64) {
-        const int hn = idx / D, dd = idx % D;
-        float M = s_m[0][hn];
+    const int nrows = min(seqs_per_item, seq_end - seq0) * a.G;
+    for (int idx = tid; idx < nrows * D; idx += kWaves * 64) {
+        const int rn = idx / D, dd = idx % D;
+        float M = s_m[0][rn];
 #pragma unroll
-        for (int w = 1; w < kWaves; ++w) M = fmaxf(M, s_m[w][hn]);
+        for (int w = 1; w < kWaves; ++w) M = fmaxf(M, s_m[w][rn]);
         float num = 0.f, den = 0.f;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
-            const float wt = __builtin_amdgcn_exp2f(s_m[w][hn] - M);
-            num += wt * s_acc[w][hn][dd];
-            den += wt * s_l[w][hn];
+            const float wt = __builtin_amdgcn_exp2f(s_m[w][rn] - M);
+            num += wt * s_acc[w][rn][dd];
+            den += wt * s_l[w][rn];
         }
-        const int64_t slot = (row0 + hn) * a.S + c;
+        const int64_t out_row = (int64_t)(seq0 + rn / a.G) * a.Hq + g * a.G + rn % a.G;
+        const int64_t slot = out_row * a.S + c;
         a.ws_acc[slot * D + dd] = num;
         if (dd == 0) {
             a.ws_m[slot] = M;
