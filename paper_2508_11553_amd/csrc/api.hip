@@ -200,9 +200,9 @@ int paged_decode_attention_prefix(const sd_shape *shape, const void *q, const vo
     sa.S = S;
     sa.chunk_tokens = chunk;
     sa.max_context_len = shape->max_context_len;
-    // shared-prefix items: whole chunks of each group's shared prefix, 16 / G sequences per workgroup
+    // shared-prefix items: whole chunks of each group's shared prefix, 4 waves x (16 / G) sequences per workgroup
     const int shared_chunks = num_groups > 0 ? max_shared_len / chunk : 0;
-    const int seqs_per_wg = sa.G <= sd::kMaxGroup / 2 ? sd::kMaxGroup / sa.G : 1;
+    const int seqs_per_wg = sd::kWaves * (sa.G <= sd::kMaxGroup / 2 ? sd::kMaxGroup / sa.G : 1);
     sa.group_start = shared_chunks ? group_start : nullptr;
     sa.shared_len = shared_chunks ? shared_len : nullptr;
     sa.num_groups = shared_chunks ? num_groups : 0;

@@ -149,7 +149,8 @@ template <int D>
 struct Bf16Path {
     static constexpr int kDim = D;
     static constexpr int kTileBytes = kPage * D * 2;     // one (page, head) tile
-    static constexpr int kScratchBytes = 2 * kTileBytes;  // K transposition scratch per wave
+    static constexpr int kScratchBytes = 2 * kTileBytes;  // K of one 32-token tile in LDS
+    static constexpr int kVBytes = 2 * kTileBytes;        // V registers of one tile parked in LDS
     static constexpr int kPieces = D / 8;                 // 16-byte pieces per K row
     static constexpr int kRowsPerLoad = 64 / kPieces;     // K rows one 1024-byte load covers
 
@@ -175,11 +176,11 @@ struct Bf16Path {
                 r.v[pg][h][j] = kv_load<STREAM>(reinterpret_cast<const u32x2 *>(vl + j * (D * 2) + h * 128));
     }
 
-    // K tiles through the wave's LDS scratch: written as they lie in memory,
-    // read back one row per lane.  Piece c of row r sits at piece index c ^ r so
-    // that the writes (16 lanes = one row) and the reads (16 lanes = one piece
-    // column over 16 rows) both spread over all banks.
-    SD_DEV static void k_operands(const Tile &r, char *scratch, int lane, u32x4 (&ka)[D / 32], u32x4 (&kb)[D / 32])
+    // K tiles go through LDS: written as they lie in memory, read back one row
+    // per lane.  Piece c of row r sits at piece index c ^ r so that the writes
+    // (16 lanes = one row) and the reads (16 lanes = one piece column over 16
+    // rows) both spread over all banks.
+    SD_DEV static void k_store(const Tile &r, char *kslot, int lane)
     {
 #pragma unroll
         for (int pg = 0; pg < 2; ++pg)
@@ -187,33 +188,63 @@ struct Bf16Path {
             for (int j = 0; j < D / 32; ++j) {
                 const int row = j * kRowsPerLoad + lane / kPieces;
                 const int piece = (lane % kPieces) ^ (row % kPieces);
-                *reinterpret_cast<u32x4 *>(scratch + pg * kTileBytes + row * (D * 2) + piece * 16) = r.k[pg][j];
+                *reinterpret_cast<u32x4 *>(kslot + pg * kTileBytes + row * (D * 2) + piece * 16) = r.k[pg][j];
             }
-        wave_lds_fence();
+    }
+
+    // K row (lane&15), d = 32*s + 8*(lane>>4) .. +8, of both pages
+    SD_DEV static void k_fetch(const char *kslot, int lane, u32x4 (&ka)[D / 32], u32x4 (&kb)[D / 32])
+    {
         const int t = lane & 15, kg = lane >> 4;
 #pragma unroll
         for (int s = 0; s < D / 32; ++s) {
             const int piece = (4 * s + kg) ^ (t % kPieces);
-            ka[s] = *reinterpret_cast<const u32x4 *>(scratch + t * (D * 2) + piece * 16);
-            kb[s] = *reinterpret_cast<const u32x4 *>(scratch + kTileBytes + t * (D * 2) + piece * 16);
+            ka[s] = *reinterpret_cast<const u32x4 *>(kslot + t * (D * 2) + piece * 16);
+            kb[s] = *reinterpret_cast<const u32x4 *>(kslot + kTileBytes + t * (D * 2) + piece * 16);
         }
-        wave_lds_fence();
     }
 
-    // One 32-token tile: tokens tok0 .. tok0+31, of which those < t_end are real.
-    SD_DEV static void consume(Tile &r, const u32x4 (&qop)[D / 32], WaveState<D> &st, float scale_log2e,
-                               int tok0, int t_end, int lane, char *scratch)
+    // V registers (the same for every wave that consumes the tile) parked in LDS, lane-linear
+    SD_DEV static void v_store(const Tile &r, char *vslot, int lane)
+    {
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+            for (int h = 0; h < D / 64; ++h)
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj) {
+                    const u32x4 w = {r.v[pg][h][2 * jj][0], r.v[pg][h][2 * jj][1], r.v[pg][h][2 * jj + 1][0],
+                                     r.v[pg][h][2 * jj + 1][1]};
+                    *reinterpret_cast<u32x4 *>(vslot + ((pg * (D / 64) + h) * 2 + jj) * 1024 + lane * 16) = w;
+                }
+    }
+    SD_DEV static void v_fetch(Tile &r, const char *vslot, int lane)
+    {
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+            for (int h = 0; h < D / 64; ++h)
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj) {
+                    const u32x4 w = *reinterpret_cast<const u32x4 *>(vslot + ((pg * (D / 64) + h) * 2 + jj) * 1024 + lane * 16);
+                    r.v[pg][h][2 * jj] = u32x2{w[0], w[1]};
+                    r.v[pg][h][2 * jj + 1] = u32x2{w[2], w[3]};
+                }
+    }
+
+    // Scores, online softmax and weighted V sum of one 32-token tile: tokens
+    // tok0 .. tok0+31, of which those < t_end are real.  ka/kb: K operands of
+    // the two pages; r.v: the V registers.
+    SD_DEV static void attend(const u32x4 (&ka)[D / 32], const u32x4 (&kb)[D / 32], Tile &r,
+                              const u32x4 (&qop)[D / 32], WaveState<D> &st, float scale_log2e, int tok0, int t_end,
+                              int lane)
     {
         const int qd = lane >> 4;
         f32x4 sa = {0, 0, 0, 0}, sb = {0, 0, 0, 0};
-        {
-            u32x4 ka[D / 32], kb[D / 32];  // K row (lane&15), d = 32*s + 8*(lane>>4) .. +8
-            k_operands(r, scratch, lane, ka, kb);
 #pragma unroll
-            for (int s = 0; s < D / 32; ++s) {
-                sa = mfma_bf16_k32(ka[s], qop[s], sa);
-                sb = mfma_bf16_k32(kb[s], qop[s], sb);
-            }
+        for (int s = 0; s < D / 32; ++s) {
+            sa = mfma_bf16_k32(ka[s], qop[s], sa);
+            sb = mfma_bf16_k32(kb[s], qop[s], sb);
         }
         const bool ragged = tok0 + kTileTokens > t_end;  // wave-uniform
         float x[8], p[8];
@@ -289,6 +320,7 @@ struct Fp8Path {
     static constexpr int kDim = D;
     static constexpr int kTileBytes = kPage * D;
     static constexpr int kScratchBytes = 2 * kTileBytes;
+    static constexpr int kVBytes = 2 * kTileBytes + 16;  // codes + the four page scales
 
     struct Tile {
         u32x4 k[2][2];  // [page][j]: 16 bytes at byte offset 1024*j + 16*lane of the K tile
@@ -315,7 +347,7 @@ struct Fp8Path {
 
     // Rows are 128 bytes = 8 pieces; piece c of row r sits at c ^ (r >> 1), and
     // odd rows start half a bank cycle later, so 16 lanes never share a bank.
-    SD_DEV static void k_operands(const Tile &r, char *scratch, int lane, u32x4 (&ka)[4], u32x4 (&kb)[4])
+    SD_DEV static void k_store(const Tile &r, char *kslot, int lane)
     {
 #pragma unroll
         for (int pg = 0; pg < 2; ++pg)
@@ -323,9 +355,12 @@ struct Fp8Path {
             for (int j = 0; j < 2; ++j) {
                 const int row = 8 * j + (lane >> 3);
                 const int piece = (lane & 7) ^ ((row >> 1) & 7);
-                *reinterpret_cast<u32x4 *>(scratch + pg * kTileBytes + row * D + piece * 16) = r.k[pg][j];
+                *reinterpret_cast<u32x4 *>(kslot + pg * kTileBytes + row * D + piece * 16) = r.k[pg][j];
             }
-        wave_lds_fence();
+    }
+
+    SD_DEV static void k_fetch(const char *kslot, int lane, u32x4 (&ka)[4], u32x4 (&kb)[4])
+    {
         const int t = lane & 15, kg = lane >> 4;
         u32x4 raw[2][2];
 #pragma unroll
@@ -333,9 +368,8 @@ struct Fp8Path {
 #pragma unroll
             for (int hh = 0; hh < 2; ++hh) {
                 const int piece = (kg + 4 * hh) ^ ((t >> 1) & 7);
-                raw[pg][hh] = *reinterpret_cast<const u32x4 *>(scratch + pg * kTileBytes + t * D + piece * 16);
+                raw[pg][hh] = *reinterpret_cast<const u32x4 *>(kslot + pg * kTileBytes + t * D + piece * 16);
             }
-        wave_lds_fence();
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const int hh = s >> 1, lo = 2 * (s & 1);
@@ -346,19 +380,44 @@ struct Fp8Path {
         }
     }
 
-    SD_DEV static void consume(Tile &r, const u32x4 (&qop)[4], WaveState<D> &st, float scale_log2e,
-                               int tok0, int t_end, int lane, char *scratch)
+    // V registers and the four page scales parked in LDS (scales after the 4 KB of codes)
+    SD_DEV static void v_store(const Tile &r, char *vslot, int lane)
+    {
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj) {
+                const u32x4 w = {r.v[pg][2 * jj][0], r.v[pg][2 * jj][1], r.v[pg][2 * jj + 1][0], r.v[pg][2 * jj + 1][1]};
+                *reinterpret_cast<u32x4 *>(vslot + (pg * 2 + jj) * 1024 + lane * 16) = w;
+            }
+        if (lane == 0) *reinterpret_cast<f32x4 *>(vslot + 4096) = f32x4{r.ks[0], r.ks[1], r.vs[0], r.vs[1]};
+    }
+    SD_DEV static void v_fetch(Tile &r, const char *vslot, int lane)
+    {
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj) {
+                const u32x4 w = *reinterpret_cast<const u32x4 *>(vslot + (pg * 2 + jj) * 1024 + lane * 16);
+                r.v[pg][2 * jj] = u32x2{w[0], w[1]};
+                r.v[pg][2 * jj + 1] = u32x2{w[2], w[3]};
+            }
+        const f32x4 sc = *reinterpret_cast<const f32x4 *>(vslot + 4096);
+        r.ks[0] = sc[0];
+        r.ks[1] = sc[1];
+        r.vs[0] = sc[2];
+        r.vs[1] = sc[3];
+    }
+
+    SD_DEV static void attend(const u32x4 (&ka)[4], const u32x4 (&kb)[4], Tile &r, const u32x4 (&qop)[4],
+                              WaveState<D> &st, float scale_log2e, int tok0, int t_end, int lane)
     {
         const int qd = lane >> 4;
         f32x4 sa = {0, 0, 0, 0}, sb = {0, 0, 0, 0};
-        {
-            u32x4 ka[4], kb[4];
-            k_operands(r, scratch, lane, ka, kb);
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                sa = mfma_bf16_k32(ka[s], qop[s], sa);
-                sb = mfma_bf16_k32(kb[s], qop[s], sb);
-            }
+        for (int s = 0; s < 4; ++s) {
+            sa = mfma_bf16_k32(ka[s], qop[s], sa);
+            sb = mfma_bf16_k32(kb[s], qop[s], sb);
         }
         const bool ragged = tok0 + kTileTokens > t_end;
         const float ca = scale_log2e * r.ks[0], cb = scale_log2e * r.ks[1];
@@ -449,8 +508,15 @@ SD_DEV void stream_tiles(const SplitArgs &a, const int32_t *bt, int g, int t0, i
         P::template load_page<STREAM>(r, 1, kbase + pb * page_bytes, vbase + pb * page_bytes, a.k_scales, a.v_scales,
                      (int64_t)pb * a.Hkv + g, lane);
     };
+    // K takes a round trip through this wave's own LDS scratch; only the owning
+    // wave touches it, so wave-level fences suffice
     auto consume = [&](typename P::Tile &r, int i) {
-        P::consume(r, qop, st, a.scale_log2e, t0 + (first + stride * i) * kTileTokens, t1, lane, scratch);
+        u32x4 ka[P::kDim / 32], kb[P::kDim / 32];
+        P::k_store(r, scratch, lane);
+        wave_lds_fence();
+        P::k_fetch(scratch, lane, ka, kb);
+        wave_lds_fence();
+        P::attend(ka, kb, r, qop, st, a.scale_log2e, t0 + (first + stride * i) * kTileTokens, t1, lane);
     };
     typename P::Tile ra, rb;
     int pa, pb;
@@ -484,89 +550,155 @@ SD_DEV void reset(WaveState<D> &st)
     for (int i = 0; i < D / 16; ++i) st.acc[i] = f32x4{0, 0, 0, 0};
 }
 
-// One workgroup = one item = 16 query rows (of one KV head) x one chunk of tokens.
-//
-// Plain item: the rows are the G query heads of one sequence (rows >= G idle);
-// the chunk may be ragged at the sequence's end; K/V bytes are read by nobody
-// else, so they stream (non-temporal loads).
-//
-// Shared-prefix item: the rows are G heads each of 16/G consecutive sequences
-// of a group, over a whole chunk of the group's shared prefix, whose pages are
-// the same for every member (the first member's table row is read).  The
-// column blocks of one (chunk, group, KV head) sit next to each other in the
-// grid, 8 entries apart when there are 8 KV heads, so that they run at the
-// same time on the same XCD and all but the first find the bytes in L2; their
-// loads are ordinary (cached) loads for that reason.
-//
-// Either way the four waves take every fourth 32-token tile, merge through
-// LDS, and write one partial per row.
+// LDS of one workgroup.  Plain items: per-wave K scratch plus the merge
+// buffers.  Shared-prefix items: four tile slots (K image + parked V
+// registers), one filled by each wave and read by all.
 template <class P>
-__global__ __launch_bounds__(kWaves * 64, 2) void split_kernel(SplitArgs a)
+struct Lds {
+    static constexpr int kRow = P::kDim + 4;  // padded: 16 rows x float4 stores hit 64 distinct banks
+    static constexpr int kSlotBytes = P::kScratchBytes + ((P::kVBytes + 15) / 16) * 16;
+    static constexpr int kPlainBytes = kWaves * P::kScratchBytes + kWaves * kMaxGroup * kRow * 4 + 2 * kWaves * kMaxGroup * 4;
+    static constexpr int kSharedBytes = kWaves * kSlotBytes;
+    static constexpr int kBytes = kPlainBytes > kSharedBytes ? kPlainBytes : kSharedBytes;
+};
+
+// Shared-prefix item: one workgroup owns one whole chunk of a group's shared
+// prefix for one KV head and up to 64 query rows: wave w owns the 16 rows of
+// column block w (G heads each of 16/G consecutive sequences of the group).
+// The pages are the same for every member, so the first member's table row is
+// read.  Per round each wave loads a different 32-token tile from HBM (one
+// round prefetched ahead), parks it in its LDS slot, and after a barrier every
+// wave attends all four tiles from LDS with its own rows: each byte leaves HBM
+// once per workgroup and the four-fold reuse is paid in LDS bandwidth.  Every
+// wave writes the partials of its own rows; nothing is merged across waves.
+template <class P>
+SD_DEV void shared_item(const SplitArgs &a, char *lds, int lane, int wave)
 {
     constexpr int D = P::kDim;
-    constexpr int kRow = D + 4;  // padded LDS row: 16 heads x float4 stores hit 64 distinct banks
-    __shared__ __attribute__((aligned(16))) float s_acc[kWaves][kMaxGroup][kRow];
-    __shared__ __attribute__((aligned(16))) char s_k[kWaves][P::kScratchBytes];
-    __shared__ float s_m[kWaves][kMaxGroup];
-    __shared__ float s_l[kWaves][kMaxGroup];
+    constexpr int kSlot = Lds<P>::kSlotBytes;
+    const unsigned item = blockIdx.x;  // (chunk, group, block of 4 column blocks, kv head), kv head fastest
+    const int g = item % a.Hkv;
+    const int sub = (item / a.Hkv) % a.group_subs;
+    const int grp = (item / (a.Hkv * a.group_subs)) % a.num_groups;
+    const int c = item / (a.Hkv * a.group_subs * a.num_groups);
+    const int gs = a.group_start[grp], ge = a.group_start[grp + 1];
+    const int spw = a.G <= kMaxGroup / 2 ? kMaxGroup / a.G : 1;  // sequences per column block
+    if (gs + sub * kWaves * spw >= ge) return;                    // workgroup-uniform
+    const int shared = min(min(a.shared_len[gs], a.context_lens[gs]), a.max_context_len);
+    const int t0 = c * a.chunk_tokens, t1 = t0 + a.chunk_tokens;
+    if (t1 > shared) return;  // only whole chunks inside the shared prefix (workgroup-uniform)
 
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-
-    int g, c, t0, t1, seq0, seq_end, seqs_per_item, table_seq;
-    const bool shared_item = blockIdx.x < a.group_items;  // shared-prefix items come first in the grid
-    if (shared_item) {
-        const unsigned item = blockIdx.x;  // (chunk, group, column block, kv head), kv head fastest
-        g = item % a.Hkv;
-        const int cb = (item / a.Hkv) % a.group_subs;
-        const int grp = (item / (a.Hkv * a.group_subs)) % a.num_groups;
-        c = item / (a.Hkv * a.group_subs * a.num_groups);
-        const int gs = a.group_start[grp];
-        seq_end = a.group_start[grp + 1];
-        seqs_per_item = a.G <= kMaxGroup / 2 ? kMaxGroup / a.G : 1;
-        seq0 = gs + cb * seqs_per_item;
-        if (seq0 >= seq_end) return;
-        table_seq = gs;
-        const int shared = min(min(a.shared_len[gs], a.context_lens[gs]), a.max_context_len);
-        t0 = c * a.chunk_tokens;
-        t1 = t0 + a.chunk_tokens;
-        if (t1 > shared) return;  // only whole chunks inside the shared prefix
-    } else {
-        const unsigned item = blockIdx.x - a.group_items;  // (chunk, sequence, kv head), kv head fastest
-        g = item % a.Hkv;
-        const int b = (item / a.Hkv) % a.B;
-        c = item / (a.Hkv * a.B);
-        const int L = min(a.context_lens[b], a.max_context_len);
-        t0 = c * a.chunk_tokens;
-        if (t0 >= L) return;
-        // whole chunks inside a shared prefix belong to the shared-prefix items
-        if (a.shared_len && t0 + a.chunk_tokens <= min(a.shared_len[b], L)) return;
-        t1 = min(L, t0 + a.chunk_tokens);
-        seq0 = table_seq = b;
-        seq_end = b + 1;
-        seqs_per_item = 1;
-    }
-
-    // Q^T operand: lane&15 = row n -> (sequence seq0 + n / G, head g*G + n % G); idle rows are zero
+    const int seq0 = gs + (sub * kWaves + wave) * spw;
+    const bool active = seq0 < ge;  // wave-uniform; idle waves still load their tile and meet the barriers
     const int n = lane & 15;
     const int row_seq = seq0 + n / a.G;
-    const int64_t row = (int64_t)row_seq * a.Hq + g * a.G + n % a.G;  // index into q / out / partial rows
-    const bool row_ok = n / a.G < seqs_per_item && row_seq < seq_end;
+    const int64_t row = (int64_t)row_seq * a.Hq + g * a.G + n % a.G;
+    const bool row_ok = active && n / a.G < spw && row_seq < ge;
     u32x4 qop[D / 32];
 #pragma unroll
     for (int s = 0; s < D / 32; ++s)
         qop[s] = row_ok ? *reinterpret_cast<const u32x4 *>(a.q + row * D + P::q_offset(s, lane)) : u32x4{0, 0, 0, 0};
+    WaveState<D> st;
+    reset(st);
+
+    const int32_t *bt = a.block_table + (int64_t)gs * a.max_blocks + t0 / kPage;
+    const int64_t page_bytes = (int64_t)P::kTileBytes * a.Hkv;
+    const char *kbase = static_cast<const char *>(a.k_pages) + g * P::kTileBytes;
+    const char *vbase = static_cast<const char *>(a.v_pages) + g * P::kTileBytes;
+    auto issue = [&](typename P::Tile &r, int pa, int pb) {
+        P::template load_page<true>(r, 0, kbase + pa * page_bytes, vbase + pa * page_bytes, a.k_scales, a.v_scales,
+                                    (int64_t)pa * a.Hkv + g, lane);
+        P::template load_page<true>(r, 1, kbase + pb * page_bytes, vbase + pb * page_bytes, a.k_scales, a.v_scales,
+                                    (int64_t)pb * a.Hkv + g, lane);
+    };
+    const int rounds = a.chunk_tokens / (kWaves * kTileTokens);
+    char *mine = lds + wave * kSlot;
+    typename P::Tile r;
+    issue(r, bt[2 * wave], bt[2 * wave + 1]);  // round 0: this wave's tile is tile `wave`
+    for (int rd = 0; rd < rounds; ++rd) {
+        const int tn = kWaves * min(rd + 1, rounds - 1) + wave;
+        const int na = bt[2 * tn], nb = bt[2 * tn + 1];
+        P::k_store(r, mine, lane);
+        P::v_store(r, mine + P::kScratchBytes, lane);
+        if (rd + 1 < rounds) issue(r, na, nb);
+        __syncthreads();
+        if (active) {
+#pragma unroll 1
+            for (int j = 0; j < kWaves; ++j) {
+                const char *slot = lds + j * kSlot;
+                u32x4 ka[D / 32], kb[D / 32];
+                typename P::Tile t;
+                P::k_fetch(slot, lane, ka, kb);
+                P::v_fetch(t, slot + P::kScratchBytes, lane);
+                P::attend(ka, kb, t, qop, st, a.scale_log2e, t0 + (kWaves * rd + j) * kTileTokens, t1, lane);
+            }
+        }
+        __syncthreads();
+    }
+    if (!active) return;
+    st.l = head_sum(st.l);
+    if (row_ok) {
+        const int64_t slot = row * a.S + c;
+        P::store_acc(st, a.ws_acc + slot * D, lane >> 4);
+        if ((lane >> 4) == 0) {
+            a.ws_m[slot] = st.m;
+            a.ws_l[slot] = st.l;
+        }
+    }
+}
+
+// Plain item: one workgroup owns one (sequence b, KV head g, chunk c).  The
+// rows of the MFMA tile are the G query heads of the KV head (rows >= G idle);
+// the chunk may be ragged at the sequence's end; nobody else reads these K/V
+// bytes, so they stream.  The four waves take every fourth 32-token tile,
+// merge through LDS and write one partial per head.
+template <class P>
+__global__ __launch_bounds__(kWaves * 64, 2) void split_kernel(SplitArgs a)
+{
+    constexpr int D = P::kDim;
+    constexpr int kRow = Lds<P>::kRow;
+    __shared__ __attribute__((aligned(16))) char lds[Lds<P>::kBytes];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    if (blockIdx.x < a.group_items) {  // shared-prefix items come first in the grid
+        shared_item<P>(a, lds, lane, wave);
+        return;
+    }
+    char *s_k = lds + wave * P::kScratchBytes;
+    float (*s_acc)[kMaxGroup][kRow] = reinterpret_cast<float (*)[kMaxGroup][kRow]>(lds + kWaves * P::kScratchBytes);
+    float (*s_m)[kMaxGroup] = reinterpret_cast<float (*)[kMaxGroup]>(lds + kWaves * P::kScratchBytes + kWaves * kMaxGroup * kRow * 4);
+    float (*s_l)[kMaxGroup] = s_m + kWaves;
+
+    const unsigned item = blockIdx.x - a.group_items;  // (chunk, sequence, kv head), kv head fastest
+    const int g = item % a.Hkv;
+    const int b = (item / a.Hkv) % a.B;
+    const int c = item / (a.Hkv * a.B);
+
+    const int L = min(a.context_lens[b], a.max_context_len);
+    const int t0 = c * a.chunk_tokens;
+    if (t0 >= L) return;
+    // whole chunks inside a shared prefix belong to the shared-prefix items
+    if (a.shared_len && t0 + a.chunk_tokens <= min(a.shared_len[b], L)) return;
+    const int t1 = min(L, t0 + a.chunk_tokens);
+
+    // Q^T operand: lane&15 = head n; heads >= G are zero rows
+    const int n = lane & 15;
+    u32x4 qop[D / 32];
+    {
+        const uint16_t *qrow = a.q + ((int64_t)b * a.Hq + (int64_t)g * a.G + n) * D;
+#pragma unroll
+        for (int s = 0; s < D / 32; ++s)
+            qop[s] = (n < a.G) ? *reinterpret_cast<const u32x4 *>(qrow + P::q_offset(s, lane)) : u32x4{0, 0, 0, 0};
+    }
 
     WaveState<D> st;
     reset(st);
-    const int32_t *bt = a.block_table + (int64_t)table_seq * a.max_blocks + t0 / kPage;
-    if (shared_item)
-        stream_tiles<P, false>(a, bt, g, t0, t1, wave, kWaves, qop, st, s_k[wave], lane);
-    else
-        stream_tiles<P, true>(a, bt, g, t0, t1, wave, kWaves, qop, st, s_k[wave], lane);
+    const int32_t *bt = a.block_table + (int64_t)b * a.max_blocks + t0 / kPage;
+    stream_tiles<P, true>(a, bt, g, t0, t1, wave, kWaves, qop, st, s_k, lane);
 
-    // the four lanes of a row hold disjoint shares of the weight sum
+    // the four lanes of a head hold disjoint shares of the weight sum
     st.l = head_sum(st.l);
 
     const int qd = lane >> 4;
@@ -578,21 +710,20 @@ __global__ __launch_bounds__(kWaves * 64, 2) void split_kernel(SplitArgs a)
     __syncthreads();
 
     // merge the four waves; wave 0 always saw at least one token, so the max is finite
-    const int nrows = min(seqs_per_item, seq_end - seq0) * a.G;
-    for (int idx = tid; idx < nrows * D; idx += kWaves * 64) {
-        const int rn = idx / D, dd = idx % D;
-        float M = s_m[0][rn];
+    const int64_t row0 = (int64_t)b * a.Hq + (int64_t)g * a.G;
+    for (int idx = tid; idx < a.G * D; idx += kWaves * 64) {
+        const int hn = idx / D, dd = idx % D;
+        float M = s_m[0][hn];
 #pragma unroll
-        for (int w = 1; w < kWaves; ++w) M = fmaxf(M, s_m[w][rn]);
+        for (int w = 1; w < kWaves; ++w) M = fmaxf(M, s_m[w][hn]);
         float num = 0.f, den = 0.f;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
-            const float wt = __builtin_amdgcn_exp2f(s_m[w][rn] - M);
-            num += wt * s_acc[w][rn][dd];
-            den += wt * s_l[w][rn];
+            const float wt = __builtin_amdgcn_exp2f(s_m[w][hn] - M);
+            num += wt * s_acc[w][hn][dd];
+            den += wt * s_l[w][hn];
         }
-        const int64_t out_row = (int64_t)(seq0 + rn / a.G) * a.Hq + g * a.G + rn % a.G;
-        const int64_t slot = out_row * a.S + c;
+        const int64_t slot = (row0 + hn) * a.S + c;
         a.ws_acc[slot * D + dd] = num;
         if (dd == 0) {
             a.ws_m[slot] = M;

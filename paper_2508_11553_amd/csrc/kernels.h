@@ -30,7 +30,7 @@ struct SplitArgs {
     // shared-prefix groups (all zero / null when the call has none)
     const int32_t *group_start;  // [num_groups + 1] first sequence of each group
     const int32_t *shared_len;   // [B] tokens whose pages the sequence shares with its whole group
-    int32_t num_groups, group_subs;  // group_subs: column blocks (16/G sequences each) of the largest group
+    int32_t num_groups, group_subs;  // group_subs: workgroups (4 x 16/G sequences each) that cover the largest group
     uint32_t group_items;        // grid entries that serve shared prefixes (they come first)
 };
 
