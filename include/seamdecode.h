@@ -159,8 +159,8 @@ int paged_decode_attention(const sd_shape *shape, const void *q,
  *   shared_len    i32 [batch] (device): tokens (from position 0) whose pages the
  *                 sequence shares with every sequence of its group; equal within
  *                 a group, <= context_lens of each member, 0 for ungrouped
- *                 sequences.  Only whole chunks (sd_chunk_tokens) inside it are
- *                 read once; the remainder is read per sequence.
+ *                 sequences; rounded down to whole pages.  These tokens are
+ *                 read once per group, everything after them once per sequence.
  *   num_groups, max_group_size, max_shared_len: host-known; upper bounds on the
  *                 group sizes and on shared_len[] (max_shared_len <= max_context_len)
  *   timer         NULL or an sd_timer (see below)

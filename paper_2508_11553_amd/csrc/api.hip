@@ -53,23 +53,22 @@ int pick_chunk(const sd_shape *s)
     int base = 512;
     while (base * elem < 200 * G && base < 4096) base *= 2;
     // Longer chunks also amortise a workgroup's start-up, but the grid must
-    // still hold several workgroups per CU slot (256 CUs x 2).  With few
-    // (sequence, kv head) pairs take the longest chunk that leaves >= 2048 grid
-    // entries; with many pairs the pairs alone fill the machine.
+    // still hold several workgroups per CU slot (256 CUs x 2): take the longest
+    // chunk that leaves >= 2048 grid entries (4096 tokens only when there are
+    // few (sequence, kv head) pairs, so that long sequences still spread out).
     const int64_t pairs = (int64_t)s->batch * s->num_kv_heads;
-    if (pairs < 1024) {
-        for (int chunk = 4096; chunk > base; chunk /= 2) {
-            const int64_t entries = pairs * ((s->max_context_len + chunk - 1) / chunk);
-            if (entries >= 2048) return chunk;
-        }
+    for (int chunk = pairs < 1024 ? 4096 : 2048; chunk > base; chunk /= 2) {
+        const int64_t entries = pairs * ((s->max_context_len + chunk - 1) / chunk);
+        if (entries >= 2048) return chunk;
     }
     return base;
 }
 
+// Chunk slots per output row: one more than the length bound needs, because a
+// shared prefix that ends inside a chunk splits that chunk in two.
 int num_chunks(const sd_shape *s, int chunk)
 {
-    const int n = (s->max_context_len + chunk - 1) / chunk;
-    return n > 0 ? n : 1;
+    return (s->max_context_len + chunk - 1) / chunk + 1;
 }
 
 struct WsLayout {
@@ -201,16 +200,18 @@ int paged_decode_attention_prefix(const sd_shape *shape, const void *q, const vo
     sa.chunk_tokens = chunk;
     sa.max_context_len = shape->max_context_len;
     // shared-prefix items: whole chunks of each group's shared prefix, 4 waves x (16 / G) sequences per workgroup
-    const int shared_chunks = num_groups > 0 ? max_shared_len / chunk : 0;
+    const int shared_chunks = num_groups > 0 ? (max_shared_len + chunk - 1) / chunk : 0;
     const int seqs_per_wg = sd::kWaves * (sa.G <= sd::kMaxGroup / 2 ? sd::kMaxGroup / sa.G : 1);
     sa.group_start = shared_chunks ? group_start : nullptr;
     sa.shared_len = shared_chunks ? shared_len : nullptr;
     sa.num_groups = shared_chunks ? num_groups : 0;
     sa.group_subs = shared_chunks ? (max_group_size + seqs_per_wg - 1) / seqs_per_wg : 0;
     const uint64_t group_items = (uint64_t)shared_chunks * (uint64_t)sa.num_groups * (uint64_t)sa.group_subs * (uint64_t)sa.Hkv;
-    const uint64_t plain_items = (uint64_t)S * (uint64_t)shape->batch * (uint64_t)shape->num_kv_heads;
+    sa.grid_chunks = shared_chunks ? S : S - 1;  // the extra slot exists only where a shared prefix splits a chunk
+    const uint64_t plain_items = (uint64_t)sa.grid_chunks * (uint64_t)shape->batch * (uint64_t)shape->num_kv_heads;
     if (group_items + plain_items > 0x7fffffffull) return SD_EUNSUPPORTED;
     sa.group_items = (uint32_t)group_items;
+    sa.max_shared_len = max_shared_len;
 
     sd::MergeArgs ma;
     ma.ws_m = sa.ws_m;
@@ -223,6 +224,8 @@ int paged_decode_attention_prefix(const sd_shape *shape, const void *q, const vo
     ma.S = S;
     ma.chunk_tokens = chunk;
     ma.max_context_len = shape->max_context_len;
+    ma.shared_len = sa.shared_len;
+    ma.max_shared_len = max_shared_len;
 
     hipEvent_t none[4] = {nullptr, nullptr, nullptr, nullptr};
     hipEvent_t *ev = timer ? &timer->ev[(size_t)timer->calls * 4] : none;

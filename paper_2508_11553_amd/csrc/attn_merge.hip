@@ -2,6 +2,7 @@
 // attention output.  For row (b, h) with n non-empty chunks:
 //   M = max_s m_s;  out = sum_s 2^(m_s-M) acc_s / sum_s 2^(m_s-M) l_s
 // in fixed chunk order (m is kept in the base-2 domain by the split pass).
+// A row's slots are those of its shared prefix followed by those of the rest.
 // One workgroup per row, one thread per output element.
 #include "kernels.h"
 
@@ -14,7 +15,8 @@ __global__ __launch_bounds__(D) void merge_kernel(MergeArgs a)
     const int b = row / a.Hq;
     const int d = threadIdx.x;
     const int L = min(a.context_lens[b], a.max_context_len);
-    const int n = (L + a.chunk_tokens - 1) / a.chunk_tokens;
+    const int sh = a.shared_len ? max(0, min(min(a.shared_len[b], a.max_shared_len), L)) & ~(kPage - 1) : 0;
+    const int n = shared_slots(sh, a.chunk_tokens) + (L - sh + a.chunk_tokens - 1) / a.chunk_tokens;
     float *o = a.out + (int64_t)row * D;
     if (n <= 0) {
         o[d] = 0.f;

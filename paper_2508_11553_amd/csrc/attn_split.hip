@@ -541,6 +541,14 @@ SD_DEV void stream_tiles(const SplitArgs &a, const int32_t *bt, int g, int t0, i
     }
 }
 
+// Tokens of sequence b that its group shares: whole pages, never more than the
+// sequence has and never more than the host-side bound.
+SD_DEV int shared_tokens(const SplitArgs &a, int b)
+{
+    const int L = min(a.context_lens[b], a.max_context_len);
+    return max(0, min(min(a.shared_len[b], a.max_shared_len), L)) & ~(kPage - 1);
+}
+
 template <int D>
 SD_DEV void reset(WaveState<D> &st)
 {
@@ -584,9 +592,10 @@ SD_DEV void shared_item(const SplitArgs &a, char *lds, int lane, int wave)
     const int gs = a.group_start[grp], ge = a.group_start[grp + 1];
     const int spw = a.G <= kMaxGroup / 2 ? kMaxGroup / a.G : 1;  // sequences per column block
     if (gs + sub * kWaves * spw >= ge) return;                    // workgroup-uniform
-    const int shared = min(min(a.shared_len[gs], a.context_lens[gs]), a.max_context_len);
-    const int t0 = c * a.chunk_tokens, t1 = t0 + a.chunk_tokens;
-    if (t1 > shared) return;  // only whole chunks inside the shared prefix (workgroup-uniform)
+    const int shared = shared_tokens(a, gs);
+    const int t0 = c * a.chunk_tokens;
+    if (t0 >= shared) return;  // workgroup-uniform
+    const int t1 = min(shared, t0 + a.chunk_tokens);  // the prefix's last chunk may be short
 
     const int seq0 = gs + (sub * kWaves + wave) * spw;
     const bool active = seq0 < ge;  // wave-uniform; idle waves still load their tile and meet the barriers
@@ -611,13 +620,15 @@ SD_DEV void shared_item(const SplitArgs &a, char *lds, int lane, int wave)
         P::template load_page<true>(r, 1, kbase + pb * page_bytes, vbase + pb * page_bytes, a.k_scales, a.v_scales,
                                     (int64_t)pb * a.Hkv + g, lane);
     };
-    const int rounds = a.chunk_tokens / (kWaves * kTileTokens);
+    const int rounds = (t1 - t0 + kWaves * kTileTokens - 1) / (kWaves * kTileTokens);
+    const int last_page = (t1 - t0) / kPage - 1;  // shared lengths are whole pages
     char *mine = lds + wave * kSlot;
     typename P::Tile r;
-    issue(r, bt[2 * wave], bt[2 * wave + 1]);  // round 0: this wave's tile is tile `wave`
+    // round 0: this wave's tile is tile `wave`; tiles past the end re-read the last page and are skipped below
+    issue(r, bt[min(2 * wave, last_page)], bt[min(2 * wave + 1, last_page)]);
     for (int rd = 0; rd < rounds; ++rd) {
         const int tn = kWaves * min(rd + 1, rounds - 1) + wave;
-        const int na = bt[2 * tn], nb = bt[2 * tn + 1];
+        const int na = bt[min(2 * tn, last_page)], nb = bt[min(2 * tn + 1, last_page)];
         P::k_store(r, mine, lane);
         P::v_store(r, mine + P::kScratchBytes, lane);
         if (rd + 1 < rounds) issue(r, na, nb);
@@ -625,6 +636,7 @@ SD_DEV void shared_item(const SplitArgs &a, char *lds, int lane, int wave)
         if (active) {
 #pragma unroll 1
             for (int j = 0; j < kWaves; ++j) {
+                if (t0 + (kWaves * rd + j) * kTileTokens >= t1) break;  // wave-uniform
                 const char *slot = lds + j * kSlot;
                 u32x4 ka[D / 32], kb[D / 32];
                 typename P::Tile t;
@@ -677,10 +689,12 @@ __global__ __launch_bounds__(kWaves * 64, 2) void split_kernel(SplitArgs a)
     const int c = item / (a.Hkv * a.B);
 
     const int L = min(a.context_lens[b], a.max_context_len);
-    const int t0 = c * a.chunk_tokens;
+    // slots of a shared prefix belong to the shared-prefix items; the others start where the prefix ends
+    const int shared = a.shared_len ? shared_tokens(a, b) : 0;
+    const int c_private = c - shared_slots(shared, a.chunk_tokens);
+    if (c_private < 0) return;
+    const int t0 = shared + c_private * a.chunk_tokens;
     if (t0 >= L) return;
-    // whole chunks inside a shared prefix belong to the shared-prefix items
-    if (a.shared_len && t0 + a.chunk_tokens <= min(a.shared_len[b], L)) return;
     const int t1 = min(L, t0 + a.chunk_tokens);
 
     // Q^T operand: lane&15 = head n; heads >= G are zero rows
@@ -735,7 +749,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void split_kernel(SplitArgs a)
 hipError_t launch_split(const SplitArgs &a, int head_dim, int kv_dtype, hipStream_t stream,
                         hipEvent_t start, hipEvent_t stop)
 {
-    const unsigned grid = a.group_items + (unsigned)a.S * (unsigned)a.B * (unsigned)a.Hkv;
+    const unsigned grid = a.group_items + (unsigned)a.grid_chunks * (unsigned)a.B * (unsigned)a.Hkv;
     if (grid == 0) return hipSuccess;
     const dim3 g(grid), b(kWaves * 64);
     if (kv_dtype == 0 && head_dim == 128)

@@ -12,6 +12,13 @@ constexpr int kWaves = 4;           // waves per workgroup of the split pass
 constexpr int kTileTokens = 32;     // tokens one wave consumes per iteration (two pages)
 constexpr int kMaxGroup = 16;       // query heads per KV head that fit one MFMA tile
 
+// Chunk slots of one output row.  Without a shared prefix, chunk c covers tokens
+// [c*chunk, (c+1)*chunk).  With a shared prefix of `sh` tokens (a multiple of
+// 16) the first ceil(sh/chunk) slots cover the prefix (the last one may be
+// short) and the following ones cover [sh + j*chunk, ...), so that the prefix
+// is cut at the same places for every member of a group.
+__host__ __device__ inline int shared_slots(int sh, int chunk) { return (sh + chunk - 1) / chunk; }
+
 // Arguments of the split-K pass (by value, lives in kernel-argument memory).
 struct SplitArgs {
     const uint16_t *q;           // [B][Hq][D] bf16
@@ -32,6 +39,8 @@ struct SplitArgs {
     const int32_t *shared_len;   // [B] tokens whose pages the sequence shares with its whole group
     int32_t num_groups, group_subs;  // group_subs: workgroups (4 x 16/G sequences each) that cover the largest group
     uint32_t group_items;        // grid entries that serve shared prefixes (they come first)
+    int32_t max_shared_len;      // host-known bound on shared_len[]; larger values are clamped to it
+    int32_t grid_chunks;         // chunk slots the plain part of the grid spans (S, or S-1 without groups)
 };
 
 struct MergeArgs {
@@ -39,6 +48,8 @@ struct MergeArgs {
     const int32_t *context_lens;
     float *out;                  // [B][Hq][D]
     int32_t B, Hq, S, chunk_tokens, max_context_len;
+    const int32_t *shared_len;   // [B] or null, as in SplitArgs
+    int32_t max_shared_len;
 };
 
 struct AppendArgs {
