@@ -61,11 +61,14 @@ def algorithmic_bytes(wl, chunk, include_append, unique=False):
 def stored_traffic(kernel_sources, workload_key):
     """HBM bytes per split launch from the committed counter summary, or None
     when the kernel source has changed since the counters were taken."""
-    path = os.path.join(ROOT, "profiles", "split_kernel_hbm_traffic.md")
-    try:
-        text = open(path).read()
-    except OSError:
-        return None
+    import glob
+
+    text = ""
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.md"))):
+        try:
+            text += open(path).read() + "\n"
+        except OSError:
+            pass
     h = hashlib.sha256()
     for s in kernel_sources:
         h.update(open(s, "rb").read())

@@ -3,7 +3,7 @@
 Usage (after the three profiler runs named in the summary's header):
     python -m paper_2508_11553_amd.profile_summary --workload 'configs[1]' \
         --kernel-trace gpurun_out/prof_kt --fetch gpurun_out/prof_fetch --write gpurun_out/prof_write \
-        > profiles/split_kernel_hbm_traffic.md
+        > profiles/split_kernel_config1.md
 
 FETCH_SIZE and WRITE_SIZE are reported by rocprofv3 in KiB per dispatch.  Each
 is scaled by what the same counter reads for a device-to-device copy of known
@@ -62,7 +62,8 @@ def main():
     ap.add_argument("--kernel-trace", required=True)
     ap.add_argument("--fetch", required=True)
     ap.add_argument("--write", required=True)
-    ap.add_argument("--bench-args", default="--steps 100 --warmup 10 --no-cpu-baseline")
+    ap.add_argument("--bench-args", default="--steps 100 --warmup 10 --no-cpu-baseline",
+                    help="arguments bench.py was given in the kernel-trace run (for the header)")
     ap.add_argument("--pmc-bench-args", default="--steps 20 --warmup 2 --no-cpu-baseline --copy-calibration")
     a = ap.parse_args()
 
