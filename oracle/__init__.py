@@ -171,3 +171,26 @@ def kv_append(k_new, v_new, seq_ids, positions, k_pages, v_pages, block_table):
     fn(ctypes.c_int(Hkv), ctypes.c_int(d), ctypes.c_int(block_table.shape[1]),
        ctypes.c_int(k_pages.dtype.itemsize), _p(k_new), _p(v_new), _p(seq_ids), _p(positions),
        ctypes.c_int(T), _p(k_pages), _p(v_pages), _p(block_table))
+
+
+def float_to_e4m3fn(y: float) -> int:
+    f = lib().oracle_float_to_e4m3fn
+    f.restype = ctypes.c_uint8
+    f.argtypes = [ctypes.c_float]
+    return int(f(float(y)))
+
+
+def kv_append_fp8(k_new, v_new, range_seq, range_start, range_row0, k_pages, v_pages, k_scales, v_scales, block_table):
+    """In-place quantising append of row ranges (bf16 rows [T][Hkv][d]) into fp8 pools and their scales."""
+    k_new, v_new = _c(k_new, np.uint16), _c(v_new, np.uint16)
+    range_seq, range_start, range_row0 = _c(range_seq, np.int32), _c(range_start, np.int32), _c(range_row0, np.int32)
+    block_table = _c(block_table, np.int32)
+    for a, t in ((k_pages, np.uint8), (v_pages, np.uint8), (k_scales, np.float32), (v_scales, np.float32)):
+        assert a.dtype == t and a.flags.c_contiguous and a.flags.writeable
+    T, Hkv, d = k_new.shape
+    assert range_row0.shape[0] == range_seq.shape[0] + 1 and int(range_row0[-1]) <= T
+    fn = lib().oracle_kv_append_fp8
+    fn.restype = None
+    fn(ctypes.c_int(Hkv), ctypes.c_int(d), ctypes.c_int(block_table.shape[1]), _p(k_new), _p(v_new), _p(range_seq),
+       _p(range_start), _p(range_row0), ctypes.c_int(range_seq.shape[0]), _p(k_pages), _p(v_pages), _p(k_scales),
+       _p(v_scales), _p(block_table))

@@ -103,3 +103,100 @@ void oracle_kv_append(int Hkv, int d, int max_blocks, int elem_bytes,
 #undef REAL
 #undef REAL_EXP
 #undef NAME
+
+/*
+ * Quantising append into fp8 pools (resuming a paused trajectory rewrites the
+ * KV of its stored tokens; with an fp8 cache the rows must be quantised as
+ * they are written).
+ *
+ * Encoding: nearest OCP e4m3fn value, ties to the even code, magnitudes above
+ * 448 saturate to 448; the sign is kept (also for zero).
+ */
+uint8_t oracle_float_to_e4m3fn(float y)
+{
+    uint8_t sign = signbit(y) ? 0x80 : 0;
+    float a = fabsf(y);
+    if (isnan(a)) return sign | 0x7F;
+    if (a >= 448.0f) return sign | 0x7E;
+    /* candidates are the 127 finite magnitudes, ascending with the code */
+    int best = 0;
+    float best_err = a; /* distance to code 0 */
+    for (int c = 1; c <= 0x7E; ++c) {
+        float v = oracle_e4m3fn_to_float((uint8_t)c);
+        float err = fabsf(v - a);
+        if (err < best_err || (err == best_err && (c & 1) == 0)) {
+            best = c;
+            best_err = err;
+        }
+    }
+    return sign | (uint8_t)best;
+}
+
+/*
+ * One range of consecutive positions of one sequence: rows row0 .. row0+n-1 of
+ * k_new/v_new ([T][Hkv][d] bf16) go to positions start .. start+n-1.  Per
+ * (page, kv head) tile touched, for K and for V alike:
+ *   s0 = first slot written (slots below it hold earlier tokens of the sequence
+ *        when the range starts inside the page; a range that starts a page
+ *        treats the page as fresh and ignores its old scale)
+ *   amax_new = max |x| over the rows written into the tile
+ *   old_amax = old_scale * 448 if s0 > 0 else 0
+ *   if amax_new <= old_amax: scale stays, old codes stay
+ *   else: scale = amax_new / 448 (fp32); each old code c in slots < s0 becomes
+ *         enc((dec(c) * old_scale) / scale), all in fp32
+ *   fresh tile with amax_new == 0: scale = 1
+ *   new codes: enc(x / scale) in fp32.
+ */
+void oracle_kv_append_fp8(int Hkv, int d, int max_blocks,
+                          const uint16_t *k_new, const uint16_t *v_new,
+                          const int32_t *range_seq, const int32_t *range_start,
+                          const int32_t *range_row0, int R,
+                          uint8_t *k_pages, uint8_t *v_pages, float *k_scales, float *v_scales,
+                          const int32_t *block_table)
+{
+    for (int r = 0; r < R; ++r) {
+        int seq = range_seq[r], start = range_start[r];
+        int n = range_row0[r + 1] - range_row0[r];
+        int end = start + n;
+        for (int pg = start / ORACLE_PAGE; pg * ORACLE_PAGE < end; ++pg) {
+            int64_t page = block_table[(int64_t)seq * max_blocks + pg];
+            int p0 = pg * ORACLE_PAGE;
+            int s0 = start > p0 ? start - p0 : 0;
+            int s1 = end < p0 + ORACLE_PAGE ? end - p0 : ORACLE_PAGE;
+            for (int g = 0; g < Hkv; ++g) {
+                for (int which = 0; which < 2; ++which) {
+                    const uint16_t *src = which ? v_new : k_new;
+                    uint8_t *tile = (which ? v_pages : k_pages) + ((int64_t)page * Hkv + g) * ORACLE_PAGE * d;
+                    float *scale_p = (which ? v_scales : k_scales) + (int64_t)page * Hkv + g;
+                    float amax_new = 0.0f;
+                    for (int s = s0; s < s1; ++s) {
+                        const uint16_t *row = src + ((int64_t)(range_row0[r] + p0 + s - start) * Hkv + g) * d;
+                        for (int i = 0; i < d; ++i) {
+                            float a = fabsf(oracle_bf16_to_float(row[i]));
+                            if (a > amax_new) amax_new = a;
+                        }
+                    }
+                    float old_scale = s0 > 0 ? *scale_p : 0.0f;
+                    float old_amax = old_scale * 448.0f;
+                    float scale;
+                    if (s0 > 0 && amax_new <= old_amax) {
+                        scale = old_scale;
+                    } else {
+                        scale = amax_new > 0.0f ? amax_new / 448.0f : 1.0f;
+                        for (int s = 0; s < s0; ++s)
+                            for (int i = 0; i < d; ++i) {
+                                float v = oracle_e4m3fn_to_float(tile[s * d + i]) * old_scale;
+                                tile[s * d + i] = oracle_float_to_e4m3fn(v / scale);
+                            }
+                        *scale_p = scale;
+                    }
+                    for (int s = s0; s < s1; ++s) {
+                        const uint16_t *row = src + ((int64_t)(range_row0[r] + p0 + s - start) * Hkv + g) * d;
+                        for (int i = 0; i < d; ++i)
+                            tile[s * d + i] = oracle_float_to_e4m3fn(oracle_bf16_to_float(row[i]) / scale);
+                    }
+                }
+            }
+        }
+    }
+}
