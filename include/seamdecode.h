@@ -105,13 +105,44 @@ size_t sd_workspace_bytes(const sd_shape *shape);
  *   positions      i32  [T]                    (device, read) in [0, 16*max_blocks_per_seq)
  *   k_pages,v_pages                            (device, written at the addressed slots only)
  *   block_table                                (device, read)
- * Only SD_BF16 pools are supported (SD_EUNSUPPORTED otherwise).  context_lens
+ * Only SD_BF16 pools are supported (SD_EUNSUPPORTED otherwise; see kv_append_fp8).  context_lens
  * is not touched: sequence state belongs to the caller.  Two rows that address
  * the same slot race.  T == 0 is a no-op.
  */
 int kv_append(const sd_shape *shape, const void *k_new, const void *v_new,
               const int32_t *seq_ids, const int32_t *positions, int32_t T,
               void *k_pages, void *v_pages, const int32_t *block_table, void *stream);
+
+/*
+ * kv_append_fp8 -- quantising append into SD_FP8_E4M3 pools (head_dim 128).
+ *
+ * Resuming a paused trajectory from its stored tokens (Data Plane: partial
+ * rollout) rewrites whole stretches of a sequence's cache, and a decode step
+ * adds one token; with an fp8 cache the rows are quantised as they are
+ * written.  Rows arrive as ranges: range r is the rows range_row0[r] ..
+ * range_row0[r+1]-1 of k_new/v_new (bf16 [T][num_kv_heads][128], device) and
+ * goes to positions range_start[r] .. of sequence range_seq[r].
+ *
+ * Per (page, KV head) tile a range touches, for K and V alike: the tile's
+ * scale is absmax/448 over its valid tokens.  If the range starts inside the
+ * page and its rows do not exceed the tile's current absmax (scale*448) the
+ * scale and the codes already there stay; otherwise the scale becomes the new
+ * rows' absmax/448 (1 if that is 0) and the codes before the range are
+ * re-encoded as (code*old_scale)/new_scale.  A range that starts a page treats
+ * the page as fresh, whatever its old scale.  Codes are the nearest e4m3fn
+ * value of x/scale (ties to even, saturating at +-448); all arithmetic fp32.
+ *
+ *   range_seq, range_start  i32 [num_ranges]      (device)
+ *   range_row0              i32 [num_ranges + 1]  (device), ascending
+ *   max_range_len           host-known bound on the rows of one range
+ * Two ranges of one call that touch the same page race.  context_lens is not
+ * touched.  Only SD_FP8_E4M3 shapes (SD_EUNSUPPORTED otherwise).
+ */
+int kv_append_fp8(const sd_shape *shape, const void *k_new, const void *v_new,
+                  const int32_t *range_seq, const int32_t *range_start, const int32_t *range_row0,
+                  int32_t num_ranges, int32_t max_range_len,
+                  void *k_pages, void *v_pages, float *k_scales, float *v_scales,
+                  const int32_t *block_table, void *stream);
 
 /*
  * paged_decode_attention -- one decode step of attention for every sequence.

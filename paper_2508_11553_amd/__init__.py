@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     KernelTimer,
     chunk_tokens,
     kv_append,
+    kv_append_fp8,
     lib_path,
     load,
     paged_decode_attention,

@@ -67,6 +67,8 @@ def load():
     L.paged_decode_attention.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, sz, vp]
     L.paged_decode_attention_timed.restype = ctypes.c_int
     L.paged_decode_attention_timed.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, sz, vp, vp]
+    L.kv_append_fp8.restype = ctypes.c_int
+    L.kv_append_fp8.argtypes = [sp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp]
     L.paged_decode_attention_prefix.restype = ctypes.c_int
     L.paged_decode_attention_prefix.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, vp, vp, sz,
                                                 vp, vp]
@@ -133,6 +135,14 @@ def kv_append(shape: Shape, k_new, v_new, seq_ids, positions, T: int, k_pages, v
     rc = load().kv_append(ctypes.byref(shape), _ptr(k_new), _ptr(v_new), _ptr(seq_ids), _ptr(positions), int(T),
                           _ptr(k_pages), _ptr(v_pages), _ptr(block_table), _stream(stream))
     _check(rc, "kv_append")
+
+
+def kv_append_fp8(shape: Shape, k_new, v_new, range_seq, range_start, range_row0, num_ranges: int,
+                  max_range_len: int, k_pages, v_pages, k_scales, v_scales, block_table, stream=None):
+    rc = load().kv_append_fp8(ctypes.byref(shape), _ptr(k_new), _ptr(v_new), _ptr(range_seq), _ptr(range_start),
+                              _ptr(range_row0), int(num_ranges), int(max_range_len), _ptr(k_pages), _ptr(v_pages),
+                              _ptr(k_scales), _ptr(v_scales), _ptr(block_table), _stream(stream))
+    _check(rc, "kv_append_fp8")
 
 
 class KernelTimer:

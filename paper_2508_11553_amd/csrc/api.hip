@@ -153,6 +153,39 @@ int kv_append(const sd_shape *shape, const void *k_new, const void *v_new,
     return e == hipSuccess ? SD_OK : hip_fail(e);
 }
 
+int kv_append_fp8(const sd_shape *shape, const void *k_new, const void *v_new, const int32_t *range_seq,
+                  const int32_t *range_start, const int32_t *range_row0, int32_t num_ranges,
+                  int32_t max_range_len, void *k_pages, void *v_pages, float *k_scales, float *v_scales,
+                  const int32_t *block_table, void *stream)
+{
+    const int rc = check_shape(shape);
+    if (rc) return rc;
+    if (num_ranges < 0 || max_range_len < 0) return SD_EINVAL;
+    if (shape->kv_dtype != SD_FP8_E4M3) return SD_EUNSUPPORTED;
+    if (num_ranges == 0 || max_range_len == 0) return SD_OK;
+    if (bad_ptr(k_new) || bad_ptr(v_new) || bad_ptr(range_seq) || bad_ptr(range_start) || bad_ptr(range_row0) ||
+        bad_ptr(k_pages) || bad_ptr(v_pages) || bad_ptr(k_scales) || bad_ptr(v_scales) || bad_ptr(block_table))
+        return SD_EINVAL;
+    sd::AppendFp8Args a;
+    a.k_new = static_cast<const uint4 *>(k_new);
+    a.v_new = static_cast<const uint4 *>(v_new);
+    a.range_seq = range_seq;
+    a.range_start = range_start;
+    a.range_row0 = range_row0;
+    a.k_pages = static_cast<uint8_t *>(k_pages);
+    a.v_pages = static_cast<uint8_t *>(v_pages);
+    a.k_scales = k_scales;
+    a.v_scales = v_scales;
+    a.block_table = block_table;
+    a.R = num_ranges;
+    a.Hkv = shape->num_kv_heads;
+    a.max_blocks = shape->max_blocks_per_seq;
+    a.pages_per_range = (max_range_len + sd::kPage - 1) / sd::kPage + 1;  // a range may start inside a page
+    const hipError_t e = sd::launch_append_fp8(a, static_cast<hipStream_t>(stream));
+    if (e == hipErrorNotSupported) return SD_EUNSUPPORTED;
+    return e == hipSuccess ? SD_OK : hip_fail(e);
+}
+
 int paged_decode_attention_prefix(const sd_shape *shape, const void *q, const void *k_pages,
                                   const void *v_pages, const float *k_scales, const float *v_scales,
                                   const int32_t *block_table, const int32_t *context_lens,

@@ -60,6 +60,15 @@ struct AppendArgs {
     int32_t T, Hkv, max_blocks;
 };
 
+struct AppendFp8Args {
+    const uint4 *k_new, *v_new;  // [T][Hkv][128] bf16 viewed as 16-byte words
+    const int32_t *range_seq, *range_start, *range_row0;  // [R], [R], [R+1]
+    uint8_t *k_pages, *v_pages;
+    float *k_scales, *v_scales;
+    const int32_t *block_table;
+    int32_t R, Hkv, max_blocks, pages_per_range;
+};
+
 struct ProbeArgs {
     const void *k_pages, *v_pages;
     const int32_t *block_table, *context_lens;
@@ -77,6 +86,7 @@ hipError_t launch_split(const SplitArgs &a, int head_dim, int kv_dtype, hipStrea
 hipError_t launch_merge(const MergeArgs &a, int head_dim, hipStream_t stream,
                         hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
 hipError_t launch_append(const AppendArgs &a, int head_dim, hipStream_t stream);
+hipError_t launch_append_fp8(const AppendFp8Args &a, hipStream_t stream);
 hipError_t launch_probe(const ProbeArgs &a, hipStream_t stream);
 
 }  // namespace sd

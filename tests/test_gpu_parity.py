@@ -420,3 +420,109 @@ def test_full_size_branching_mix_prefix_aware(sd):
     rows = sampled_rows(wl, 96)
     ref = oracle.attend_rows(wl.q, wl.k_pages, wl.v_pages, wl.block_table, wl.context_lens, wl.scale, rows)
     check(got[rows[:, 0], rows[:, 1]], ref)
+
+
+# ---------------------------------------------------------------- fp8 quantising append
+def _fp8_append_case(sd, ranges, Hkv=2, num_pages=12, seed=0, scales=(1.0,), prefill=None):
+    """Run the same range append on the device and in the oracle; both start from the same pool."""
+    import torch
+    from paper_2508_11553_amd import binding
+    from paper_2508_11553_amd.device import _to_dev
+    rng = np.random.default_rng(seed)
+    d = 128
+    nseq = max(r[0] for r in ranges) + 1
+    maxnb = 6
+    bt = rng.permutation(num_pages)[:nseq * maxnb].reshape(nseq, maxnb).astype(np.int32)
+    T = sum(r[2] for r in ranges)
+    mag = rng.choice(scales, size=(T, 1, 1))
+    kn = workloads.f32_to_bf16_bits((rng.standard_normal((T, Hkv, d)) * mag).astype(np.float32))
+    vn = workloads.f32_to_bf16_bits((rng.standard_normal((T, Hkv, d)) * mag[::-1]).astype(np.float32))
+    k = np.full((num_pages, Hkv, 16, d), 0x7F, np.uint8); v = k.copy()
+    ks = np.full((num_pages, Hkv), np.nan, np.float32); vs = ks.copy()
+    if prefill is not None:  # earlier tokens, written by the oracle on both sides
+        pk = workloads.f32_to_bf16_bits(rng.standard_normal((sum(p[2] for p in prefill), Hkv, d)).astype(np.float32))
+        oracle.kv_append_fp8(pk, pk, np.int32([p[0] for p in prefill]), np.int32([p[1] for p in prefill]),
+                             np.int32(np.concatenate([[0], np.cumsum([p[2] for p in prefill])])), k, v, ks, vs, bt)
+    rs, st = np.int32([r[0] for r in ranges]), np.int32([r[1] for r in ranges])
+    r0 = np.int32(np.concatenate([[0], np.cumsum([r[2] for r in ranges])]))
+    shape = sd.Shape(batch=nseq, num_q_heads=Hkv, num_kv_heads=Hkv, head_dim=d, page_size=16, num_pages=num_pages,
+                     max_blocks_per_seq=maxnb, kv_dtype=sd.SD_FP8_E4M3, max_context_len=16 * maxnb, chunk_tokens=0)
+    dev = "cuda:0"
+    dk, dv, dks, dvs = _to_dev(k, dev), _to_dev(v, dev), _to_dev(ks, dev), _to_dev(vs, dev)
+    binding.kv_append_fp8(shape, _to_dev(kn, dev), _to_dev(vn, dev), _to_dev(rs, dev), _to_dev(st, dev), _to_dev(r0, dev),
+                          len(ranges), max(r[2] for r in ranges), dk, dv, dks, dvs, _to_dev(bt, dev))
+    torch.cuda.synchronize()
+    oracle.kv_append_fp8(kn, vn, rs, st, r0, k, v, ks, vs, bt)
+    assert np.array_equal(dk.cpu().numpy(), k) and np.array_equal(dv.cpu().numpy(), v)
+    assert np.array_equal(dks.cpu().numpy().view(np.uint32), ks.view(np.uint32))
+    assert np.array_equal(dvs.cpu().numpy().view(np.uint32), vs.view(np.uint32))
+
+
+def test_fp8_append_fresh_ranges_bit_exact(sd):
+    _fp8_append_case(sd, [(0, 0, 96), (1, 0, 1), (2, 0, 17)], num_pages=20, seed=1, scales=(1.0, 0.01, 30.0))
+
+
+def test_fp8_append_into_partly_filled_pages_bit_exact(sd):
+    # sequence 0 holds 5 tokens, 1 holds 21, 2 holds 16 (next append opens a page)
+    pre = [(0, 0, 5), (1, 0, 21), (2, 0, 16)]
+    _fp8_append_case(sd, [(0, 5, 3), (1, 21, 40), (2, 16, 1)], num_pages=20, seed=2, scales=(0.05, 1.0, 8.0), prefill=pre)
+    _fp8_append_case(sd, [(0, 5, 1), (1, 21, 1), (2, 16, 1)], num_pages=20, seed=3, scales=(0.05,), prefill=pre)   # no growth
+    _fp8_append_case(sd, [(0, 5, 1), (1, 21, 1), (2, 16, 1)], num_pages=20, seed=4, scales=(40.0,), prefill=pre)   # growth
+
+
+def test_fp8_append_encoder_matches_the_oracle_on_every_bf16_magnitude(sd):
+    """One page whose first row pins the scale to 1 (a 448 in it); the other rows sweep bf16 values
+    across every binade the format covers, including exact ties between neighbouring codes."""
+    import torch
+    from paper_2508_11553_amd import binding
+    from paper_2508_11553_amd.device import _to_dev
+    d, Hkv = 128, 1
+    vals = []
+    for e in range(-12, 9):
+        for m in range(0, 128, 1):
+            vals.append((1 + m / 128.0) * 2.0 ** e)
+    vals = np.float32(vals)[:15 * d]
+    x = np.zeros((16, Hkv, d), np.float32)
+    x[0, 0, 0] = 448.0
+    x[1:, 0, :].flat[:len(vals)] = vals
+    x[1::2] *= -1
+    kn = workloads.f32_to_bf16_bits(x)
+    bt = np.int32([[0]])
+    k = np.zeros((1, Hkv, 16, d), np.uint8); v = k.copy(); ks = np.zeros((1, Hkv), np.float32); vs = ks.copy()
+    shape = sd.Shape(batch=1, num_q_heads=1, num_kv_heads=1, head_dim=d, page_size=16, num_pages=1,
+                     max_blocks_per_seq=1, kv_dtype=sd.SD_FP8_E4M3, max_context_len=16, chunk_tokens=0)
+    dev = "cuda:0"
+    dk, dv, dks, dvs = _to_dev(k, dev), _to_dev(v, dev), _to_dev(ks, dev), _to_dev(vs, dev)
+    binding.kv_append_fp8(shape, _to_dev(kn, dev), _to_dev(kn, dev), _to_dev(np.int32([0]), dev), _to_dev(np.int32([0]), dev),
+                          _to_dev(np.int32([0, 16]), dev), 1, 16, dk, dv, dks, dvs, _to_dev(bt, dev))
+    torch.cuda.synchronize()
+    oracle.kv_append_fp8(kn, kn, np.int32([0]), np.int32([0]), np.int32([0, 16]), k, v, ks, vs, bt)
+    assert ks[0, 0] == 1.0
+    assert np.array_equal(dk.cpu().numpy(), k) and np.array_equal(dv.cpu().numpy(), v)
+
+
+def test_fp8_resume_then_attend(sd):
+    """Rebuild an fp8 cache from bf16 rows in one bulk call per sequence, then attend: the result must match
+    the oracle run over the oracle-built pool."""
+    import torch
+    from paper_2508_11553_amd import binding
+    from paper_2508_11553_amd.device import _to_dev
+    src = workloads.make_custom([700, 33, 1500], 16, 2, 128, "bf16", seed=30, poison=False)
+    rows_k, rows_v = [], []
+    for b, L in enumerate(src.context_lens):
+        t = np.arange(L)
+        rows_k.append(src.k_pages[src.block_table[b, t // 16], :, t % 16]); rows_v.append(src.v_pages[src.block_table[b, t // 16], :, t % 16])
+    kn, vn = np.concatenate(rows_k), np.concatenate(rows_v)
+    r0 = np.int32(np.concatenate([[0], np.cumsum(src.context_lens)]))
+    wl = workloads.make_custom(src.context_lens, 16, 2, 128, "fp8", seed=31)  # same table shape; pools get overwritten
+    wl.q, wl.block_table = src.q, src.block_table
+    wl.k_pages[:] = 0x7F; wl.v_pages[:] = 0x7F; wl.k_scales[:] = np.nan; wl.v_scales[:] = np.nan
+    dw = device_workload(wl)
+    binding.kv_append_fp8(dw.shape, _to_dev(kn, dw.device), _to_dev(vn, dw.device), _to_dev(np.int32([0, 1, 2]), dw.device),
+                          _to_dev(np.int32([0, 0, 0]), dw.device), _to_dev(r0, dw.device), 3, int(src.context_lens.max()),
+                          dw.k_pages, dw.v_pages, dw.k_scales, dw.v_scales, dw.block_table)
+    out = dw.attend()
+    torch.cuda.synchronize()
+    oracle.kv_append_fp8(kn, vn, np.int32([0, 1, 2]), np.int32([0, 0, 0]), r0, wl.k_pages, wl.v_pages, wl.k_scales, wl.v_scales, wl.block_table)
+    assert np.array_equal(dw.k_pages.cpu().numpy(), wl.k_pages) and np.array_equal(dw.v_pages.cpu().numpy(), wl.v_pages)
+    check_fp8(out.cpu().numpy(), oracle_full(wl))
