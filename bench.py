@@ -2,8 +2,9 @@
 """Decode-attention benchmark for libseamdecode on one MI355X.
 
 One step = one pass of the whole hot path over one batch: kv_append of one
-new token per sequence (bf16 workloads), then paged_decode_attention (split-K
-pass + merge pass).  Inputs are synthetic, seeded and resident in HBM before
+new token per sequence (kv_append_fp8 for fp8 pools), then
+paged_decode_attention (split-K pass + merge pass; the shared-prefix aware
+entry point for the branching workload).  Inputs are synthetic, seeded and resident in HBM before
 the timed region.  Workloads whose K/V pool is small enough to sit in the
 256 MB memory-side cache are rotated over several independent pools.
 
@@ -54,7 +55,8 @@ def algorithmic_bytes(wl, chunk, include_append, unique=False):
     merge = partials + out + wl.batch * 4
     append = 0
     if include_append and wl.k_new is not None:
-        append = 2 * 2 * wl.k_new.size * 2 + wl.k_new.shape[0] * 12
+        # rows read (bf16) and written (bf16 or fp8 codes), K and V, plus the index arrays
+        append = 2 * wl.k_new.size * (2 + wl.kv_elem_bytes) + wl.k_new.shape[0] * 12
     return {"split": split, "merge": merge, "append": append, "step": split + merge + append, "kv": kv}
 
 
@@ -151,7 +153,7 @@ def main():
     torch.cuda.set_device(0)
     cfg = args.config
     t_gen = time.perf_counter()
-    do_append = (not args.no_append) and cfg != 4
+    do_append = not args.no_append
     wl = workloads.make_config(cfg, append=do_append)
     pool_bytes = 2 * wl.k_pages.nbytes
     npools = args.pools or (4 if pool_bytes < SMALL_POOL_BYTES else 1)

@@ -43,9 +43,9 @@ hipError_t launch_append(const AppendArgs &a, int head_dim, hipStream_t stream)
 // Quantising append into fp8 e4m3fn pools (head_dim 128).
 //
 // Rows arrive as ranges of consecutive positions of one sequence.  One
-// workgroup owns one (range, page touched by the range, KV head, K or V) tile:
-// thread t handles 8 elements, slot t/16, d = 8*(t%16)..+8.
-//   amax_new over the rows written into the tile        (block max, exact)
+// wave owns one (range, page touched by the range, KV head, K or V) tile:
+// lane l handles 32 elements, slot l/4, d = 32*(l%4)..+32.
+//   amax_new over the rows written into the tile        (wave max, exact)
 //   the tile's scale stays if the range starts inside the page and
 //   amax_new <= old_scale*448; otherwise scale = amax_new/448 (1 if 0) and the
 //   codes of the slots before the range are re-encoded as (dec*old_scale)/scale
@@ -70,66 +70,81 @@ __device__ __forceinline__ unsigned enc4(float a, float b, float c, float d)
     return w;
 }
 
-__global__ __launch_bounds__(256) void append_fp8_kernel(AppendFp8Args a)
+__global__ __launch_bounds__(64) void append_fp8_kernel(AppendFp8Args a)
 {
     constexpr int D = 128;
-    __shared__ float s_max[4];
-    const int tid = threadIdx.x;
+    const int lane = threadIdx.x;
     const int which = blockIdx.x & 1;                 // 0: K, 1: V
     const int g = (blockIdx.x >> 1) % a.Hkv;
     const int pi = (blockIdx.x >> 1) / a.Hkv % a.pages_per_range;
     const int r = (blockIdx.x >> 1) / a.Hkv / a.pages_per_range;
-    const int seq = a.range_seq[r], start = a.range_start[r], row0 = a.range_row0[r];
+    const int start = a.range_start[r], row0 = a.range_row0[r];
     const int end = start + (a.range_row0[r + 1] - row0);
     const int pg = start / kPage + pi;
     const int p0 = pg * kPage;
-    if (p0 >= end) return;  // workgroup-uniform
+    if (p0 >= end) return;  // wave-uniform
+    const int seq = a.range_seq[r];
     const int s0 = max(start - p0, 0), s1 = min(end - p0, kPage);
     const int64_t page = a.block_table[(int64_t)seq * a.max_blocks + pg];
     const int64_t tile_index = page * a.Hkv + g;
-    uint2 *tile = reinterpret_cast<uint2 *>((which ? a.v_pages : a.k_pages) + tile_index * (kPage * D));
+    uint4 *tile = reinterpret_cast<uint4 *>((which ? a.v_pages : a.k_pages) + tile_index * (kPage * D));
     float *scale_p = (which ? a.v_scales : a.k_scales) + tile_index;
     const uint4 *src = which ? a.v_new : a.k_new;
 
-    const int slot = tid >> 4, piece = tid & 15;
+    // one wave per tile: lane -> slot lane/4, d = 32*(lane%4) .. +32
+    const int slot = lane >> 2, quarter = lane & 3;
     const bool is_new = slot >= s0 && slot < s1;
-    float x[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    float x[32];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) x[i] = 0.f;
     if (is_new) {
         const int64_t row = row0 + (p0 + slot - start);
-        const uint4 w = src[(row * a.Hkv + g) * (D / 8) + piece];
-        x[0] = bf16_lo(w.x); x[1] = bf16_hi(w.x); x[2] = bf16_lo(w.y); x[3] = bf16_hi(w.y);
-        x[4] = bf16_lo(w.z); x[5] = bf16_hi(w.z); x[6] = bf16_lo(w.w); x[7] = bf16_hi(w.w);
-    }
-    float m = 0.f;
+        const uint4 *p = src + (row * a.Hkv + g) * (D / 8) + quarter * 4;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) m = fmaxf(m, fabsf(x[i]));
-    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
-    if ((tid & 63) == 0) s_max[tid >> 6] = m;
-    __syncthreads();
-    const float amax_new = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
+        for (int j = 0; j < 4; ++j) {
+            const uint4 w = p[j];
+            x[8 * j + 0] = bf16_lo(w.x); x[8 * j + 1] = bf16_hi(w.x); x[8 * j + 2] = bf16_lo(w.y); x[8 * j + 3] = bf16_hi(w.y);
+            x[8 * j + 4] = bf16_lo(w.z); x[8 * j + 5] = bf16_hi(w.z); x[8 * j + 6] = bf16_lo(w.w); x[8 * j + 7] = bf16_hi(w.w);
+        }
+    }
+    float amax_new = 0.f;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) amax_new = fmaxf(amax_new, fabsf(x[i]));
+    for (int off = 32; off > 0; off >>= 1) amax_new = fmaxf(amax_new, __shfl_xor(amax_new, off, 64));
 
     const float old_scale = s0 > 0 ? *scale_p : 0.f;
     const float old_amax = old_scale * 448.0f;
     const bool keep = s0 > 0 && amax_new <= old_amax;
     const float scale = keep ? old_scale : (amax_new > 0.f ? amax_new / 448.0f : 1.0f);
-    __syncthreads();  // every thread has read the old scale before it is replaced
     if (!keep) {
         if (slot < s0) {  // re-encode what the page already held
-            const uint2 c = tile[slot * (D / 8) + piece];
-            const f32x2 a0 = __builtin_amdgcn_cvt_pk_f32_fp8(c.x, false), a1 = __builtin_amdgcn_cvt_pk_f32_fp8(c.x, true);
-            const f32x2 b0 = __builtin_amdgcn_cvt_pk_f32_fp8(c.y, false), b1 = __builtin_amdgcn_cvt_pk_f32_fp8(c.y, true);
-            uint2 o;
-            o.x = enc4((a0[0] * old_scale) / scale, (a0[1] * old_scale) / scale, (a1[0] * old_scale) / scale, (a1[1] * old_scale) / scale);
-            o.y = enc4((b0[0] * old_scale) / scale, (b0[1] * old_scale) / scale, (b1[0] * old_scale) / scale, (b1[1] * old_scale) / scale);
-            tile[slot * (D / 8) + piece] = o;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const uint4 c = tile[slot * (D / 16) + quarter * 2 + j];
+                const unsigned in[4] = {c.x, c.y, c.z, c.w};
+                unsigned o[4];
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(in[w], false), hi = __builtin_amdgcn_cvt_pk_f32_fp8(in[w], true);
+                    o[w] = enc4((lo[0] * old_scale) / scale, (lo[1] * old_scale) / scale, (hi[0] * old_scale) / scale,
+                                (hi[1] * old_scale) / scale);
+                }
+                tile[slot * (D / 16) + quarter * 2 + j] = uint4{o[0], o[1], o[2], o[3]};
+            }
         }
-        if (tid == 0) *scale_p = scale;
+        if (lane == 0) *scale_p = scale;  // every lane has read the old scale: one wave runs in lockstep
     }
     if (is_new) {
-        uint2 o;
-        o.x = enc4(x[0] / scale, x[1] / scale, x[2] / scale, x[3] / scale);
-        o.y = enc4(x[4] / scale, x[5] / scale, x[6] / scale, x[7] / scale);
-        tile[slot * (D / 8) + piece] = o;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            unsigned o[4];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const int e = 16 * j + 4 * w;
+                o[w] = enc4(x[e] / scale, x[e + 1] / scale, x[e + 2] / scale, x[e + 3] / scale);
+            }
+            tile[slot * (D / 16) + quarter * 2 + j] = uint4{o[0], o[1], o[2], o[3]};
+        }
     }
 }
 
@@ -138,7 +153,7 @@ hipError_t launch_append_fp8(const AppendFp8Args &a, hipStream_t stream)
     const uint64_t grid = 2ull * (uint64_t)a.R * (uint64_t)a.pages_per_range * (uint64_t)a.Hkv;
     if (grid == 0) return hipSuccess;
     if (grid > 0x7fffffffull) return hipErrorNotSupported;
-    hipLaunchKernelGGL(append_fp8_kernel, dim3((unsigned)grid), dim3(256), 0, stream, a);
+    hipLaunchKernelGGL(append_fp8_kernel, dim3((unsigned)grid), dim3(64), 0, stream, a);
     return hipGetLastError();
 }
 

@@ -41,6 +41,8 @@ class DeviceWorkload:
             self.k_new, self.v_new = _to_dev(wl.k_new, self.device), _to_dev(wl.v_new, self.device)
             self.seq_ids, self.positions = _to_dev(wl.seq_ids, self.device), _to_dev(wl.positions, self.device)
             self.T = int(wl.k_new.shape[0])
+            # the same rows as ranges of one token each, for the fp8 append
+            self.range_row0 = _to_dev(np.arange(self.T + 1, dtype=np.int32), self.device)
         self.group_start = self.shared_len = None
         self.num_groups = self.max_group_size = self.max_shared_len = 0
         if getattr(wl, "group_start", None) is not None:
@@ -62,6 +64,11 @@ class DeviceWorkload:
         return sd.chunk_tokens(self.shape)
 
     def append(self, stream=None):
+        if self.shape.kv_dtype == sd.SD_FP8_E4M3:
+            sd.kv_append_fp8(self.shape, self.k_new, self.v_new, self.seq_ids, self.positions, self.range_row0,
+                             self.T, 1, self.k_pages, self.v_pages, self.k_scales, self.v_scales, self.block_table,
+                             stream)
+            return
         sd.kv_append(self.shape, self.k_new, self.v_new, self.seq_ids, self.positions, self.T,
                      self.k_pages, self.v_pages, self.block_table, stream)
 

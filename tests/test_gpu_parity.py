@@ -526,3 +526,19 @@ def test_fp8_resume_then_attend(sd):
     oracle.kv_append_fp8(kn, vn, np.int32([0, 1, 2]), np.int32([0, 0, 0]), r0, wl.k_pages, wl.v_pages, wl.k_scales, wl.v_scales, wl.block_table)
     assert np.array_equal(dw.k_pages.cpu().numpy(), wl.k_pages) and np.array_equal(dw.v_pages.cpu().numpy(), wl.v_pages)
     check_fp8(out.cpu().numpy(), oracle_full(wl))
+
+
+def test_fp8_decode_step_append_then_attend(sd):
+    """One decode step on an fp8 cache: quantising append of one token per sequence, then attention."""
+    import torch
+    wl = workloads.make_custom([17, 33, 5, 16, 700, 1025], 16, 2, 128, "fp8", seed=33, append=True)
+    dw = device_workload(wl)
+    dw.append()
+    out = dw.attend()
+    torch.cuda.synchronize()
+    k, v, ks, vs = wl.k_pages, wl.v_pages, wl.k_scales, wl.v_scales
+    oracle.kv_append_fp8(wl.k_new, wl.v_new, wl.seq_ids, wl.positions, np.arange(len(wl.seq_ids) + 1, dtype=np.int32),
+                         k, v, ks, vs, wl.block_table)
+    assert np.array_equal(dw.k_pages.cpu().numpy(), k) and np.array_equal(dw.v_pages.cpu().numpy(), v)
+    assert np.array_equal(dw.k_scales.cpu().numpy().view(np.uint32), ks.view(np.uint32))
+    check_fp8(out.cpu().numpy(), oracle_full(wl))

@@ -220,10 +220,20 @@ def build_paged(
         phys = block_table[b, :n]
         valid[phys] = np.maximum(valid[phys], cnt)
 
+    # tokens actually stored before the call: with a staged append the last token of each
+    # sequence is not in the pool yet (fp8 scales are taken over the stored tokens only)
+    stored = valid
+    if append:
+        stored = valid.copy()
+        for b in range(B):
+            if lens[b] > 0:
+                last = block_table[b, (lens[b] - 1) // PAGE]
+                stored[last] = min(stored[last], (lens[b] - 1) % PAGE)
+
     # ---- draws ---------------------------------------------------------------
     q = f32_to_bf16_bits(_rng(seed, _TAG_Q).standard_normal((B, Hq, d), dtype=np.float32))
-    k_pages, k_scales = _draw_pool(seed, _TAG_K, num_pages, Hkv, d, kv_dtype, valid, threads)
-    v_pages, v_scales = _draw_pool(seed, _TAG_V, num_pages, Hkv, d, kv_dtype, valid, threads)
+    k_pages, k_scales = _draw_pool(seed, _TAG_K, num_pages, Hkv, d, kv_dtype, stored, threads)
+    v_pages, v_scales = _draw_pool(seed, _TAG_V, num_pages, Hkv, d, kv_dtype, stored, threads)
 
     # prefix tails that do not fill a page: same bytes in every branch
     if session_of is not None:
@@ -251,7 +261,7 @@ def build_paged(
         wl.shared_len = (shared_pages * PAGE).astype(np.int32)
 
     if append:
-        assert kv_dtype == "bf16", "the staged append is bf16 only"
+        assert session_of is None or kv_dtype == "bf16"
         rows = np.nonzero(lens > 0)[0]
         r = _rng(seed, _TAG_APPEND)
         wl.k_new = f32_to_bf16_bits(r.standard_normal((len(rows), Hkv, d), dtype=np.float32))
@@ -267,8 +277,8 @@ def build_paged(
             k_pages[p, :, valid[p]:] = nan
             v_pages[p, :, valid[p]:] = nan
         if k_scales is not None:
-            k_scales[valid == 0] = np.nan
-            v_scales[valid == 0] = np.nan
+            k_scales[stored == 0] = np.nan
+            v_scales[stored == 0] = np.nan
         if append:
             for b, pos in zip(wl.seq_ids, wl.positions):
                 p = block_table[b, pos // PAGE]
