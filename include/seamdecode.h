@@ -211,6 +211,48 @@ int paged_decode_attention_prefix(const sd_shape *shape, const void *q,
                                   struct sd_timer *timer);
 
 /*
+ * Session prefix tree (host only; no device memory, no HIP calls).
+ *
+ * The Trajectory Manager keeps the trajectories of a session in a prefix tree
+ * built by longest-prefix matching and tags every token with the model version
+ * that produced it (Data Plane, Trajectory Manager paragraph).  sd_tree does
+ * that bookkeeping at KV-page granularity: trajectories share the physical
+ * page of a full 16-token page exactly when all their tokens and version tags
+ * up to the end of that page are equal; a partly filled last page is private.
+ * The tree owns the page ids 0 .. num_pages-1 of a pool (free list, reference
+ * counts) and emits block-table rows and the group arrays of
+ * paged_decode_attention_prefix.  Not thread-safe: one tree, one thread.
+ *
+ *   sd_tree_insert        stores tokens[n] (+ versions[n], NULL = all 0); returns
+ *                         the trajectory id (>= 0), SD_EINVAL, or SD_EWORKSPACE when
+ *                         the pool is out of pages.  *matched_tokens (optional) =
+ *                         leading tokens whose pages already existed: K/V has to be
+ *                         appended from that position on only.
+ *   sd_tree_match         the same count without storing anything
+ *   sd_tree_release       drops a trajectory; unreferenced pages return to the pool
+ *   sd_tree_block_table   writes min(pages, cap) page ids, returns the page count
+ *   sd_tree_token_at      token id / model version stored at a position
+ *   sd_tree_batch_groups  for trajectories in batch order: consecutive ones that
+ *                         start with the same page form a group; fills
+ *                         group_start_out[groups + 1] and shared_len_out[B] (16 x the
+ *                         pages common to the whole group, 0 for groups of one);
+ *                         returns the number of groups
+ */
+typedef struct sd_tree sd_tree;
+sd_tree *sd_tree_create(int32_t num_pages);
+void sd_tree_destroy(sd_tree *t);
+int32_t sd_tree_pages_in_use(const sd_tree *t);
+int32_t sd_tree_match(const sd_tree *t, const int32_t *tokens, const uint32_t *versions, int32_t n);
+int32_t sd_tree_insert(sd_tree *t, const int32_t *tokens, const uint32_t *versions, int32_t n,
+                       int32_t *matched_tokens);
+int sd_tree_release(sd_tree *t, int32_t traj);
+int32_t sd_tree_length(const sd_tree *t, int32_t traj);
+int32_t sd_tree_block_table(const sd_tree *t, int32_t traj, int32_t *pages_out, int32_t cap);
+int sd_tree_token_at(const sd_tree *t, int32_t traj, int32_t pos, int32_t *token, uint32_t *version);
+int32_t sd_tree_batch_groups(const sd_tree *t, const int32_t *trajs, int32_t B, int32_t *group_start_out,
+                             int32_t *shared_len_out);
+
+/*
  * Measurement aids (not part of the decode step).
  *
  * sd_timer owns HIP events (host objects; no device memory).  The _timed
