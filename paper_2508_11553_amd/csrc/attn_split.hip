@@ -683,18 +683,23 @@ __global__ __launch_bounds__(kWaves * 64, 2) void split_kernel(SplitArgs a)
     float (*s_m)[kMaxGroup] = reinterpret_cast<float (*)[kMaxGroup]>(lds + kWaves * P::kScratchBytes + kWaves * kMaxGroup * kRow * 4);
     float (*s_l)[kMaxGroup] = s_m + kWaves;
 
-    const unsigned item = blockIdx.x - a.group_items;  // (chunk, sequence, kv head), kv head fastest
+    // (chunk counted from the sequence's end, sequence, kv head), kv head fastest.  The grid
+    // walks the chunks of every sequence from the front, aligned at the END: its last rows
+    // hold every sequence's last chunk, which is the short one, so the workgroups that run
+    // while the machine drains are the small ones.
+    const unsigned item = blockIdx.x - a.group_items;
     const int g = item % a.Hkv;
     const int b = (item / a.Hkv) % a.B;
-    const int c = item / (a.Hkv * a.B);
+    const int from_end = a.grid_chunks - 1 - (int)(item / (a.Hkv * a.B));
 
     const int L = min(a.context_lens[b], a.max_context_len);
     // slots of a shared prefix belong to the shared-prefix items; the others start where the prefix ends
     const int shared = a.shared_len ? shared_tokens(a, b) : 0;
-    const int c_private = c - shared_slots(shared, a.chunk_tokens);
+    const int n_private = (L - shared + a.chunk_tokens - 1) / a.chunk_tokens;
+    const int c_private = n_private - 1 - from_end;
     if (c_private < 0) return;
+    const int c = shared_slots(shared, a.chunk_tokens) + c_private;  // slot of this chunk
     const int t0 = shared + c_private * a.chunk_tokens;
-    if (t0 >= L) return;
     const int t1 = min(L, t0 + a.chunk_tokens);
 
     // Q^T operand: lane&15 = head n; heads >= G are zero rows
