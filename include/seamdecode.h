@@ -128,7 +128,7 @@ int kv_append(const sd_shape *shape, const void *k_new, const void *v_new,
  * page and its rows do not exceed the tile's current absmax (scale*448) the
  * scale and the codes already there stay; otherwise the scale becomes the new
  * rows' absmax/448 (1 if that is 0) and the codes before the range are
- * re-encoded as (code*old_scale)/new_scale.  A range that starts a page treats
+ * re-encoded as code*(old_scale/new_scale).  A range that starts a page treats
  * the page as fresh, whatever its old scale.  Codes are the nearest e4m3fn
  * value of x/scale (ties to even, saturating at +-448); all arithmetic fp32.
  *

@@ -143,7 +143,7 @@ uint8_t oracle_float_to_e4m3fn(float y)
  *   old_amax = old_scale * 448 if s0 > 0 else 0
  *   if amax_new <= old_amax: scale stays, old codes stay
  *   else: scale = amax_new / 448 (fp32); each old code c in slots < s0 becomes
- *         enc((dec(c) * old_scale) / scale), all in fp32
+ *         enc(dec(c) * (old_scale / scale)), all in fp32: one ratio per tile
  *   fresh tile with amax_new == 0: scale = 1
  *   new codes: enc(x / scale) in fp32.
  */
@@ -183,11 +183,10 @@ void oracle_kv_append_fp8(int Hkv, int d, int max_blocks,
                         scale = old_scale;
                     } else {
                         scale = amax_new > 0.0f ? amax_new / 448.0f : 1.0f;
+                        float ratio = old_scale / scale;
                         for (int s = 0; s < s0; ++s)
-                            for (int i = 0; i < d; ++i) {
-                                float v = oracle_e4m3fn_to_float(tile[s * d + i]) * old_scale;
-                                tile[s * d + i] = oracle_float_to_e4m3fn(v / scale);
-                            }
+                            for (int i = 0; i < d; ++i)
+                                tile[s * d + i] = oracle_float_to_e4m3fn(oracle_e4m3fn_to_float(tile[s * d + i]) * ratio);
                         *scale_p = scale;
                     }
                     for (int s = s0; s < s1; ++s) {

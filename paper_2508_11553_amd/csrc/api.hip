@@ -180,7 +180,11 @@ int kv_append_fp8(const sd_shape *shape, const void *k_new, const void *v_new, c
     a.R = num_ranges;
     a.Hkv = shape->num_kv_heads;
     a.max_blocks = shape->max_blocks_per_seq;
-    a.pages_per_range = (max_range_len + sd::kPage - 1) / sd::kPage + 1;  // a range may start inside a page
+    a.pages_per_range = (max_range_len + sd::kPage - 2) / sd::kPage + 1;  // a range may start inside a page
+    const uint64_t tiles = 2ull * (uint64_t)num_ranges * (uint64_t)a.pages_per_range * (uint64_t)a.Hkv;
+    if (tiles > 0x7fffffffull) return SD_EUNSUPPORTED;
+    a.num_tiles = (uint32_t)tiles;
+    a.single_rows = max_range_len == 1;
     const hipError_t e = sd::launch_append_fp8(a, static_cast<hipStream_t>(stream));
     if (e == hipErrorNotSupported) return SD_EUNSUPPORTED;
     return e == hipSuccess ? SD_OK : hip_fail(e);

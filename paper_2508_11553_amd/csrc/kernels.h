@@ -67,6 +67,8 @@ struct AppendFp8Args {
     float *k_scales, *v_scales;
     const int32_t *block_table;
     int32_t R, Hkv, max_blocks, pages_per_range;
+    uint32_t num_tiles;          // 2 * R * pages_per_range * Hkv (K and V tiles)
+    int32_t single_rows;         // every range has at most one row (the decode step)
 };
 
 struct ProbeArgs {

@@ -43,12 +43,12 @@ hipError_t launch_append(const AppendArgs &a, int head_dim, hipStream_t stream)
 // Quantising append into fp8 e4m3fn pools (head_dim 128).
 //
 // Rows arrive as ranges of consecutive positions of one sequence.  One
-// wave owns one (range, page touched by the range, KV head, K or V) tile:
+// wave (four to a workgroup) owns one (range, page touched by the range, KV head, K or V) tile:
 // lane l handles 32 elements, slot l/4, d = 32*(l%4)..+32.
 //   amax_new over the rows written into the tile        (wave max, exact)
 //   the tile's scale stays if the range starts inside the page and
 //   amax_new <= old_scale*448; otherwise scale = amax_new/448 (1 if 0) and the
-//   codes of the slots before the range are re-encoded as (dec*old_scale)/scale
+//   codes of the slots before the range are re-encoded as dec*(old_scale/scale)
 //   new codes = enc(x/scale): v_cvt_pk_fp8_f32 (round-to-nearest-even) after
 //   clamping to +-448.
 // A range that starts a page treats it as fresh and ignores its old scale.
@@ -70,14 +70,17 @@ __device__ __forceinline__ unsigned enc4(float a, float b, float c, float d)
     return w;
 }
 
-__global__ __launch_bounds__(64) void append_fp8_kernel(AppendFp8Args a)
+__global__ __launch_bounds__(256) void append_fp8_kernel(AppendFp8Args a)
 {
     constexpr int D = 128;
-    const int lane = threadIdx.x;
-    const int which = blockIdx.x & 1;                 // 0: K, 1: V
-    const int g = (blockIdx.x >> 1) % a.Hkv;
-    const int pi = (blockIdx.x >> 1) / a.Hkv % a.pages_per_range;
-    const int r = (blockIdx.x >> 1) / a.Hkv / a.pages_per_range;
+    const int lane = threadIdx.x & 63;
+    // four independent waves per workgroup (no barrier below), one tile each
+    const unsigned tile_id = blockIdx.x * 4u + (threadIdx.x >> 6);
+    if (tile_id >= a.num_tiles) return;
+    const int which = tile_id & 1;                    // 0: K, 1: V
+    const int g = (tile_id >> 1) % a.Hkv;
+    const int pi = (tile_id >> 1) / a.Hkv % a.pages_per_range;
+    const int r = (tile_id >> 1) / a.Hkv / a.pages_per_range;
     const int start = a.range_start[r], row0 = a.range_row0[r];
     const int end = start + (a.range_row0[r + 1] - row0);
     const int pg = start / kPage + pi;
@@ -116,6 +119,7 @@ __global__ __launch_bounds__(64) void append_fp8_kernel(AppendFp8Args a)
     const float old_amax = old_scale * 448.0f;
     const bool keep = s0 > 0 && amax_new <= old_amax;
     const float scale = keep ? old_scale : (amax_new > 0.f ? amax_new / 448.0f : 1.0f);
+    const float ratio = old_scale / scale;  // re-encoding factor, one per tile
     if (!keep) {
         if (slot < s0) {  // re-encode what the page already held
 #pragma unroll
@@ -126,8 +130,7 @@ __global__ __launch_bounds__(64) void append_fp8_kernel(AppendFp8Args a)
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {
                     const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(in[w], false), hi = __builtin_amdgcn_cvt_pk_f32_fp8(in[w], true);
-                    o[w] = enc4((lo[0] * old_scale) / scale, (lo[1] * old_scale) / scale, (hi[0] * old_scale) / scale,
-                                (hi[1] * old_scale) / scale);
+                    o[w] = enc4(lo[0] * ratio, lo[1] * ratio, hi[0] * ratio, hi[1] * ratio);
                 }
                 tile[slot * (D / 16) + quarter * 2 + j] = uint4{o[0], o[1], o[2], o[3]};
             }
@@ -148,12 +151,92 @@ __global__ __launch_bounds__(64) void append_fp8_kernel(AppendFp8Args a)
     }
 }
 
+// The decode step's form of the same operation: every range is a single row, so
+// a tile is touched in one slot only and 4 lanes (32 elements each) are enough
+// for it.  Lane group u = (range, KV head, K or V); 16 groups per wave.  Same
+// arithmetic, in the same order, as append_fp8_kernel.
+__global__ __launch_bounds__(256) void append_fp8_row_kernel(AppendFp8Args a)
+{
+    constexpr int D = 128;
+    const unsigned gid = blockIdx.x * 256u + threadIdx.x;
+    const unsigned unit = gid >> 2;
+    const int quarter = gid & 3;
+    if (unit >= a.num_tiles) return;  // whole 4-lane groups leave together
+    const int which = unit & 1;
+    const int g = (unit >> 1) % a.Hkv;
+    const int r = (unit >> 1) / a.Hkv;
+    const int row0 = a.range_row0[r];
+    if (a.range_row0[r + 1] - row0 <= 0) return;
+    const int start = a.range_start[r], seq = a.range_seq[r];
+    const int s0 = start % kPage;
+    const int64_t page = a.block_table[(int64_t)seq * a.max_blocks + start / kPage];
+    const int64_t tile_index = page * a.Hkv + g;
+    uint4 *tile = reinterpret_cast<uint4 *>((which ? a.v_pages : a.k_pages) + tile_index * (kPage * D));
+    float *scale_p = (which ? a.v_scales : a.k_scales) + tile_index;
+    const uint4 *p = (which ? a.v_new : a.k_new) + ((int64_t)row0 * a.Hkv + g) * (D / 8) + quarter * 4;
+    float x[32];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint4 w = p[j];
+        x[8 * j + 0] = bf16_lo(w.x); x[8 * j + 1] = bf16_hi(w.x); x[8 * j + 2] = bf16_lo(w.y); x[8 * j + 3] = bf16_hi(w.y);
+        x[8 * j + 4] = bf16_lo(w.z); x[8 * j + 5] = bf16_hi(w.z); x[8 * j + 6] = bf16_lo(w.w); x[8 * j + 7] = bf16_hi(w.w);
+    }
+    float amax_new = 0.f;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) amax_new = fmaxf(amax_new, fabsf(x[i]));
+    amax_new = fmaxf(amax_new, __shfl_xor(amax_new, 1, 64));
+    amax_new = fmaxf(amax_new, __shfl_xor(amax_new, 2, 64));
+
+    const float old_scale = s0 > 0 ? *scale_p : 0.f;
+    const float old_amax = old_scale * 448.0f;
+    const bool keep = s0 > 0 && amax_new <= old_amax;
+    const float scale = keep ? old_scale : (amax_new > 0.f ? amax_new / 448.0f : 1.0f);
+    const float ratio = old_scale / scale;  // re-encoding factor, one per tile
+    if (!keep) {
+        // re-encode what the page already held: eight slots' loads in flight at a time
+        for (int base = 0; base < s0; base += 8) {
+            uint4 c[8][2];
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    if (base + i < s0) c[i][j] = tile[(base + i) * (D / 16) + quarter * 2 + j];
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    if (base + i >= s0) continue;
+                    const unsigned in[4] = {c[i][j].x, c[i][j].y, c[i][j].z, c[i][j].w};
+                    unsigned o[4];
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) {
+                        const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(in[w], false), hi = __builtin_amdgcn_cvt_pk_f32_fp8(in[w], true);
+                        o[w] = enc4(lo[0] * ratio, lo[1] * ratio, hi[0] * ratio, hi[1] * ratio);
+                    }
+                    tile[(base + i) * (D / 16) + quarter * 2 + j] = uint4{o[0], o[1], o[2], o[3]};
+                }
+        }
+        if (quarter == 0) *scale_p = scale;  // the group's four lanes read the old scale in the same instruction
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        unsigned o[4];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const int e = 16 * j + 4 * w;
+            o[w] = enc4(x[e] / scale, x[e + 1] / scale, x[e + 2] / scale, x[e + 3] / scale);
+        }
+        tile[s0 * (D / 16) + quarter * 2 + j] = uint4{o[0], o[1], o[2], o[3]};
+    }
+}
+
 hipError_t launch_append_fp8(const AppendFp8Args &a, hipStream_t stream)
 {
-    const uint64_t grid = 2ull * (uint64_t)a.R * (uint64_t)a.pages_per_range * (uint64_t)a.Hkv;
-    if (grid == 0) return hipSuccess;
-    if (grid > 0x7fffffffull) return hipErrorNotSupported;
-    hipLaunchKernelGGL(append_fp8_kernel, dim3((unsigned)grid), dim3(64), 0, stream, a);
+    if (a.num_tiles == 0) return hipSuccess;
+    if (a.pages_per_range == 1 && a.single_rows)
+        hipLaunchKernelGGL(append_fp8_row_kernel, dim3((a.num_tiles + 63) / 64), dim3(256), 0, stream, a);
+    else
+        hipLaunchKernelGGL(append_fp8_kernel, dim3((a.num_tiles + 3) / 4), dim3(256), 0, stream, a);
     return hipGetLastError();
 }
 

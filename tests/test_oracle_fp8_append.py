@@ -79,8 +79,8 @@ def numpy_append(k_new, start, tile, scale):
         new_scale = np.float32(scale)
     else:
         new_scale = amax_new / np.float32(448.0) if amax_new > 0 else np.float32(1.0)
-        old = (table()[tile[:s0]] * np.float32(scale)).astype(np.float32)
-        tile[:s0] = f32_to_e4m3fn_bits((old / new_scale).astype(np.float32))
+        ratio = np.float32(scale) / new_scale
+        tile[:s0] = f32_to_e4m3fn_bits((table()[tile[:s0]] * ratio).astype(np.float32))
     tile[s0:s1] = f32_to_e4m3fn_bits((x / new_scale).astype(np.float32))
     return tile, new_scale
 
