@@ -41,9 +41,11 @@ hipError_t launch_merge(const MergeArgs &a, int head_dim, hipStream_t stream, hi
     const unsigned grid = (unsigned)a.B * (unsigned)a.Hq;
     if (grid == 0) return hipSuccess;
     if (head_dim == 128)
-        hipExtLaunchKernelGGL(merge_kernel<128>, dim3(grid), dim3(128), 0, stream, start, stop, 0, a);
+        if (start || stop) hipExtLaunchKernelGGL(merge_kernel<128>, dim3(grid), dim3(128), 0, stream, start, stop, 0, a);
+        else hipLaunchKernelGGL(merge_kernel<128>, dim3(grid), dim3(128), 0, stream, a);
     else if (head_dim == 64)
-        hipExtLaunchKernelGGL(merge_kernel<64>, dim3(grid), dim3(64), 0, stream, start, stop, 0, a);
+        if (start || stop) hipExtLaunchKernelGGL(merge_kernel<64>, dim3(grid), dim3(64), 0, stream, start, stop, 0, a);
+        else hipLaunchKernelGGL(merge_kernel<64>, dim3(grid), dim3(64), 0, stream, a);
     else
         return hipErrorNotSupported;
     return hipGetLastError();

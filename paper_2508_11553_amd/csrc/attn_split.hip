@@ -751,6 +751,17 @@ __global__ __launch_bounds__(kWaves * 64, 2) void split_kernel(SplitArgs a)
     }
 }
 
+// Plain launches go through hipLaunchKernelGGL (capturable into HIP graphs); only
+// timed launches bind begin/end events with hipExtLaunchKernelGGL.
+template <class P>
+static void launch_one(const SplitArgs &a, dim3 g, dim3 b, hipStream_t stream, hipEvent_t start, hipEvent_t stop)
+{
+    if (start || stop)
+        hipExtLaunchKernelGGL(split_kernel<P>, g, b, 0, stream, start, stop, 0, a);
+    else
+        hipLaunchKernelGGL(split_kernel<P>, g, b, 0, stream, a);
+}
+
 hipError_t launch_split(const SplitArgs &a, int head_dim, int kv_dtype, hipStream_t stream,
                         hipEvent_t start, hipEvent_t stop)
 {
@@ -758,11 +769,11 @@ hipError_t launch_split(const SplitArgs &a, int head_dim, int kv_dtype, hipStrea
     if (grid == 0) return hipSuccess;
     const dim3 g(grid), b(kWaves * 64);
     if (kv_dtype == 0 && head_dim == 128)
-        hipExtLaunchKernelGGL(split_kernel<Bf16Path<128>>, g, b, 0, stream, start, stop, 0, a);
+        launch_one<Bf16Path<128>>(a, g, b, stream, start, stop);
     else if (kv_dtype == 0 && head_dim == 64)
-        hipExtLaunchKernelGGL(split_kernel<Bf16Path<64>>, g, b, 0, stream, start, stop, 0, a);
+        launch_one<Bf16Path<64>>(a, g, b, stream, start, stop);
     else if (kv_dtype == 1 && head_dim == 128)
-        hipExtLaunchKernelGGL(split_kernel<Fp8Path>, g, b, 0, stream, start, stop, 0, a);
+        launch_one<Fp8Path>(a, g, b, stream, start, stop);
     else
         return hipErrorNotSupported;
     return hipGetLastError();

@@ -542,3 +542,37 @@ def test_fp8_decode_step_append_then_attend(sd):
     assert np.array_equal(dw.k_pages.cpu().numpy(), k) and np.array_equal(dw.v_pages.cpu().numpy(), v)
     assert np.array_equal(dw.k_scales.cpu().numpy().view(np.uint32), ks.view(np.uint32))
     check_fp8(out.cpu().numpy(), oracle_full(wl))
+
+
+# ---------------------------------------------------------------- HIP graph capture
+def test_decode_step_replays_from_a_hip_graph(sd):
+    """The library neither allocates nor synchronises, so a whole decode step (append + attention) can be
+    captured once and replayed.  Every replay, with new queries and new appended rows written into the same
+    buffers and with eager work in between, must equal the eager result bit for bit."""
+    import torch
+    wl = workloads.make_custom([700, 33, 1500, 64], 8, 2, 128, seed=40, append=True)
+    dw = device_workload(wl)
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        dw.append(stream); dw.attend(stream)  # warm-up on the capture stream
+        stream.synchronize()
+        with torch.cuda.graph(graph, stream=stream):
+            dw.append(); dw.attend()
+    rng = np.random.default_rng(0)
+    from paper_2508_11553_amd.device import _to_dev
+    for it in range(4):
+        q = workloads.f32_to_bf16_bits(rng.standard_normal(wl.q.shape).astype(np.float32))
+        kn = workloads.f32_to_bf16_bits(rng.standard_normal(wl.k_new.shape).astype(np.float32))
+        dw.q.copy_(_to_dev(q, dw.device)); dw.k_new.copy_(_to_dev(kn, dw.device))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = dw.out.clone()
+        dw.out.zero_()                      # eager work between replays
+        dw.append(); eager = dw.attend().clone()
+        torch.cuda.synchronize()
+        assert torch.equal(got, eager), f"replay {it} differs from the eager step"
+    k, v = wl.k_pages.copy(), wl.v_pages.copy()
+    oracle.kv_append(kn, wl.v_new, wl.seq_ids, wl.positions, k, v, wl.block_table)
+    wl.q = q
+    check(got.cpu().numpy(), oracle_full(wl, k, v))
