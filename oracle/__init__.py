@@ -194,3 +194,25 @@ def kv_append_fp8(k_new, v_new, range_seq, range_start, range_row0, k_pages, v_p
     fn(ctypes.c_int(Hkv), ctypes.c_int(d), ctypes.c_int(block_table.shape[1]), _p(k_new), _p(v_new), _p(range_seq),
        _p(range_start), _p(range_row0), ctypes.c_int(range_seq.shape[0]), _p(k_pages), _p(v_pages), _p(k_scales),
        _p(v_scales), _p(block_table))
+
+
+def paged_prefill_attention(q, q_start, k_pages, v_pages, block_table, context_lens, scale,
+                            k_scales=None, v_scales=None, kv_dtype="bf16", precision="f64"):
+    """Causal attention of several query rows per sequence: q [rows][Hq][d], q_start [B+1] -> [rows][Hq][d]."""
+    kvd = np.uint8 if kv_dtype == "fp8" else np.uint16
+    q, k_pages, v_pages = _c(q, np.uint16), _c(k_pages, kvd), _c(v_pages, kvd)
+    k_scales, v_scales = _c(k_scales, np.float32), _c(v_scales, np.float32)
+    q_start, block_table, context_lens = _c(q_start, np.int32), _c(block_table, np.int32), _c(context_lens, np.int32)
+    rows, Hq, d = q.shape
+    B = context_lens.shape[0]
+    assert q_start.shape == (B + 1,) and int(q_start[-1]) == rows
+    real = np.float64 if precision == "f64" else np.float32
+    out = np.zeros((rows, Hq, d), dtype=real)
+    fn = getattr(lib(), f"oracle_paged_prefill_attention_{precision}")
+    fn.restype = ctypes.c_int
+    rc = fn(ctypes.c_int(B), ctypes.c_int(Hq), ctypes.c_int(k_pages.shape[1]), ctypes.c_int(d),
+            ctypes.c_int(block_table.shape[1]), ctypes.c_int(KV_CODE[kv_dtype]), _p(q), _p(q_start), _p(k_pages),
+            _p(v_pages), _p(k_scales), _p(v_scales), _p(block_table), _p(context_lens), ctypes.c_float(scale), _p(out))
+    if rc:
+        raise MemoryError("oracle_paged_prefill_attention failed")
+    return out

@@ -34,12 +34,11 @@ static REAL NAME(kv_elem)(const void *pages, const float *scales, int kv_dtype,
 
 /* scores s_t for t in [t0, t1) of row (b, h) */
 static void NAME(scores)(int Hq, int Hkv, int d, int max_blocks, int kv_dtype,
-                         const uint16_t *q, const void *k_pages, const float *k_scales,
+                         const uint16_t *qrow, const void *k_pages, const float *k_scales,
                          const int32_t *block_table, REAL scale, int b, int h,
                          int t0, int t1, REAL *s)
 {
     int G = Hq / Hkv, g = h / G;
-    const uint16_t *qrow = q + ((int64_t)b * Hq + h) * d;
     for (int t = t0; t < t1; ++t) {
         int64_t page = block_table[(int64_t)b * max_blocks + t / ORACLE_PAGE];
         REAL dot = 0;
@@ -56,11 +55,29 @@ static void NAME(scores)(int Hq, int Hkv, int d, int max_blocks, int kv_dtype,
  * The full result is acc / l with [t0, t1) = [0, L).  Exposed so that the
  * split-and-merge identity can be tested on the CPU.
  */
+static int NAME(partial_row)(int Hq, int Hkv, int d, int max_blocks, int kv_dtype,
+                             const uint16_t *qrow, const void *k_pages, const void *v_pages,
+                             const float *k_scales, const float *v_scales,
+                             const int32_t *block_table, float scale_f, int b, int h,
+                             int t0, int t1, REAL *m_out, REAL *l_out, REAL *acc);
+
 int NAME(oracle_partial)(int Hq, int Hkv, int d, int max_blocks, int kv_dtype,
                          const uint16_t *q, const void *k_pages, const void *v_pages,
                          const float *k_scales, const float *v_scales,
                          const int32_t *block_table, float scale_f, int b, int h,
                          int t0, int t1, REAL *m_out, REAL *l_out, REAL *acc)
+{
+    /* decode: the query row of (b, h) in q [B][Hq][d] */
+    return NAME(partial_row)(Hq, Hkv, d, max_blocks, kv_dtype, q + ((int64_t)b * Hq + h) * d, k_pages, v_pages,
+                             k_scales, v_scales, block_table, scale_f, b, h, t0, t1, m_out, l_out, acc);
+}
+
+/* the same for an explicit query row (bf16 [d]) of head h attending sequence b */
+static int NAME(partial_row)(int Hq, int Hkv, int d, int max_blocks, int kv_dtype,
+                             const uint16_t *q, const void *k_pages, const void *v_pages,
+                             const float *k_scales, const float *v_scales,
+                             const int32_t *block_table, float scale_f, int b, int h,
+                             int t0, int t1, REAL *m_out, REAL *l_out, REAL *acc)
 {
     int G = Hq / Hkv, g = h / G, n = t1 - t0;
     for (int i = 0; i < d; ++i) acc[i] = 0;
@@ -156,4 +173,43 @@ int NAME(oracle_paged_decode_attention)(int B, int Hq, int Hkv, int d, int max_b
                                       rows, n, out);
     free(rows);
     return rc;
+}
+
+/*
+ * Several query tokens per sequence over the paged cache, causal (a resumed
+ * trajectory re-computes attention for a stretch of its stored tokens at once).
+ * Sequence b owns the query rows q_start[b] .. q_start[b+1]-1 of q
+ * [rows][Hq][d]; they are its LAST n_b positions: row i sits at position
+ * pos = context_lens[b] - n_b + i and attends the tokens 0 .. pos, i.e. it is
+ * the single-query problem with context length pos + 1.  Rows with pos < 0
+ * (more queries than tokens) give zero rows.  out is [rows][Hq][d].
+ */
+int NAME(oracle_paged_prefill_attention)(int B, int Hq, int Hkv, int d, int max_blocks, int kv_dtype,
+                                         const uint16_t *q, const int32_t *q_start,
+                                         const void *k_pages, const void *v_pages,
+                                         const float *k_scales, const float *v_scales,
+                                         const int32_t *block_table, const int32_t *context_lens,
+                                         float scale, REAL *out)
+{
+    int err = 0;
+    for (int b = 0; b < B; ++b) {
+        int n = q_start[b + 1] - q_start[b];
+#pragma omp parallel for schedule(dynamic, 1) collapse(2)
+        for (int i = 0; i < n; ++i)
+            for (int h = 0; h < Hq; ++h) {
+                int64_t r = (int64_t)q_start[b] + i;
+                int pos = context_lens[b] - n + i;
+                REAL m, l, *o = out + (r * Hq + h) * d;
+                int rc = NAME(partial_row)(Hq, Hkv, d, max_blocks, kv_dtype, q + (r * Hq + h) * d, k_pages,
+                                           v_pages, k_scales, v_scales, block_table, scale, b, h, 0, pos + 1,
+                                           &m, &l, o);
+                if (rc) {
+#pragma omp atomic write
+                    err = rc;
+                }
+                if (l > 0)
+                    for (int j = 0; j < d; ++j) o[j] /= l;
+            }
+    }
+    return err;
 }
