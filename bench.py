@@ -225,7 +225,7 @@ def main():
 
     value = ab["step"] / (ms_per_step * 1e-3) / 1e9
     achieved = ab["split"] / (split_avg * 1e-3) / 1e9
-    src = [os.path.join(ROOT, "paper_2508_11553_amd", "csrc", f) for f in ("attn_split.hip", "kernels.h")]
+    src = [os.path.join(ROOT, "paper_2508_11553_amd", "csrc", f) for f in ("attn_split.hip", "attn_tile.h", "kernels.h")]
     rec = {
         "metric": "decode-attention HBM GB/s (% of MI355X peak) + attended KV tokens/sec, 1 GPU",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

@@ -211,6 +211,37 @@ int paged_decode_attention_prefix(const sd_shape *shape, const void *q,
                                   struct sd_timer *timer);
 
 /*
+ * paged_prefill_attention -- causal attention of several query tokens per
+ * sequence over the paged cache.
+ *
+ * Rollout is interrupted and resumed (partial rollout; the Trajectory Manager
+ * re-sends a session's stored prefix to whichever instance continues it, Data
+ * Plane), and a resumed trajectory re-computes attention for a stretch of its
+ * own tokens whose K/V already sit in the cache.  Sequence b owns the query
+ * rows q_start[b] .. q_start[b+1]-1 of q; with n_b of them and
+ * L = min(context_lens[b], max_context_len), row i is the query of position
+ * pos = L - n_b + i and attends the tokens 0 .. pos:
+ *     out[row][h] = softmax_{t <= pos}(scale * <q[row][h], K_t>) . V
+ * i.e. paged_decode_attention with context length pos + 1 (the arithmetic is
+ * the same: bf16 operands, fp32 accumulation, bf16 weights normalised by their
+ * own sum).  n_b == 1 for every b is the decode step.  Rows with pos < 0 (more
+ * queries than tokens) get zero rows.  One kernel, no workspace.
+ *
+ *   q         bf16 [total_q][num_q_heads][head_dim]  (device)
+ *   q_start   i32 [batch + 1] (device), ascending, q_start[batch] <= total_q; a
+ *             sequence whose range leaves [0, total_q) is skipped
+ *   max_q_len host-known bound on n_b; rows past it in a sequence are not computed
+ *   out       f32 [total_q][num_q_heads][head_dim]   (device); rows no sequence owns are left as they are
+ *   timer     NULL or an sd_timer; the kernel's time is reported as split_ms, merge_ms reads ~0
+ */
+int paged_prefill_attention(const sd_shape *shape, const void *q, const int32_t *q_start,
+                            int32_t total_q, int32_t max_q_len,
+                            const void *k_pages, const void *v_pages,
+                            const float *k_scales, const float *v_scales,
+                            const int32_t *block_table, const int32_t *context_lens,
+                            float scale, float *out, void *stream, struct sd_timer *timer);
+
+/*
  * Session prefix tree (host only; no device memory, no HIP calls).
  *
  * The Trajectory Manager keeps the trajectories of a session in a prefix tree

@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     load,
     paged_decode_attention,
     paged_decode_attention_prefix,
+    paged_prefill_attention,
     probe_read,
     strerror,
     version,

@@ -72,6 +72,8 @@ def load():
     L.paged_decode_attention_prefix.restype = ctypes.c_int
     L.paged_decode_attention_prefix.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, vp, vp, sz,
                                                 vp, vp]
+    L.paged_prefill_attention.restype = ctypes.c_int
+    L.paged_prefill_attention.argtypes = [sp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp]
     L.sd_timer_create.restype = vp
     L.sd_timer_create.argtypes = [i32]
     L.sd_timer_destroy.restype = None
@@ -204,6 +206,16 @@ def paged_decode_attention_prefix(shape: Shape, q, k_pages, v_pages, k_scales, v
         int(max_shared_len), float(scale), _ptr(out), _ptr(workspace), int(workspace_nbytes), _stream(stream),
         timer._h if timer is not None else None)
     _check(rc, "paged_decode_attention_prefix")
+
+
+def paged_prefill_attention(shape: Shape, q, q_start, total_q: int, max_q_len: int, k_pages, v_pages, k_scales,
+                            v_scales, block_table, context_lens, scale: float, out, stream=None,
+                            timer: Optional[KernelTimer] = None):
+    rc = load().paged_prefill_attention(
+        ctypes.byref(shape), _ptr(q), _ptr(q_start), int(total_q), int(max_q_len), _ptr(k_pages), _ptr(v_pages),
+        _ptr(k_scales), _ptr(v_scales), _ptr(block_table), _ptr(context_lens), float(scale), _ptr(out),
+        _stream(stream), timer._h if timer is not None else None)
+    _check(rc, "paged_prefill_attention")
 
 
 def probe_read(shape: Shape, k_pages, v_pages, block_table, context_lens, sink, stream=None):

@@ -295,6 +295,57 @@ int paged_decode_attention(const sd_shape *shape, const void *q, const void *k_p
                                          workspace_bytes, stream, nullptr);
 }
 
+int paged_prefill_attention(const sd_shape *shape, const void *q, const int32_t *q_start, int32_t total_q,
+                            int32_t max_q_len, const void *k_pages, const void *v_pages, const float *k_scales,
+                            const float *v_scales, const int32_t *block_table, const int32_t *context_lens,
+                            float scale, float *out, void *stream, sd_timer *timer)
+{
+    const int rc = check_shape(shape);
+    if (rc) return rc;
+    if (total_q < 0 || max_q_len < 0) return SD_EINVAL;
+    if (shape->batch == 0 || total_q == 0 || max_q_len == 0) return SD_OK;
+    if (bad_ptr(q) || bad_ptr(q_start) || bad_ptr(k_pages) || bad_ptr(v_pages) || bad_ptr(block_table) ||
+        bad_ptr(context_lens) || bad_ptr(out))
+        return SD_EINVAL;
+    if (shape->kv_dtype == SD_FP8_E4M3 && (bad_ptr(k_scales) || bad_ptr(v_scales))) return SD_EINVAL;
+    if (!(scale == scale)) return SD_EINVAL;
+    if (timer && timer->calls >= timer->max_calls) return SD_EINVAL;
+    sd::PrefillArgs a;
+    a.q = static_cast<const uint16_t *>(q);
+    a.q_start = q_start;
+    a.k_pages = k_pages;
+    a.v_pages = v_pages;
+    a.k_scales = k_scales;
+    a.v_scales = v_scales;
+    a.block_table = block_table;
+    a.context_lens = context_lens;
+    a.out = out;
+    a.scale_log2e = scale * 1.4426950408889634f;
+    a.B = shape->batch;
+    a.Hq = shape->num_q_heads;
+    a.Hkv = shape->num_kv_heads;
+    a.G = shape->num_q_heads / shape->num_kv_heads;
+    a.max_blocks = shape->max_blocks_per_seq;
+    a.max_context_len = shape->max_context_len;
+    a.total_q = total_q;
+    a.max_q_len = max_q_len < total_q ? max_q_len : total_q;
+    const int tokens_per_wg = sd::kWaves * (a.G <= sd::kMaxGroup / 2 ? sd::kMaxGroup / a.G : 1);
+    a.q_blocks = (a.max_q_len + tokens_per_wg - 1) / tokens_per_wg;
+    if ((uint64_t)a.q_blocks * (uint64_t)a.B * (uint64_t)a.Hkv > 0x7fffffffull) return SD_EUNSUPPORTED;
+    hipEvent_t none[2] = {nullptr, nullptr};
+    hipEvent_t *ev = timer ? &timer->ev[(size_t)timer->calls * 4] : none;
+    const hipError_t e = sd::launch_prefill(a, shape->head_dim, shape->kv_dtype, static_cast<hipStream_t>(stream), ev[0], ev[1]);
+    if (e != hipSuccess) return e == hipErrorNotSupported ? SD_EUNSUPPORTED : hip_fail(e);
+    if (timer) {
+        // the timer keeps four events per call; this call has one kernel, so the second pair brackets nothing
+        hipError_t r = hipEventRecord(ev[2], static_cast<hipStream_t>(stream));
+        if (r == hipSuccess) r = hipEventRecord(ev[3], static_cast<hipStream_t>(stream));
+        if (r != hipSuccess) return hip_fail(r);
+        timer->calls++;
+    }
+    return SD_OK;
+}
+
 sd_timer *sd_timer_create(int32_t max_calls)
 {
     if (max_calls <= 0) return nullptr;

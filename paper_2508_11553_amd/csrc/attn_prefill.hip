@@ -1,0 +1,143 @@
+// Causal attention of several query tokens per sequence over the paged cache
+// (gfx950, wave64, MFMA): the re-computation of a stretch of a trajectory's own
+// stored tokens when it resumes after an interruption.
+//
+// Sequence b brings n_b = q_start[b+1] - q_start[b] query tokens, its LAST n_b
+// positions: query i sits at position pos = L - n_b + i and attends the tokens
+// 0 .. pos.  One workgroup (4 waves) owns a block of 4 * (16 / G) consecutive
+// query tokens of one sequence and one KV head; wave w owns 16 / G of them, and
+// the 16 columns of its MFMA tiles are those tokens times the G query heads of
+// the KV head.  The K/V tiles are the same for the four waves: per round each
+// wave loads a different 32-token tile from HBM (one round ahead), parks the K
+// image and its V registers in an LDS slot, and after a barrier every wave
+// attends the four tiles from LDS with its own columns.  Each wave carries its
+// rows through the whole range with the online softmax, so there is no split
+// and no merge: the wave normalises and writes its rows itself.
+//
+// The causal limit is a per-lane token bound in the score mask; a wave stops
+// once a tile starts at or past the last position any of its rows may see.
+// The grid runs the blocks of late positions (long ranges) first.
+#include "attn_tile.h"
+
+namespace sd {
+
+template <class P>
+__global__ __launch_bounds__(kWaves * 64, 2) void prefill_kernel(PrefillArgs a)
+{
+    constexpr int D = P::kDim;
+    constexpr int kSlot = Lds<P>::kSlotBytes;
+    __shared__ __attribute__((aligned(16))) char lds[kWaves * kSlot];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const unsigned item = blockIdx.x;  // (query block counted from the back, sequence, kv head), kv head fastest
+    const int g = item % a.Hkv;
+    const int b = (item / a.Hkv) % a.B;
+    const int jb = a.q_blocks - 1 - (int)(item / (a.Hkv * a.B));
+    const int tpw = a.G <= kMaxGroup / 2 ? kMaxGroup / a.G : 1;  // query tokens per wave
+
+    // everything below up to the loop is workgroup-uniform
+    const int qs = a.q_start[b];
+    const int nq = min(a.q_start[b + 1] - qs, a.max_q_len);
+    const int i0 = jb * kWaves * tpw;
+    if (i0 >= nq) return;
+    if (qs < 0 || (int64_t)qs + nq > a.total_q) return;  // rows outside q: nothing is read or written
+    const int L = max(0, min(a.context_lens[b], a.max_context_len));
+    const int base = L - nq;                                            // position of query 0 (may be negative)
+    const int kv_end = max(0, base + min(nq, i0 + kWaves * tpw));       // tokens the block's last row sees
+
+    // this wave's rows
+    const int iw0 = i0 + wave * tpw;
+    const int iw1 = min(iw0 + tpw, nq);
+    const bool active = iw0 < nq && base + iw1 > 0;  // some row of the wave sees a token
+    const int wave_max_end = base + iw1;            // its last row's limit
+    const int wave_min_end = max(0, base + iw0) + 1;  // its first visible row's limit
+    const int n = lane & 15;
+    const int i = iw0 + n / a.G;
+    const bool in_range = n / a.G < tpw && i < nq;
+    const bool row_ok = in_range && base + i >= 0;
+    // rows that see nothing ride along with zero queries, masked only past the sequence's end
+    const int row_end = row_ok ? base + i + 1 : L;
+    const int64_t row = ((int64_t)qs + i) * a.Hq + g * a.G + n % a.G;
+
+    u32x4 qop[D / 32];
+#pragma unroll
+    for (int s = 0; s < D / 32; ++s)
+        qop[s] = row_ok ? *reinterpret_cast<const u32x4 *>(a.q + row * D + P::q_offset(s, lane)) : u32x4{0, 0, 0, 0};
+    WaveState<D> st;
+    reset(st);
+
+    const int32_t *bt = a.block_table + (int64_t)b * a.max_blocks;
+    const int64_t page_bytes = (int64_t)P::kTileBytes * a.Hkv;
+    const char *kbase = static_cast<const char *>(a.k_pages) + g * P::kTileBytes;
+    const char *vbase = static_cast<const char *>(a.v_pages) + g * P::kTileBytes;
+    auto issue = [&](typename P::Tile &r, int pa, int pb) {
+        P::template load_page<false>(r, 0, kbase + pa * page_bytes, vbase + pa * page_bytes, a.k_scales, a.v_scales,
+                                     (int64_t)pa * a.Hkv + g, lane);
+        P::template load_page<false>(r, 1, kbase + pb * page_bytes, vbase + pb * page_bytes, a.k_scales, a.v_scales,
+                                     (int64_t)pb * a.Hkv + g, lane);
+    };
+    const int ntiles = (kv_end + kTileTokens - 1) / kTileTokens;
+    const int rounds = (ntiles + kWaves - 1) / kWaves;
+    const int last_page = (kv_end + kPage - 1) / kPage - 1;
+    char *mine = lds + wave * kSlot;
+    if (rounds > 0) {
+        typename P::Tile r;
+        // tiles past the end re-read the last page; nobody attends them
+        issue(r, bt[min(2 * wave, last_page)], bt[min(2 * wave + 1, last_page)]);
+        for (int rd = 0; rd < rounds; ++rd) {
+            const int tn = kWaves * min(rd + 1, rounds - 1) + wave;
+            const int na = bt[min(2 * tn, last_page)], nb = bt[min(2 * tn + 1, last_page)];
+            P::k_store(r, mine, lane);
+            P::v_store(r, mine + P::kScratchBytes, lane);
+            if (rd + 1 < rounds) issue(r, na, nb);
+            __syncthreads();
+            if (active) {
+#pragma unroll 1
+                for (int j = 0; j < kWaves; ++j) {
+                    const int tok0 = (kWaves * rd + j) * kTileTokens;
+                    if (tok0 >= wave_max_end) break;  // wave-uniform
+                    const char *slot = lds + j * kSlot;
+                    u32x4 ka[D / 32], kb[D / 32];
+                    typename P::Tile t;
+                    P::k_fetch(slot, lane, ka, kb);
+                    P::v_fetch(t, slot + P::kScratchBytes, lane);
+                    P::attend(ka, kb, t, qop, st, a.scale_log2e, tok0, L, lane, row_end, tok0 + kTileTokens > wave_min_end);
+                }
+            }
+            __syncthreads();
+        }
+    }
+    st.l = head_sum(st.l);
+    if (!in_range) return;
+    // rows before the sequence's first token get zeros
+    const float inv = row_ok ? 1.0f / st.l : 0.0f;
+#pragma unroll
+    for (int k = 0; k < D / 16; ++k) st.acc[k] = row_ok ? st.acc[k] * inv : f32x4{0, 0, 0, 0};
+    P::store_acc(st, a.out + row * D, lane >> 4);
+}
+
+hipError_t launch_prefill(const PrefillArgs &a, int head_dim, int kv_dtype, hipStream_t stream, hipEvent_t start,
+                          hipEvent_t stop)
+{
+    const unsigned grid = (unsigned)a.q_blocks * (unsigned)a.B * (unsigned)a.Hkv;
+    if (grid == 0) return hipSuccess;
+    const dim3 g(grid), b(kWaves * 64);
+    auto go = [&](auto kernel) {
+        if (start || stop)
+            hipExtLaunchKernelGGL(kernel, g, b, 0, stream, start, stop, 0, a);
+        else
+            hipLaunchKernelGGL(kernel, g, b, 0, stream, a);
+    };
+    if (kv_dtype == 0 && head_dim == 128)
+        go(prefill_kernel<Bf16Path<128>>);
+    else if (kv_dtype == 0 && head_dim == 64)
+        go(prefill_kernel<Bf16Path<64>>);
+    else if (kv_dtype == 1 && head_dim == 128)
+        go(prefill_kernel<Fp8Path>);
+    else
+        return hipErrorNotSupported;
+    return hipGetLastError();
+}
+
+}  // namespace sd

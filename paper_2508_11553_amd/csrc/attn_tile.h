@@ -1,0 +1,487 @@
+// Tile-level building blocks shared by the attention kernels of libseamdecode
+// (gfx950, wave64): MFMA wrappers, the online softmax of one 32-token tile, and
+// the two storage paths (bf16 pools, fp8 e4m3fn pools) with their loads, LDS
+// layouts and operand formation.  See attn_split.hip for how they are used.
+#pragma once
+#include "kernels.h"
+
+namespace sd {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+
+#define SD_DEV __device__ __forceinline__
+
+SD_DEV f32x4 mfma_bf16_k32(u32x4 a, u32x4 b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                   __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// (lo16 of x) | (lo16 of y) << 16, or the same with the high halves
+SD_DEV unsigned pack_lo(unsigned x, unsigned y) { return __builtin_amdgcn_perm(y, x, 0x05040100u); }
+SD_DEV unsigned pack_hi(unsigned x, unsigned y) { return __builtin_amdgcn_perm(y, x, 0x07060302u); }
+
+// two floats -> packed bf16 pair, round-to-nearest-even (v_cvt_pk_bf16_f32)
+SD_DEV unsigned cvt_pk_bf16(float lo, float hi)
+{
+    bf16x2 r;
+    r[0] = (__bf16)lo;
+    r[1] = (__bf16)hi;
+    return __builtin_bit_cast(unsigned, r);
+}
+
+// two e4m3fn codes (one 16-bit half of w) -> packed bf16 pair, exact.  The
+// instruction applies only the power-of-two part of its scale operand; 1.0
+// leaves the values as they are.
+template <bool HI>
+SD_DEV unsigned cvt_pk_bf16_fp8(unsigned w)
+{
+    return __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, HI));
+}
+
+// K/V bytes that one wave uses once per launch are loaded with the
+// non-temporal hint, so that they stream through the caches instead of
+// displacing each other (STREAM = true).  Bytes that the four waves of a
+// workgroup all read (shared-prefix items) take ordinary loads: the first wave
+// to ask brings a line in and the caches serve the other three.
+template <bool STREAM, typename T>
+SD_DEV T kv_load(const T *p)
+{
+    if (STREAM) return __builtin_nontemporal_load(p);
+    return *p;
+}
+
+// Reductions over the four lanes {n, n+16, n+32, n+48} that share a head.
+// v_permlane16_swap exchanges rows 1<->0' and 3<->2' of its two operands and
+// v_permlane32_swap the upper half of one with the lower half of the other;
+// fed the same value twice they return (x, x from the partner row/half).
+SD_DEV float head_max(float x)
+{
+    const unsigned u = __builtin_bit_cast(unsigned, x);
+    const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    const float y = fmaxf(__builtin_bit_cast(float, a[0]), __builtin_bit_cast(float, a[1]));
+    const unsigned w = __builtin_bit_cast(unsigned, y);
+    const auto b = __builtin_amdgcn_permlane32_swap(w, w, false, false);
+    return fmaxf(__builtin_bit_cast(float, b[0]), __builtin_bit_cast(float, b[1]));
+}
+SD_DEV float head_sum(float x)
+{
+    x += __shfl_xor(x, 16, 64);
+    return x + __shfl_xor(x, 32, 64);
+}
+
+// Keeps the compiler from moving this wave's LDS reads above its LDS writes
+// (and the other way round).  Only the owning wave touches its scratch and the
+// LDS operations of one wave execute in order, so no workgroup barrier is needed.
+SD_DEV void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int D>
+struct WaveState {
+    float m;             // running max of this lane's head (same in the 4 lanes of a head)
+    float l;             // this lane's share of the weight sum
+    f32x4 acc[D / 16];   // O^T accumulators; which d each one holds is the path's business
+};
+
+// Scores of one tile -> weights.  x holds, for row lane&15, the scaled scores
+// of tokens tok0 + 4qd + e (e < 4, first page) and tok0 + 16 + 4qd + e - 4
+// (second page).  Tokens >= row_end (this lane's row: the end of the sequence
+// for a decode query, position + 1 for a causal one) are masked when `mask` is
+// set (wave-uniform: some row of the wave ends inside the tile).  Updates the
+// running max and rescales the accumulators when some row's max moved.
+// Returns exp2(x - m) in p.
+template <int D>
+SD_DEV void online_softmax(float (&x)[8], float (&p)[8], WaveState<D> &st, bool mask, int tok0, int row_end, int qd)
+{
+    if (mask) {  // mask by position, never by content
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (tok0 + 4 * qd + e >= row_end) x[e] = -INFINITY;
+            if (tok0 + 16 + 4 * qd + e >= row_end) x[4 + e] = -INFINITY;
+        }
+    }
+    float tmax = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+    tmax = head_max(tmax);
+    const float m_new = fmaxf(st.m, tmax);
+    const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
+    st.m = m_new;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(x[e] - m_new);
+    st.l *= alpha;
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f)) {
+#pragma unroll
+        for (int i = 0; i < D / 16; ++i) st.acc[i] *= alpha;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// bf16 pools
+// ---------------------------------------------------------------------------
+template <int D>
+struct Bf16Path {
+    static constexpr int kDim = D;
+    static constexpr int kTileBytes = kPage * D * 2;     // one (page, head) tile
+    static constexpr int kScratchBytes = 2 * kTileBytes;  // K of one 32-token tile in LDS
+    static constexpr int kVBytes = 2 * kTileBytes;        // V registers of one tile parked in LDS
+    static constexpr int kPieces = D / 8;                 // 16-byte pieces per K row
+    static constexpr int kRowsPerLoad = 64 / kPieces;     // K rows one 1024-byte load covers
+
+    struct Tile {
+        u32x4 k[2][D / 32];     // [page][j]: 16 bytes at byte offset 1024*j + 16*lane of the K tile
+        u32x2 v[2][D / 64][4];  // [page][half][j]: V row 4*(lane>>4)+j, d = 64*half + 4*(lane&15) .. +4
+    };
+
+    // Q^T operand of step s: head lane&15, d = 32*s + 8*(lane>>4) .. +8
+    SD_DEV static int q_offset(int s, int lane) { return 32 * s + 8 * (lane >> 4); }
+
+    template <bool STREAM>
+    SD_DEV static void load_page(Tile &r, int pg, const char *kp, const char *vp, const float *, const float *, int64_t, int lane)
+    {
+        const char *kl = kp + lane * 16;
+#pragma unroll
+        for (int j = 0; j < D / 32; ++j) r.k[pg][j] = kv_load<STREAM>(reinterpret_cast<const u32x4 *>(kl + j * 1024));
+        const char *vl = vp + (lane >> 4) * 4 * (D * 2) + (lane & 15) * 8;
+#pragma unroll
+        for (int h = 0; h < D / 64; ++h)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                r.v[pg][h][j] = kv_load<STREAM>(reinterpret_cast<const u32x2 *>(vl + j * (D * 2) + h * 128));
+    }
+
+    // K tiles go through LDS: written as they lie in memory, read back one row
+    // per lane.  Piece c of row r sits at piece index c ^ r so that the writes
+    // (16 lanes = one row) and the reads (16 lanes = one piece column over 16
+    // rows) both spread over all banks.
+    SD_DEV static void k_store(const Tile &r, char *kslot, int lane)
+    {
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+            for (int j = 0; j < D / 32; ++j) {
+                const int row = j * kRowsPerLoad + lane / kPieces;
+                const int piece = (lane % kPieces) ^ (row % kPieces);
+                *reinterpret_cast<u32x4 *>(kslot + pg * kTileBytes + row * (D * 2) + piece * 16) = r.k[pg][j];
+            }
+    }
+
+    // K row (lane&15), d = 32*s + 8*(lane>>4) .. +8, of both pages
+    SD_DEV static void k_fetch(const char *kslot, int lane, u32x4 (&ka)[D / 32], u32x4 (&kb)[D / 32])
+    {
+        const int t = lane & 15, kg = lane >> 4;
+#pragma unroll
+        for (int s = 0; s < D / 32; ++s) {
+            const int piece = (4 * s + kg) ^ (t % kPieces);
+            ka[s] = *reinterpret_cast<const u32x4 *>(kslot + t * (D * 2) + piece * 16);
+            kb[s] = *reinterpret_cast<const u32x4 *>(kslot + kTileBytes + t * (D * 2) + piece * 16);
+        }
+    }
+
+    // V registers (the same for every wave that consumes the tile) parked in LDS, lane-linear
+    SD_DEV static void v_store(const Tile &r, char *vslot, int lane)
+    {
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+            for (int h = 0; h < D / 64; ++h)
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj) {
+                    const u32x4 w = {r.v[pg][h][2 * jj][0], r.v[pg][h][2 * jj][1], r.v[pg][h][2 * jj + 1][0],
+                                     r.v[pg][h][2 * jj + 1][1]};
+                    *reinterpret_cast<u32x4 *>(vslot + ((pg * (D / 64) + h) * 2 + jj) * 1024 + lane * 16) = w;
+                }
+    }
+    SD_DEV static void v_fetch(Tile &r, const char *vslot, int lane)
+    {
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+            for (int h = 0; h < D / 64; ++h)
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj) {
+                    const u32x4 w = *reinterpret_cast<const u32x4 *>(vslot + ((pg * (D / 64) + h) * 2 + jj) * 1024 + lane * 16);
+                    r.v[pg][h][2 * jj] = u32x2{w[0], w[1]};
+                    r.v[pg][h][2 * jj + 1] = u32x2{w[2], w[3]};
+                }
+    }
+
+    // Scores, online softmax and weighted V sum of one 32-token tile: tokens
+    // tok0 .. tok0+31, of which those < t_end are real.  ka/kb: K operands of
+    // the two pages; r.v: the V registers.
+    // Tokens >= t_end do not exist (their V is zeroed); each lane's row
+    // additionally ends at row_end <= t_end; `mask` says some row ends inside the tile.
+    SD_DEV static void attend(const u32x4 (&ka)[D / 32], const u32x4 (&kb)[D / 32], Tile &r,
+                              const u32x4 (&qop)[D / 32], WaveState<D> &st, float scale_log2e, int tok0, int t_end,
+                              int lane, int row_end, bool mask)
+    {
+        const int qd = lane >> 4;
+        f32x4 sa = {0, 0, 0, 0}, sb = {0, 0, 0, 0};
+#pragma unroll
+        for (int s = 0; s < D / 32; ++s) {
+            sa = mfma_bf16_k32(ka[s], qop[s], sa);
+            sb = mfma_bf16_k32(kb[s], qop[s], sb);
+        }
+        const bool ragged = tok0 + kTileTokens > t_end;  // wave-uniform
+        float x[8], p[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            x[e] = sa[e] * scale_log2e;
+            x[4 + e] = sb[e] * scale_log2e;
+        }
+        online_softmax<D>(x, p, st, mask, tok0, row_end, qd);
+        u32x4 pop;
+        float psum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+            const unsigned w = cvt_pk_bf16(p[e], p[e + 1]);
+            pop[e >> 1] = w;
+            // the sum runs over the rounded weights, the ones the product below uses
+            psum += __builtin_bit_cast(float, w << 16) + __builtin_bit_cast(float, w & 0xffff0000u);
+        }
+        st.l += psum;
+
+        auto &v = r.v;
+        if (ragged) {  // slots past the end may hold anything, NaN included: 0 * NaN must not happen
+#pragma unroll
+            for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (tok0 + 16 * pg + 4 * qd + j >= t_end) {
+#pragma unroll
+                        for (int h = 0; h < D / 64; ++h) v[pg][h][j] = u32x2{0, 0};
+                    }
+        }
+        // acc[4h + i][r] = O[head lane&15][d = 64h + 16qd + 4r + i]
+#pragma unroll
+        for (int h = 0; h < D / 64; ++h) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int w = i >> 1;
+                u32x4 a;
+                if (i & 1) {
+                    a[0] = pack_hi(v[0][h][0][w], v[0][h][1][w]);
+                    a[1] = pack_hi(v[0][h][2][w], v[0][h][3][w]);
+                    a[2] = pack_hi(v[1][h][0][w], v[1][h][1][w]);
+                    a[3] = pack_hi(v[1][h][2][w], v[1][h][3][w]);
+                } else {
+                    a[0] = pack_lo(v[0][h][0][w], v[0][h][1][w]);
+                    a[1] = pack_lo(v[0][h][2][w], v[0][h][3][w]);
+                    a[2] = pack_lo(v[1][h][0][w], v[1][h][1][w]);
+                    a[3] = pack_lo(v[1][h][2][w], v[1][h][3][w]);
+                }
+                st.acc[4 * h + i] = mfma_bf16_k32(a, pop, st.acc[4 * h + i]);
+            }
+        }
+    }
+
+    // this lane's accumulators -> row `dst` ([D] floats) of its head
+    SD_DEV static void store_acc(const WaveState<D> &st, float *dst, int qd)
+    {
+#pragma unroll
+        for (int h = 0; h < D / 64; ++h)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const f32x4 o = {st.acc[4 * h][r], st.acc[4 * h + 1][r], st.acc[4 * h + 2][r], st.acc[4 * h + 3][r]};
+                *reinterpret_cast<f32x4 *>(dst + 64 * h + 16 * qd + 4 * r) = o;
+            }
+    }
+};
+
+// ---------------------------------------------------------------------------
+// fp8 e4m3fn pools, head_dim 128: rows of 128 bytes, tiles of 2 KB
+// ---------------------------------------------------------------------------
+struct Fp8Path {
+    static constexpr int D = 128;
+    static constexpr int kDim = D;
+    static constexpr int kTileBytes = kPage * D;
+    static constexpr int kScratchBytes = 2 * kTileBytes;
+    static constexpr int kVBytes = 2 * kTileBytes + 16;  // codes + the four page scales
+
+    struct Tile {
+        u32x4 k[2][2];  // [page][j]: 16 bytes at byte offset 1024*j + 16*lane of the K tile
+        u32x2 v[2][4];  // [page][j]: V row 4*(lane>>4)+j, d = 8*(lane&15) .. +8
+        float ks[2], vs[2];
+    };
+
+    // Step s of the first product uses the 8 codes at d = 16*(kg + 4*(s>>1)) + 8*(s&1)
+    // of the lane's K row (kg = lane>>4): each lane converts two 16-byte pieces.
+    SD_DEV static int q_offset(int s, int lane) { return 16 * ((lane >> 4) + 4 * (s >> 1)) + 8 * (s & 1); }
+
+    template <bool STREAM>
+    SD_DEV static void load_page(Tile &r, int pg, const char *kp, const char *vp, const float *ks, const float *vs, int64_t si, int lane)
+    {
+        const char *kl = kp + lane * 16;
+        r.k[pg][0] = kv_load<STREAM>(reinterpret_cast<const u32x4 *>(kl));
+        r.k[pg][1] = kv_load<STREAM>(reinterpret_cast<const u32x4 *>(kl + 1024));
+        const char *vl = vp + (lane >> 4) * 4 * D + (lane & 15) * 8;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) r.v[pg][j] = kv_load<STREAM>(reinterpret_cast<const u32x2 *>(vl + j * D));
+        r.ks[pg] = ks[si];
+        r.vs[pg] = vs[si];
+    }
+
+    // Rows are 128 bytes = 8 pieces; piece c of row r sits at c ^ (r >> 1), and
+    // odd rows start half a bank cycle later, so 16 lanes never share a bank.
+    SD_DEV static void k_store(const Tile &r, char *kslot, int lane)
+    {
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int row = 8 * j + (lane >> 3);
+                const int piece = (lane & 7) ^ ((row >> 1) & 7);
+                *reinterpret_cast<u32x4 *>(kslot + pg * kTileBytes + row * D + piece * 16) = r.k[pg][j];
+            }
+    }
+
+    SD_DEV static void k_fetch(const char *kslot, int lane, u32x4 (&ka)[4], u32x4 (&kb)[4])
+    {
+        const int t = lane & 15, kg = lane >> 4;
+        u32x4 raw[2][2];
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+                const int piece = (kg + 4 * hh) ^ ((t >> 1) & 7);
+                raw[pg][hh] = *reinterpret_cast<const u32x4 *>(kslot + pg * kTileBytes + t * D + piece * 16);
+            }
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int hh = s >> 1, lo = 2 * (s & 1);
+            ka[s] = u32x4{cvt_pk_bf16_fp8<false>(raw[0][hh][lo]), cvt_pk_bf16_fp8<true>(raw[0][hh][lo]),
+                          cvt_pk_bf16_fp8<false>(raw[0][hh][lo + 1]), cvt_pk_bf16_fp8<true>(raw[0][hh][lo + 1])};
+            kb[s] = u32x4{cvt_pk_bf16_fp8<false>(raw[1][hh][lo]), cvt_pk_bf16_fp8<true>(raw[1][hh][lo]),
+                          cvt_pk_bf16_fp8<false>(raw[1][hh][lo + 1]), cvt_pk_bf16_fp8<true>(raw[1][hh][lo + 1])};
+        }
+    }
+
+    // V registers and the four page scales parked in LDS (scales after the 4 KB of codes)
+    SD_DEV static void v_store(const Tile &r, char *vslot, int lane)
+    {
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj) {
+                const u32x4 w = {r.v[pg][2 * jj][0], r.v[pg][2 * jj][1], r.v[pg][2 * jj + 1][0], r.v[pg][2 * jj + 1][1]};
+                *reinterpret_cast<u32x4 *>(vslot + (pg * 2 + jj) * 1024 + lane * 16) = w;
+            }
+        if (lane == 0) *reinterpret_cast<f32x4 *>(vslot + 4096) = f32x4{r.ks[0], r.ks[1], r.vs[0], r.vs[1]};
+    }
+    SD_DEV static void v_fetch(Tile &r, const char *vslot, int lane)
+    {
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj) {
+                const u32x4 w = *reinterpret_cast<const u32x4 *>(vslot + (pg * 2 + jj) * 1024 + lane * 16);
+                r.v[pg][2 * jj] = u32x2{w[0], w[1]};
+                r.v[pg][2 * jj + 1] = u32x2{w[2], w[3]};
+            }
+        const f32x4 sc = *reinterpret_cast<const f32x4 *>(vslot + 4096);
+        r.ks[0] = sc[0];
+        r.ks[1] = sc[1];
+        r.vs[0] = sc[2];
+        r.vs[1] = sc[3];
+    }
+
+    SD_DEV static void attend(const u32x4 (&ka)[4], const u32x4 (&kb)[4], Tile &r, const u32x4 (&qop)[4],
+                              WaveState<D> &st, float scale_log2e, int tok0, int t_end, int lane, int row_end, bool mask)
+    {
+        const int qd = lane >> 4;
+        f32x4 sa = {0, 0, 0, 0}, sb = {0, 0, 0, 0};
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            sa = mfma_bf16_k32(ka[s], qop[s], sa);
+            sb = mfma_bf16_k32(kb[s], qop[s], sb);
+        }
+        const bool ragged = tok0 + kTileTokens > t_end;
+        const float ca = scale_log2e * r.ks[0], cb = scale_log2e * r.ks[1];
+        float x[8], p[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            x[e] = sa[e] * ca;
+            x[4 + e] = sb[e] * cb;
+        }
+        online_softmax<D>(x, p, st, mask, tok0, row_end, qd);
+        // the weight sum takes the unscaled weights; the product takes them times the page's V scale
+        st.l += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+        u32x4 pop;
+        pop[0] = cvt_pk_bf16(p[0] * r.vs[0], p[1] * r.vs[0]);
+        pop[1] = cvt_pk_bf16(p[2] * r.vs[0], p[3] * r.vs[0]);
+        pop[2] = cvt_pk_bf16(p[4] * r.vs[1], p[5] * r.vs[1]);
+        pop[3] = cvt_pk_bf16(p[6] * r.vs[1], p[7] * r.vs[1]);
+
+        auto &v = r.v;
+        if (ragged) {
+#pragma unroll
+            for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (tok0 + 16 * pg + 4 * qd + j >= t_end) v[pg][j] = u32x2{0, 0};
+        }
+        // acc[i][r] = O[head lane&15][d = 8*(4qd + r) + i]: codes i, i+1 of four tokens at a time;
+        // converting to f32 and packing two tokens' values per register is the transposition.
+#pragma unroll
+        for (int w = 0; w < 2; ++w) {
+#pragma unroll
+            for (int hi = 0; hi < 2; ++hi) {
+                f32x2 f[2][4];
+#pragma unroll
+                for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        f[pg][j] = hi ? __builtin_amdgcn_cvt_pk_f32_fp8(v[pg][j][w], true)
+                                      : __builtin_amdgcn_cvt_pk_f32_fp8(v[pg][j][w], false);
+#pragma unroll
+                for (int ii = 0; ii < 2; ++ii) {
+                    const int i = 4 * w + 2 * hi + ii;
+                    const u32x4 a = {cvt_pk_bf16(f[0][0][ii], f[0][1][ii]), cvt_pk_bf16(f[0][2][ii], f[0][3][ii]),
+                                     cvt_pk_bf16(f[1][0][ii], f[1][1][ii]), cvt_pk_bf16(f[1][2][ii], f[1][3][ii])};
+                    st.acc[i] = mfma_bf16_k32(a, pop, st.acc[i]);
+                }
+            }
+        }
+    }
+
+    SD_DEV static void store_acc(const WaveState<D> &st, float *dst, int qd)
+    {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const f32x4 lo = {st.acc[0][r], st.acc[1][r], st.acc[2][r], st.acc[3][r]};
+            const f32x4 hi = {st.acc[4][r], st.acc[5][r], st.acc[6][r], st.acc[7][r]};
+            *reinterpret_cast<f32x4 *>(dst + 32 * qd + 8 * r) = lo;
+            *reinterpret_cast<f32x4 *>(dst + 32 * qd + 8 * r + 4) = hi;
+        }
+    }
+};
+
+template <int D>
+SD_DEV void reset(WaveState<D> &st)
+{
+    st.m = -INFINITY;
+    st.l = 0.f;
+#pragma unroll
+    for (int i = 0; i < D / 16; ++i) st.acc[i] = f32x4{0, 0, 0, 0};
+}
+
+// LDS of one workgroup.  Plain items: per-wave K scratch plus the merge
+// buffers.  Shared-prefix items: four tile slots (K image + parked V
+// registers), one filled by each wave and read by all.
+template <class P>
+struct Lds {
+    static constexpr int kRow = P::kDim + 4;  // padded: 16 rows x float4 stores hit 64 distinct banks
+    static constexpr int kSlotBytes = P::kScratchBytes + ((P::kVBytes + 15) / 16) * 16;
+    static constexpr int kPlainBytes = kWaves * P::kScratchBytes + kWaves * kMaxGroup * kRow * 4 + 2 * kWaves * kMaxGroup * 4;
+    static constexpr int kSharedBytes = kWaves * kSlotBytes;
+    static constexpr int kBytes = kPlainBytes > kSharedBytes ? kPlainBytes : kSharedBytes;
+};
+
+}  // namespace sd

@@ -52,6 +52,20 @@ struct MergeArgs {
     int32_t max_shared_len;
 };
 
+// Arguments of the causal multi-query pass.
+struct PrefillArgs {
+    const uint16_t *q;           // [total_q][Hq][D] bf16
+    const int32_t *q_start;      // [B + 1] first query row of each sequence
+    const void *k_pages, *v_pages;
+    const float *k_scales, *v_scales;
+    const int32_t *block_table, *context_lens;
+    float *out;                  // [total_q][Hq][D]
+    float scale_log2e;
+    int32_t B, Hq, Hkv, G, max_blocks, max_context_len;
+    int32_t total_q, max_q_len;  // rows of q; host-known bound on the rows of one sequence
+    int32_t q_blocks;            // workgroups (4 x 16/G query tokens each) that cover max_q_len
+};
+
 struct AppendArgs {
     const uint4 *k_new, *v_new;  // [T][Hkv][D] bf16 viewed as 16-byte words
     const int32_t *seq_ids, *positions;
@@ -87,6 +101,8 @@ hipError_t launch_split(const SplitArgs &a, int head_dim, int kv_dtype, hipStrea
                         hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
 hipError_t launch_merge(const MergeArgs &a, int head_dim, hipStream_t stream,
                         hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
+hipError_t launch_prefill(const PrefillArgs &a, int head_dim, int kv_dtype, hipStream_t stream,
+                          hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
 hipError_t launch_append(const AppendArgs &a, int head_dim, hipStream_t stream);
 hipError_t launch_append_fp8(const AppendFp8Args &a, hipStream_t stream);
 hipError_t launch_probe(const ProbeArgs &a, hipStream_t stream);

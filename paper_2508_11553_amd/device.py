@@ -88,6 +88,17 @@ class DeviceWorkload:
                                          self.workspace, self.ws_bytes, stream, timer)
         return out
 
+    def attend_prefill(self, q_rows, q_start, stream=None, timer=None):
+        """Causal attention of the query rows q_rows ([rows][Hq][d] bf16 bits, numpy) split by q_start ([B+1])."""
+        q_start = np.asarray(q_start, dtype=np.int32)
+        q_dev, qs_dev = _to_dev(q_rows, self.device), _to_dev(q_start, self.device)
+        rows = int(q_rows.shape[0])
+        out = torch.zeros((rows, self.wl.num_q_heads, self.wl.head_dim), dtype=torch.float32, device=self.device)
+        max_q = int(np.diff(q_start).max()) if len(q_start) > 1 else 0
+        sd.paged_prefill_attention(self.shape, q_dev, qs_dev, rows, max_q, self.k_pages, self.v_pages, self.k_scales,
+                                   self.v_scales, self.block_table, self.context_lens, self.scale, out, stream, timer)
+        return out
+
     def pools_to_host(self):
         """Pool bytes back as numpy arrays of the workload's dtype."""
         k, v = self.k_pages.cpu().numpy(), self.v_pages.cpu().numpy()

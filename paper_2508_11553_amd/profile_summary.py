@@ -20,7 +20,7 @@ import os
 import statistics
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-KERNEL_SOURCES = [os.path.join(ROOT, "paper_2508_11553_amd", "csrc", f) for f in ("attn_split.hip", "kernels.h")]
+KERNEL_SOURCES = [os.path.join(ROOT, "paper_2508_11553_amd", "csrc", f) for f in ("attn_split.hip", "attn_tile.h", "kernels.h")]
 COPY_KIB = float(1 << 20)
 
 

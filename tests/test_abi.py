@@ -101,6 +101,22 @@ def test_null_and_misaligned_pointers_are_rejected_before_any_launch(lib):
     assert lib.kv_append(ctypes.byref(s8), 16, 16, 16, 16, 3, 16, 16, 16, None) == -2
 
 
+def test_prefill_arguments_are_checked_on_the_host(lib):
+    s = good_shape()
+    args = [16, 32, 8, 8, 48, 64, None, None, 80, 96, 1.0, 112, None, None]
+    for i in (0, 1, 4, 5, 8, 9, 11):
+        bad = list(args); bad[i] = None
+        assert lib.paged_prefill_attention(ctypes.byref(s), *bad) == -1
+        bad[i] = 24
+        assert lib.paged_prefill_attention(ctypes.byref(s), *bad) == -1
+    neg = list(args); neg[2] = -1
+    assert lib.paged_prefill_attention(ctypes.byref(s), *neg) == -1
+    none = list(args); none[2] = 0
+    assert lib.paged_prefill_attention(ctypes.byref(s), *none) == 0   # no query rows: nothing to do
+    s8 = good_shape(kv_dtype=sd.SD_FP8_E4M3, head_dim=128)
+    assert lib.paged_prefill_attention(ctypes.byref(s8), *args) == -1  # fp8 needs scales
+
+
 def test_empty_calls_are_noops(lib):
     s = good_shape(batch=0)
     assert lib.paged_decode_attention(ctypes.byref(s), None, None, None, None, None, None, None, 1.0, None, None, 0, None) == 0
