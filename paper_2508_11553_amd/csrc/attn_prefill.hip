@@ -4,10 +4,11 @@
 //
 // Sequence b brings n_b = q_start[b+1] - q_start[b] query tokens, its LAST n_b
 // positions: query i sits at position pos = L - n_b + i and attends the tokens
-// 0 .. pos.  One workgroup (4 waves) owns a block of 4 * (16 / G) consecutive
-// query tokens of one sequence and one KV head; wave w owns 16 / G of them, and
-// the 16 columns of its MFMA tiles are those tokens times the G query heads of
-// the KV head.  The K/V tiles are the same for the four waves: per round each
+// 0 .. pos.  One workgroup (4 waves) owns a block of 8 * (16 / G) consecutive
+// query tokens of one sequence and one KV head; wave w owns 2 * (16 / G) of
+// them as two column blocks of 16 rows (tokens times the G query heads of the
+// KV head), which share every K operand fetched from LDS and every V operand
+// formed in registers.  The K/V tiles are the same for the four waves: per round each
 // wave loads a different 32-token tile from HBM (one round ahead), parks the K
 // image and its V registers in an LDS slot, and after a barrier every wave
 // attends the four tiles from LDS with its own columns.  Each wave carries its
@@ -26,6 +27,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void prefill_kernel(PrefillArgs a)
 {
     constexpr int D = P::kDim;
     constexpr int kSlot = Lds<P>::kSlotBytes;
+    constexpr int NB = kPrefillBlocks;
     __shared__ __attribute__((aligned(16))) char lds[kWaves * kSlot];
 
     const int lane = threadIdx.x & 63;
@@ -34,7 +36,8 @@ __global__ __launch_bounds__(kWaves * 64, 2) void prefill_kernel(PrefillArgs a)
     const int g = item % a.Hkv;
     const int b = (item / a.Hkv) % a.B;
     const int jb = a.q_blocks - 1 - (int)(item / (a.Hkv * a.B));
-    const int tpw = a.G <= kMaxGroup / 2 ? kMaxGroup / a.G : 1;  // query tokens per wave
+    const int tpb = a.G <= kMaxGroup / 2 ? kMaxGroup / a.G : 1;  // query tokens per column block
+    const int tpw = kPrefillBlocks * tpb;                        // and per wave
 
     // everything below up to the loop is workgroup-uniform
     const int qs = a.q_start[b];
@@ -53,19 +56,31 @@ __global__ __launch_bounds__(kWaves * 64, 2) void prefill_kernel(PrefillArgs a)
     const int wave_max_end = base + iw1;            // its last row's limit
     const int wave_min_end = max(0, base + iw0) + 1;  // its first visible row's limit
     const int n = lane & 15;
-    const int i = iw0 + n / a.G;
-    const bool in_range = n / a.G < tpw && i < nq;
-    const bool row_ok = in_range && base + i >= 0;
-    // rows that see nothing ride along with zero queries, masked only past the sequence's end
-    const int row_end = row_ok ? base + i + 1 : L;
-    const int64_t row = ((int64_t)qs + i) * a.Hq + g * a.G + n % a.G;
-
-    u32x4 qop[D / 32];
+    // row of column block c in this lane: query token, whether it exists, whether it sees a token
+    // (recomputed where needed rather than kept in registers across the loop)
+    auto locate = [&](int c, bool &in_range, bool &row_ok, int64_t &row) {
+        const int i = iw0 + c * tpb + n / a.G;
+        in_range = n / a.G < tpb && i < nq;
+        row_ok = in_range && base + i >= 0;
+        row = ((int64_t)qs + i) * a.Hq + g * a.G + n % a.G;
+        return i;
+    };
+    int row_end[NB];
+    u32x4 qop[NB][D / 32];
+    WaveState<D> st[NB];
 #pragma unroll
-    for (int s = 0; s < D / 32; ++s)
-        qop[s] = row_ok ? *reinterpret_cast<const u32x4 *>(a.q + row * D + P::q_offset(s, lane)) : u32x4{0, 0, 0, 0};
-    WaveState<D> st;
-    reset(st);
+    for (int c = 0; c < NB; ++c) {
+        bool in_range, row_ok;
+        int64_t row;
+        const int i = locate(c, in_range, row_ok, row);
+        // rows that see nothing ride along with zero queries, masked only past the sequence's end
+        row_end[c] = row_ok ? base + i + 1 : L;
+#pragma unroll
+        for (int s = 0; s < D / 32; ++s)
+            qop[c][s] = row_ok ? *reinterpret_cast<const u32x4 *>(a.q + row * D + P::q_offset(s, lane))
+                               : u32x4{0, 0, 0, 0};
+        reset(st[c]);
+    }
 
     const int32_t *bt = a.block_table + (int64_t)b * a.max_blocks;
     const int64_t page_bytes = (int64_t)P::kTileBytes * a.Hkv;
@@ -102,19 +117,26 @@ __global__ __launch_bounds__(kWaves * 64, 2) void prefill_kernel(PrefillArgs a)
                     typename P::Tile t;
                     P::k_fetch(slot, lane, ka, kb);
                     P::v_fetch(t, slot + P::kScratchBytes, lane);
-                    P::attend(ka, kb, t, qop, st, a.scale_log2e, tok0, L, lane, row_end, tok0 + kTileTokens > wave_min_end);
+                    P::template attend_n<NB>(ka, kb, t, qop, st, a.scale_log2e, tok0, L, lane, row_end,
+                                             tok0 + kTileTokens > wave_min_end);
                 }
             }
             __syncthreads();
         }
     }
-    st.l = head_sum(st.l);
-    if (!in_range) return;
-    // rows before the sequence's first token get zeros
-    const float inv = row_ok ? 1.0f / st.l : 0.0f;
 #pragma unroll
-    for (int k = 0; k < D / 16; ++k) st.acc[k] = row_ok ? st.acc[k] * inv : f32x4{0, 0, 0, 0};
-    P::store_acc(st, a.out + row * D, lane >> 4);
+    for (int c = 0; c < NB; ++c) {
+        st[c].l = head_sum(st[c].l);
+        bool in_range, row_ok;
+        int64_t row;
+        locate(c, in_range, row_ok, row);
+        if (!in_range) continue;
+        // rows before the sequence's first token get zeros
+        const float inv = row_ok ? 1.0f / st[c].l : 0.0f;
+#pragma unroll
+        for (int k = 0; k < D / 16; ++k) st[c].acc[k] = row_ok ? st[c].acc[k] * inv : f32x4{0, 0, 0, 0};
+        P::store_acc(st[c], a.out + row * D, lane >> 4);
+    }
 }
 
 hipError_t launch_prefill(const PrefillArgs &a, int head_dim, int kv_dtype, hipStream_t stream, hipEvent_t start,

@@ -213,40 +213,48 @@ struct Bf16Path {
                 }
     }
 
-    // Scores, online softmax and weighted V sum of one 32-token tile: tokens
-    // tok0 .. tok0+31, of which those < t_end are real.  ka/kb: K operands of
-    // the two pages; r.v: the V registers.
-    // Tokens >= t_end do not exist (their V is zeroed); each lane's row
-    // additionally ends at row_end <= t_end; `mask` says some row ends inside the tile.
-    SD_DEV static void attend(const u32x4 (&ka)[D / 32], const u32x4 (&kb)[D / 32], Tile &r,
-                              const u32x4 (&qop)[D / 32], WaveState<D> &st, float scale_log2e, int tok0, int t_end,
-                              int lane, int row_end, bool mask)
+    // Scores, online softmax and weighted V sum of one 32-token tile (tokens
+    // tok0 .. tok0+31) for NB column blocks of 16 rows each, which share the K
+    // operands ka/kb and the V registers r.v.  Tokens >= t_end do not exist
+    // (their V is zeroed); the row of block c in this lane additionally ends at
+    // row_end[c] <= t_end; `mask` (wave-uniform) says some row ends inside the tile.
+    template <int NB>
+    SD_DEV static void attend_n(const u32x4 (&ka)[D / 32], const u32x4 (&kb)[D / 32], Tile &r,
+                                const u32x4 (&qop)[NB][D / 32], WaveState<D> (&st)[NB], float scale_log2e, int tok0,
+                                int t_end, int lane, const int (&row_end)[NB], bool mask)
     {
         const int qd = lane >> 4;
-        f32x4 sa = {0, 0, 0, 0}, sb = {0, 0, 0, 0};
+        f32x4 sa[NB], sb[NB];
 #pragma unroll
-        for (int s = 0; s < D / 32; ++s) {
-            sa = mfma_bf16_k32(ka[s], qop[s], sa);
-            sb = mfma_bf16_k32(kb[s], qop[s], sb);
-        }
+        for (int c = 0; c < NB; ++c) sa[c] = sb[c] = f32x4{0, 0, 0, 0};
+#pragma unroll
+        for (int s = 0; s < D / 32; ++s)
+#pragma unroll
+            for (int c = 0; c < NB; ++c) {
+                sa[c] = mfma_bf16_k32(ka[s], qop[c][s], sa[c]);
+                sb[c] = mfma_bf16_k32(kb[s], qop[c][s], sb[c]);
+            }
         const bool ragged = tok0 + kTileTokens > t_end;  // wave-uniform
-        float x[8], p[8];
+        u32x4 pop[NB];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            x[e] = sa[e] * scale_log2e;
-            x[4 + e] = sb[e] * scale_log2e;
-        }
-        online_softmax<D>(x, p, st, mask, tok0, row_end, qd);
-        u32x4 pop;
-        float psum = 0.f;
+        for (int c = 0; c < NB; ++c) {
+            float x[8], p[8];
 #pragma unroll
-        for (int e = 0; e < 8; e += 2) {
-            const unsigned w = cvt_pk_bf16(p[e], p[e + 1]);
-            pop[e >> 1] = w;
-            // the sum runs over the rounded weights, the ones the product below uses
-            psum += __builtin_bit_cast(float, w << 16) + __builtin_bit_cast(float, w & 0xffff0000u);
+            for (int e = 0; e < 4; ++e) {
+                x[e] = sa[c][e] * scale_log2e;
+                x[4 + e] = sb[c][e] * scale_log2e;
+            }
+            online_softmax<D>(x, p, st[c], mask, tok0, row_end[c], qd);
+            float psum = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) {
+                const unsigned w = cvt_pk_bf16(p[e], p[e + 1]);
+                pop[c][e >> 1] = w;
+                // the sum runs over the rounded weights, the ones the product below uses
+                psum += __builtin_bit_cast(float, w << 16) + __builtin_bit_cast(float, w & 0xffff0000u);
+            }
+            st[c].l += psum;
         }
-        st.l += psum;
 
         auto &v = r.v;
         if (ragged) {  // slots past the end may hold anything, NaN included: 0 * NaN must not happen
@@ -259,7 +267,7 @@ struct Bf16Path {
                         for (int h = 0; h < D / 64; ++h) v[pg][h][j] = u32x2{0, 0};
                     }
         }
-        // acc[4h + i][r] = O[head lane&15][d = 64h + 16qd + 4r + i]
+        // acc[4h + i][r] = O[row lane&15][d = 64h + 16qd + 4r + i]
 #pragma unroll
         for (int h = 0; h < D / 64; ++h) {
 #pragma unroll
@@ -277,9 +285,20 @@ struct Bf16Path {
                     a[2] = pack_lo(v[1][h][0][w], v[1][h][1][w]);
                     a[3] = pack_lo(v[1][h][2][w], v[1][h][3][w]);
                 }
-                st.acc[4 * h + i] = mfma_bf16_k32(a, pop, st.acc[4 * h + i]);
+#pragma unroll
+                for (int c = 0; c < NB; ++c) st[c].acc[4 * h + i] = mfma_bf16_k32(a, pop[c], st[c].acc[4 * h + i]);
             }
         }
+    }
+
+    // one column block
+    SD_DEV static void attend(const u32x4 (&ka)[D / 32], const u32x4 (&kb)[D / 32], Tile &r,
+                              const u32x4 (&qop)[D / 32], WaveState<D> &st, float scale_log2e, int tok0, int t_end,
+                              int lane, int row_end, bool mask)
+    {
+        const int ends[1] = {row_end};
+        attend_n<1>(ka, kb, r, reinterpret_cast<const u32x4 (&)[1][D / 32]>(qop),
+                    reinterpret_cast<WaveState<D> (&)[1]>(st), scale_log2e, tok0, t_end, lane, ends, mask);
     }
 
     // this lane's accumulators -> row `dst` ([D] floats) of its head
@@ -392,32 +411,42 @@ struct Fp8Path {
         r.vs[1] = sc[3];
     }
 
-    SD_DEV static void attend(const u32x4 (&ka)[4], const u32x4 (&kb)[4], Tile &r, const u32x4 (&qop)[4],
-                              WaveState<D> &st, float scale_log2e, int tok0, int t_end, int lane, int row_end, bool mask)
+    // as Bf16Path::attend_n; the K scale multiplies a page's scores, the V scale its weights
+    template <int NB>
+    SD_DEV static void attend_n(const u32x4 (&ka)[4], const u32x4 (&kb)[4], Tile &r, const u32x4 (&qop)[NB][4],
+                                WaveState<D> (&st)[NB], float scale_log2e, int tok0, int t_end, int lane,
+                                const int (&row_end)[NB], bool mask)
     {
         const int qd = lane >> 4;
-        f32x4 sa = {0, 0, 0, 0}, sb = {0, 0, 0, 0};
+        f32x4 sa[NB], sb[NB];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            sa = mfma_bf16_k32(ka[s], qop[s], sa);
-            sb = mfma_bf16_k32(kb[s], qop[s], sb);
-        }
+        for (int c = 0; c < NB; ++c) sa[c] = sb[c] = f32x4{0, 0, 0, 0};
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int c = 0; c < NB; ++c) {
+                sa[c] = mfma_bf16_k32(ka[s], qop[c][s], sa[c]);
+                sb[c] = mfma_bf16_k32(kb[s], qop[c][s], sb[c]);
+            }
         const bool ragged = tok0 + kTileTokens > t_end;
         const float ca = scale_log2e * r.ks[0], cb = scale_log2e * r.ks[1];
-        float x[8], p[8];
+        u32x4 pop[NB];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            x[e] = sa[e] * ca;
-            x[4 + e] = sb[e] * cb;
+        for (int c = 0; c < NB; ++c) {
+            float x[8], p[8];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                x[e] = sa[c][e] * ca;
+                x[4 + e] = sb[c][e] * cb;
+            }
+            online_softmax<D>(x, p, st[c], mask, tok0, row_end[c], qd);
+            // the weight sum takes the unscaled weights; the product takes them times the page's V scale
+            st[c].l += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+            pop[c][0] = cvt_pk_bf16(p[0] * r.vs[0], p[1] * r.vs[0]);
+            pop[c][1] = cvt_pk_bf16(p[2] * r.vs[0], p[3] * r.vs[0]);
+            pop[c][2] = cvt_pk_bf16(p[4] * r.vs[1], p[5] * r.vs[1]);
+            pop[c][3] = cvt_pk_bf16(p[6] * r.vs[1], p[7] * r.vs[1]);
         }
-        online_softmax<D>(x, p, st, mask, tok0, row_end, qd);
-        // the weight sum takes the unscaled weights; the product takes them times the page's V scale
-        st.l += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
-        u32x4 pop;
-        pop[0] = cvt_pk_bf16(p[0] * r.vs[0], p[1] * r.vs[0]);
-        pop[1] = cvt_pk_bf16(p[2] * r.vs[0], p[3] * r.vs[0]);
-        pop[2] = cvt_pk_bf16(p[4] * r.vs[1], p[5] * r.vs[1]);
-        pop[3] = cvt_pk_bf16(p[6] * r.vs[1], p[7] * r.vs[1]);
 
         auto &v = r.v;
         if (ragged) {
@@ -427,7 +456,7 @@ struct Fp8Path {
                 for (int j = 0; j < 4; ++j)
                     if (tok0 + 16 * pg + 4 * qd + j >= t_end) v[pg][j] = u32x2{0, 0};
         }
-        // acc[i][r] = O[head lane&15][d = 8*(4qd + r) + i]: codes i, i+1 of four tokens at a time;
+        // acc[i][r] = O[row lane&15][d = 8*(4qd + r) + i]: codes i, i+1 of four tokens at a time;
         // converting to f32 and packing two tokens' values per register is the transposition.
 #pragma unroll
         for (int w = 0; w < 2; ++w) {
@@ -445,10 +474,19 @@ struct Fp8Path {
                     const int i = 4 * w + 2 * hi + ii;
                     const u32x4 a = {cvt_pk_bf16(f[0][0][ii], f[0][1][ii]), cvt_pk_bf16(f[0][2][ii], f[0][3][ii]),
                                      cvt_pk_bf16(f[1][0][ii], f[1][1][ii]), cvt_pk_bf16(f[1][2][ii], f[1][3][ii])};
-                    st.acc[i] = mfma_bf16_k32(a, pop, st.acc[i]);
+#pragma unroll
+                    for (int c = 0; c < NB; ++c) st[c].acc[i] = mfma_bf16_k32(a, pop[c], st[c].acc[i]);
                 }
             }
         }
+    }
+
+    SD_DEV static void attend(const u32x4 (&ka)[4], const u32x4 (&kb)[4], Tile &r, const u32x4 (&qop)[4],
+                              WaveState<D> &st, float scale_log2e, int tok0, int t_end, int lane, int row_end, bool mask)
+    {
+        const int ends[1] = {row_end};
+        attend_n<1>(ka, kb, r, reinterpret_cast<const u32x4 (&)[1][4]>(qop), reinterpret_cast<WaveState<D> (&)[1]>(st),
+                    scale_log2e, tok0, t_end, lane, ends, mask);
     }
 
     SD_DEV static void store_acc(const WaveState<D> &st, float *dst, int qd)

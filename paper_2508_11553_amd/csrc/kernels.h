@@ -11,6 +11,7 @@ constexpr int kPage = 16;           // tokens per page
 constexpr int kWaves = 4;           // waves per workgroup of the split pass
 constexpr int kTileTokens = 32;     // tokens one wave consumes per iteration (two pages)
 constexpr int kMaxGroup = 16;       // query heads per KV head that fit one MFMA tile
+constexpr int kPrefillBlocks = 2;   // 16-row column blocks one wave of the causal pass carries
 
 // Chunk slots of one output row.  Without a shared prefix, chunk c covers tokens
 // [c*chunk, (c+1)*chunk).  With a shared prefix of `sh` tokens (a multiple of
@@ -63,7 +64,7 @@ struct PrefillArgs {
     float scale_log2e;
     int32_t B, Hq, Hkv, G, max_blocks, max_context_len;
     int32_t total_q, max_q_len;  // rows of q; host-known bound on the rows of one sequence
-    int32_t q_blocks;            // workgroups (4 x 16/G query tokens each) that cover max_q_len
+    int32_t q_blocks;            // workgroups (4 waves x kPrefillBlocks x 16/G query tokens each) that cover max_q_len
 };
 
 struct AppendArgs {
