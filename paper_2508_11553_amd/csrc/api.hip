@@ -331,7 +331,7 @@ int paged_prefill_attention(const sd_shape *shape, const void *q, const int32_t 
     a.max_q_len = max_q_len < total_q ? max_q_len : total_q;
     const int tokens_per_wg = sd::kWaves * sd::kPrefillBlocks * (a.G <= sd::kMaxGroup / 2 ? sd::kMaxGroup / a.G : 1);
     a.q_blocks = (a.max_q_len + tokens_per_wg - 1) / tokens_per_wg;
-    if ((uint64_t)a.q_blocks * (uint64_t)a.B * (uint64_t)a.Hkv > 0x7fffffffull) return SD_EUNSUPPORTED;
+    if ((uint64_t)a.q_blocks * (uint64_t)a.B * (uint64_t)a.Hkv > 0x7ffffff0ull) return SD_EUNSUPPORTED;
     hipEvent_t none[2] = {nullptr, nullptr};
     hipEvent_t *ev = timer ? &timer->ev[(size_t)timer->calls * 4] : none;
     const hipError_t e = sd::launch_prefill(a, shape->head_dim, shape->kv_dtype, static_cast<hipStream_t>(stream), ev[0], ev[1]);

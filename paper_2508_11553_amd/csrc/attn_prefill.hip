@@ -10,14 +10,13 @@
 // KV head), which share every K operand fetched from LDS and every V operand
 // formed in registers.  The K/V tiles are the same for the four waves: per round each
 // wave loads a different 32-token tile from HBM (one round ahead), parks the K
-// image and its V registers in an LDS slot, and after a barrier every wave
-// attends the four tiles from LDS with its own columns.  Each wave carries its
+// image and the ready-made V^T operands in an LDS slot, and after a barrier
+// every wave attends the four tiles from LDS with its own columns.  Each wave carries its
 // rows through the whole range with the online softmax, so there is no split
 // and no merge: the wave normalises and writes its rows itself.
 //
 // The causal limit is a per-lane token bound in the score mask; a wave stops
 // once a tile starts at or past the last position any of its rows may see.
-// The grid runs the blocks of late positions (long ranges) first.
 #include "attn_tile.h"
 
 namespace sd {
@@ -26,16 +25,22 @@ template <class P>
 __global__ __launch_bounds__(kWaves * 64, 2) void prefill_kernel(PrefillArgs a)
 {
     constexpr int D = P::kDim;
-    constexpr int kSlot = Lds<P>::kSlotBytes;
+    constexpr int kSlot = Lds<P>::kParkedSlotBytes;
     constexpr int NB = kPrefillBlocks;
     __shared__ __attribute__((aligned(16))) char lds[kWaves * kSlot];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const unsigned item = blockIdx.x;  // (query block counted from the back, sequence, kv head), kv head fastest
-    const int g = item % a.Hkv;
-    const int b = (item / a.Hkv) % a.B;
-    const int jb = a.q_blocks - 1 - (int)(item / (a.Hkv * a.B));
+    // Workgroup i runs on XCD i % 8, and each XCD has its own L2.  All query blocks of one
+    // (sequence, kv head) read the same K/V, so they get consecutive slots of ONE XCD (query
+    // block fastest, late positions = long ranges first): they run side by side, walk the
+    // range at about the same pace, and all but the first find the tiles in that L2.
+    const unsigned per_xcd = gridDim.x / kXcds;  // the grid is padded to a multiple of kXcds
+    const unsigned item = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+    if (item >= (unsigned)a.q_blocks * (unsigned)a.B * (unsigned)a.Hkv) return;
+    const int jb = a.q_blocks - 1 - (int)(item % a.q_blocks);
+    const int g = (item / a.q_blocks) % a.Hkv;
+    const int b = item / ((unsigned)a.q_blocks * a.Hkv);
     const int tpb = a.G <= kMaxGroup / 2 ? kMaxGroup / a.G : 1;  // query tokens per column block
     const int tpw = kPrefillBlocks * tpb;                        // and per wave
 
@@ -67,7 +72,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void prefill_kernel(PrefillArgs a)
     };
     int row_end[NB];
     u32x4 qop[NB][D / 32];
-    WaveState<D> st[NB];
+    typename P::ParkedState st[NB];
 #pragma unroll
     for (int c = 0; c < NB; ++c) {
         bool in_range, row_ok;
@@ -104,7 +109,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void prefill_kernel(PrefillArgs a)
             const int tn = kWaves * min(rd + 1, rounds - 1) + wave;
             const int na = bt[min(2 * tn, last_page)], nb = bt[min(2 * tn + 1, last_page)];
             P::k_store(r, mine, lane);
-            P::v_store(r, mine + P::kScratchBytes, lane);
+            P::v_park(r, mine + P::kScratchBytes, lane, (kWaves * rd + wave) * kTileTokens, L);
             if (rd + 1 < rounds) issue(r, na, nb);
             __syncthreads();
             if (active) {
@@ -114,11 +119,9 @@ __global__ __launch_bounds__(kWaves * 64, 2) void prefill_kernel(PrefillArgs a)
                     if (tok0 >= wave_max_end) break;  // wave-uniform
                     const char *slot = lds + j * kSlot;
                     u32x4 ka[D / 32], kb[D / 32];
-                    typename P::Tile t;
                     P::k_fetch(slot, lane, ka, kb);
-                    P::v_fetch(t, slot + P::kScratchBytes, lane);
-                    P::template attend_n<NB>(ka, kb, t, qop, st, a.scale_log2e, tok0, L, lane, row_end,
-                                             tok0 + kTileTokens > wave_min_end);
+                    P::template attend_parked<NB>(ka, kb, slot + P::kScratchBytes, qop, st, a.scale_log2e, tok0, lane,
+                                                  row_end, tok0 + kTileTokens > wave_min_end);
                 }
             }
             __syncthreads();
@@ -126,13 +129,13 @@ __global__ __launch_bounds__(kWaves * 64, 2) void prefill_kernel(PrefillArgs a)
     }
 #pragma unroll
     for (int c = 0; c < NB; ++c) {
-        st[c].l = head_sum(st[c].l);
+        const float l = P::weight_sum(st[c]);
         bool in_range, row_ok;
         int64_t row;
         locate(c, in_range, row_ok, row);
         if (!in_range) continue;
         // rows before the sequence's first token get zeros
-        const float inv = row_ok ? 1.0f / st[c].l : 0.0f;
+        const float inv = row_ok ? 1.0f / l : 0.0f;
 #pragma unroll
         for (int k = 0; k < D / 16; ++k) st[c].acc[k] = row_ok ? st[c].acc[k] * inv : f32x4{0, 0, 0, 0};
         P::store_acc(st[c], a.out + row * D, lane >> 4);
@@ -142,8 +145,9 @@ __global__ __launch_bounds__(kWaves * 64, 2) void prefill_kernel(PrefillArgs a)
 hipError_t launch_prefill(const PrefillArgs &a, int head_dim, int kv_dtype, hipStream_t stream, hipEvent_t start,
                           hipEvent_t stop)
 {
-    const unsigned grid = (unsigned)a.q_blocks * (unsigned)a.B * (unsigned)a.Hkv;
-    if (grid == 0) return hipSuccess;
+    const unsigned items = (unsigned)a.q_blocks * (unsigned)a.B * (unsigned)a.Hkv;
+    if (items == 0) return hipSuccess;
+    const unsigned grid = (items + kXcds - 1) / kXcds * kXcds;
     const dim3 g(grid), b(kWaves * 64);
     auto go = [&](auto kernel) {
         if (start || stop)

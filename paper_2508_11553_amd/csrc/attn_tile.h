@@ -85,11 +85,13 @@ SD_DEV void wave_lds_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <int D>
+template <int D, int EXTRA = 0>
 struct WaveState {
+    static constexpr int kAcc = D / 16 + EXTRA;
     float m;             // running max of this lane's head (same in the 4 lanes of a head)
     float l;             // this lane's share of the weight sum
-    f32x4 acc[D / 16];   // O^T accumulators; which d each one holds is the path's business
+    f32x4 acc[kAcc];     // O^T accumulators; which d each one holds is the path's business
+                         // (EXTRA = 1: one more that accumulates the weights themselves)
 };
 
 // Scores of one tile -> weights.  x holds, for row lane&15, the scaled scores
@@ -99,8 +101,8 @@ struct WaveState {
 // set (wave-uniform: some row of the wave ends inside the tile).  Updates the
 // running max and rescales the accumulators when some row's max moved.
 // Returns exp2(x - m) in p.
-template <int D>
-SD_DEV void online_softmax(float (&x)[8], float (&p)[8], WaveState<D> &st, bool mask, int tok0, int row_end, int qd)
+template <class State>
+SD_DEV void online_softmax(float (&x)[8], float (&p)[8], State &st, bool mask, int tok0, int row_end, int qd)
 {
     if (mask) {  // mask by position, never by content
 #pragma unroll
@@ -119,7 +121,7 @@ SD_DEV void online_softmax(float (&x)[8], float (&p)[8], WaveState<D> &st, bool 
     st.l *= alpha;
     if (__builtin_amdgcn_ballot_w64(alpha != 1.0f)) {
 #pragma unroll
-        for (int i = 0; i < D / 16; ++i) st.acc[i] *= alpha;
+        for (int i = 0; i < State::kAcc; ++i) st.acc[i] *= alpha;
     }
 }
 
@@ -244,7 +246,7 @@ struct Bf16Path {
                 x[e] = sa[c][e] * scale_log2e;
                 x[4 + e] = sb[c][e] * scale_log2e;
             }
-            online_softmax<D>(x, p, st[c], mask, tok0, row_end[c], qd);
+            online_softmax(x, p, st[c], mask, tok0, row_end[c], qd);
             float psum = 0.f;
 #pragma unroll
             for (int e = 0; e < 8; e += 2) {
@@ -291,6 +293,92 @@ struct Bf16Path {
         }
     }
 
+    // --- V^T operands formed once by the wave that loaded the tile -------------
+    // When several waves consume a tile from LDS, the loading wave turns its V
+    // registers into the D/16 A operands of the second product (tokens >= t_end
+    // zeroed) and parks those; each consumer then reads an operand with one
+    // 16-byte LDS load per lane instead of re-forming it with byte permutes.
+    static constexpr int kOpsBytes = (D / 16) * 1024;
+    typedef WaveState<D, 1> ParkedState;  // acc[D/16] sums the rounded weights through the MFMA
+
+    SD_DEV static void v_park(Tile &r, char *vslot, int lane, int tok0, int t_end)
+    {
+        const int qd = lane >> 4;
+        auto &v = r.v;
+        if (tok0 + kTileTokens > t_end) {
+#pragma unroll
+            for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (tok0 + 16 * pg + 4 * qd + j >= t_end) {
+#pragma unroll
+                        for (int h = 0; h < D / 64; ++h) v[pg][h][j] = u32x2{0, 0};
+                    }
+        }
+#pragma unroll
+        for (int h = 0; h < D / 64; ++h)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int w = i >> 1;
+                u32x4 a;
+                if (i & 1) {
+                    a[0] = pack_hi(v[0][h][0][w], v[0][h][1][w]);
+                    a[1] = pack_hi(v[0][h][2][w], v[0][h][3][w]);
+                    a[2] = pack_hi(v[1][h][0][w], v[1][h][1][w]);
+                    a[3] = pack_hi(v[1][h][2][w], v[1][h][3][w]);
+                } else {
+                    a[0] = pack_lo(v[0][h][0][w], v[0][h][1][w]);
+                    a[1] = pack_lo(v[0][h][2][w], v[0][h][3][w]);
+                    a[2] = pack_lo(v[1][h][0][w], v[1][h][1][w]);
+                    a[3] = pack_lo(v[1][h][2][w], v[1][h][3][w]);
+                }
+                *reinterpret_cast<u32x4 *>(vslot + (4 * h + i) * 1024 + lane * 16) = a;
+            }
+    }
+
+    // attend_n with the V^T operands read from `vslot`; the weight sum is one more
+    // accumulator fed an all-ones operand, so it is the sum of the rounded weights exactly
+    template <int NB>
+    SD_DEV static void attend_parked(const u32x4 (&ka)[D / 32], const u32x4 (&kb)[D / 32], const char *vslot,
+                                     const u32x4 (&qop)[NB][D / 32], ParkedState (&st)[NB], float scale_log2e,
+                                     int tok0, int lane, const int (&row_end)[NB], bool mask)
+    {
+        const int qd = lane >> 4;
+        f32x4 sa[NB], sb[NB];
+#pragma unroll
+        for (int c = 0; c < NB; ++c) sa[c] = sb[c] = f32x4{0, 0, 0, 0};
+#pragma unroll
+        for (int s = 0; s < D / 32; ++s)
+#pragma unroll
+            for (int c = 0; c < NB; ++c) {
+                sa[c] = mfma_bf16_k32(ka[s], qop[c][s], sa[c]);
+                sb[c] = mfma_bf16_k32(kb[s], qop[c][s], sb[c]);
+            }
+        u32x4 pop[NB];
+#pragma unroll
+        for (int c = 0; c < NB; ++c) {
+            float x[8], p[8];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                x[e] = sa[c][e] * scale_log2e;
+                x[4 + e] = sb[c][e] * scale_log2e;
+            }
+            online_softmax(x, p, st[c], mask, tok0, row_end[c], qd);
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) pop[c][e >> 1] = cvt_pk_bf16(p[e], p[e + 1]);
+        }
+        const u32x4 ones = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};  // bf16 1.0 pairs
+#pragma unroll
+        for (int c = 0; c < NB; ++c) st[c].acc[D / 16] = mfma_bf16_k32(ones, pop[c], st[c].acc[D / 16]);
+#pragma unroll
+        for (int k = 0; k < D / 16; ++k) {
+            const u32x4 a = *reinterpret_cast<const u32x4 *>(vslot + k * 1024 + lane * 16);
+#pragma unroll
+            for (int c = 0; c < NB; ++c) st[c].acc[k] = mfma_bf16_k32(a, pop[c], st[c].acc[k]);
+        }
+    }
+    SD_DEV static float weight_sum(const ParkedState &st) { return st.acc[D / 16][0]; }
+
     // one column block
     SD_DEV static void attend(const u32x4 (&ka)[D / 32], const u32x4 (&kb)[D / 32], Tile &r,
                               const u32x4 (&qop)[D / 32], WaveState<D> &st, float scale_log2e, int tok0, int t_end,
@@ -302,7 +390,8 @@ struct Bf16Path {
     }
 
     // this lane's accumulators -> row `dst` ([D] floats) of its head
-    SD_DEV static void store_acc(const WaveState<D> &st, float *dst, int qd)
+    template <class State>
+    SD_DEV static void store_acc(const State &st, float *dst, int qd)
     {
 #pragma unroll
         for (int h = 0; h < D / 64; ++h)
@@ -439,7 +528,7 @@ struct Fp8Path {
                 x[e] = sa[c][e] * ca;
                 x[4 + e] = sb[c][e] * cb;
             }
-            online_softmax<D>(x, p, st[c], mask, tok0, row_end[c], qd);
+            online_softmax(x, p, st[c], mask, tok0, row_end[c], qd);
             // the weight sum takes the unscaled weights; the product takes them times the page's V scale
             st[c].l += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
             pop[c][0] = cvt_pk_bf16(p[0] * r.vs[0], p[1] * r.vs[0]);
@@ -481,6 +570,87 @@ struct Fp8Path {
         }
     }
 
+    // --- V^T operands formed once by the wave that loaded the tile (see Bf16Path) ---
+    // Eight bf16 operands (exact conversions of the codes) and the four page scales.
+    static constexpr int kOpsBytes = 8 * 1024 + 16;
+    typedef WaveState<D> ParkedState;
+
+    SD_DEV static void v_park(Tile &r, char *vslot, int lane, int tok0, int t_end)
+    {
+        const int qd = lane >> 4;
+        auto &v = r.v;
+        if (tok0 + kTileTokens > t_end) {
+#pragma unroll
+            for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (tok0 + 16 * pg + 4 * qd + j >= t_end) v[pg][j] = u32x2{0, 0};
+        }
+#pragma unroll
+        for (int w = 0; w < 2; ++w)
+#pragma unroll
+            for (int hi = 0; hi < 2; ++hi) {
+                f32x2 f[2][4];
+#pragma unroll
+                for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        f[pg][j] = hi ? __builtin_amdgcn_cvt_pk_f32_fp8(v[pg][j][w], true)
+                                      : __builtin_amdgcn_cvt_pk_f32_fp8(v[pg][j][w], false);
+#pragma unroll
+                for (int ii = 0; ii < 2; ++ii) {
+                    const int i = 4 * w + 2 * hi + ii;
+                    const u32x4 a = {cvt_pk_bf16(f[0][0][ii], f[0][1][ii]), cvt_pk_bf16(f[0][2][ii], f[0][3][ii]),
+                                     cvt_pk_bf16(f[1][0][ii], f[1][1][ii]), cvt_pk_bf16(f[1][2][ii], f[1][3][ii])};
+                    *reinterpret_cast<u32x4 *>(vslot + i * 1024 + lane * 16) = a;
+                }
+            }
+        if (lane == 0) *reinterpret_cast<f32x4 *>(vslot + 8 * 1024) = f32x4{r.ks[0], r.ks[1], r.vs[0], r.vs[1]};
+    }
+
+    template <int NB>
+    SD_DEV static void attend_parked(const u32x4 (&ka)[4], const u32x4 (&kb)[4], const char *vslot,
+                                     const u32x4 (&qop)[NB][4], ParkedState (&st)[NB], float scale_log2e, int tok0,
+                                     int lane, const int (&row_end)[NB], bool mask)
+    {
+        const int qd = lane >> 4;
+        const f32x4 sc = *reinterpret_cast<const f32x4 *>(vslot + 8 * 1024);  // k scales, v scales of the two pages
+        f32x4 sa[NB], sb[NB];
+#pragma unroll
+        for (int c = 0; c < NB; ++c) sa[c] = sb[c] = f32x4{0, 0, 0, 0};
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int c = 0; c < NB; ++c) {
+                sa[c] = mfma_bf16_k32(ka[s], qop[c][s], sa[c]);
+                sb[c] = mfma_bf16_k32(kb[s], qop[c][s], sb[c]);
+            }
+        const float ca = scale_log2e * sc[0], cb = scale_log2e * sc[1];
+        u32x4 pop[NB];
+#pragma unroll
+        for (int c = 0; c < NB; ++c) {
+            float x[8], p[8];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                x[e] = sa[c][e] * ca;
+                x[4 + e] = sb[c][e] * cb;
+            }
+            online_softmax(x, p, st[c], mask, tok0, row_end[c], qd);
+            st[c].l += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+            pop[c][0] = cvt_pk_bf16(p[0] * sc[2], p[1] * sc[2]);
+            pop[c][1] = cvt_pk_bf16(p[2] * sc[2], p[3] * sc[2]);
+            pop[c][2] = cvt_pk_bf16(p[4] * sc[3], p[5] * sc[3]);
+            pop[c][3] = cvt_pk_bf16(p[6] * sc[3], p[7] * sc[3]);
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const u32x4 a = *reinterpret_cast<const u32x4 *>(vslot + k * 1024 + lane * 16);
+#pragma unroll
+            for (int c = 0; c < NB; ++c) st[c].acc[k] = mfma_bf16_k32(a, pop[c], st[c].acc[k]);
+        }
+    }
+    SD_DEV static float weight_sum(const ParkedState &st) { return head_sum(st.l); }
+
     SD_DEV static void attend(const u32x4 (&ka)[4], const u32x4 (&kb)[4], Tile &r, const u32x4 (&qop)[4],
                               WaveState<D> &st, float scale_log2e, int tok0, int t_end, int lane, int row_end, bool mask)
     {
@@ -489,7 +659,8 @@ struct Fp8Path {
                     scale_log2e, tok0, t_end, lane, ends, mask);
     }
 
-    SD_DEV static void store_acc(const WaveState<D> &st, float *dst, int qd)
+    template <class State>
+    SD_DEV static void store_acc(const State &st, float *dst, int qd)
     {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -501,13 +672,13 @@ struct Fp8Path {
     }
 };
 
-template <int D>
-SD_DEV void reset(WaveState<D> &st)
+template <class State>
+SD_DEV void reset(State &st)
 {
     st.m = -INFINITY;
     st.l = 0.f;
 #pragma unroll
-    for (int i = 0; i < D / 16; ++i) st.acc[i] = f32x4{0, 0, 0, 0};
+    for (int i = 0; i < State::kAcc; ++i) st.acc[i] = f32x4{0, 0, 0, 0};
 }
 
 // LDS of one workgroup.  Plain items: per-wave K scratch plus the merge
@@ -519,6 +690,7 @@ struct Lds {
     static constexpr int kSlotBytes = P::kScratchBytes + ((P::kVBytes + 15) / 16) * 16;
     static constexpr int kPlainBytes = kWaves * P::kScratchBytes + kWaves * kMaxGroup * kRow * 4 + 2 * kWaves * kMaxGroup * 4;
     static constexpr int kSharedBytes = kWaves * kSlotBytes;
+    static constexpr int kParkedSlotBytes = P::kScratchBytes + ((P::kOpsBytes + 15) / 16) * 16;  // K image + V^T operands
     static constexpr int kBytes = kPlainBytes > kSharedBytes ? kPlainBytes : kSharedBytes;
 };
 

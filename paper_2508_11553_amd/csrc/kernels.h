@@ -11,6 +11,7 @@ constexpr int kPage = 16;           // tokens per page
 constexpr int kWaves = 4;           // waves per workgroup of the split pass
 constexpr int kTileTokens = 32;     // tokens one wave consumes per iteration (two pages)
 constexpr int kMaxGroup = 16;       // query heads per KV head that fit one MFMA tile
+constexpr int kXcds = 8;            // accelerator dies, each with its own L2; workgroup i runs on die i % 8
 constexpr int kPrefillBlocks = 2;   // 16-row column blocks one wave of the causal pass carries
 
 // Chunk slots of one output row.  Without a shared prefix, chunk c covers tokens
