@@ -121,6 +121,87 @@ def cpu_baseline(cfg, wall_target=10.0):
     }
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 peak
+
+
+def prefill_main(args):
+    """--prefill: the causal multi-query pass (paged_prefill_attention) at a resume shape: every
+    sequence re-computes attention for the last `nq` of its L stored tokens.  One step = one call.
+    Reported in TFLOP/s of the causal work, 4 * d flops per (query row, visible token) pair."""
+    import numpy as np
+    import torch
+
+    import paper_2508_11553_amd as sd
+    import workloads
+    from paper_2508_11553_amd.device import DeviceWorkload, _to_dev
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    sd.load()
+    torch.cuda.set_device(0)
+    B, L, nq, Hq, Hkv, d = 16, 8192, 2048, 32, 8, 128
+    wl = workloads.make_custom([L] * B, Hq, Hkv, d, args.prefill_kv, seed=0)
+    dw = DeviceWorkload(wl)
+    rng = np.random.default_rng(1)
+    q = workloads.f32_to_bf16_bits(rng.standard_normal((B * nq, Hq, d)).astype(np.float32))
+    q_start = (np.arange(B + 1) * nq).astype(np.int32)
+    q_dev, qs_dev = _to_dev(q, dw.device), _to_dev(q_start, dw.device)
+    out = torch.zeros((B * nq, Hq, d), dtype=torch.float32, device=dw.device)
+    stream = torch.cuda.current_stream()
+
+    def call(timer=None):
+        sd.paged_prefill_attention(dw.shape, q_dev, qs_dev, B * nq, nq, dw.k_pages, dw.v_pages, dw.k_scales,
+                                   dw.v_scales, dw.block_table, dw.context_lens, dw.scale, out, stream, timer)
+
+    for _ in range(args.warmup):
+        call()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        call()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) / args.steps * 1e3
+    timer = sd.KernelTimer(args.steps)
+    for _ in range(args.steps):
+        call(timer)
+    torch.cuda.synchronize()
+    kernel_ms = float(np.mean(timer.read()[0]))
+    pairs = B * Hq * sum(L - nq + i + 1 for i in range(nq))
+    flops = 4.0 * d * pairs
+    rec = {
+        "metric": "causal re-prefill attention over the paged cache, TFLOP/s, 1 GPU",
+        "value": flops / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if wl.kv_dtype == "bf16" else "fp8(e4m3fn KV)->bf16", "data": "synthetic",
+        "config": {"workload": f"resume: {B} sequences of {L} tokens re-compute their last {nq}", "batch": B,
+                   "q_heads": Hq, "kv_heads": Hkv, "head_dim": d, "page_size": 16, "kv_dtype": wl.kv_dtype,
+                   "query_rows": B * nq, "row_token_pairs": pairs, "entry_point": "paged_prefill_attention", "seed": 0},
+        "kernel_ms": {"prefill": kernel_ms},
+        "roofline": {"bound": "mfma", "achieved": flops / (kernel_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": flops / (kernel_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                     "traffic": None, "kernel": "causal pass (sd::prefill_kernel)", "flops_per_launch": flops},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        b0 = slice(0, 1)
+
+        def run(n):  # the last n query rows of sequence 0, all heads
+            qs = np.int32([0, n])
+            t = time.perf_counter()
+            oracle.paged_prefill_attention(q[nq - n:nq], qs, wl.k_pages, wl.v_pages, wl.block_table[b0],
+                                           wl.context_lens[b0], wl.scale, wl.k_scales, wl.v_scales, wl.kv_dtype)
+            return time.perf_counter() - t
+
+        run(1)
+        n = max(1, min(nq, int(10.0 / max(run(2) / 2, 1e-6))))
+        dt = run(n)
+        sample_pairs = Hq * sum(L - n + i + 1 for i in range(n))
+        rec["cpu_baseline"] = {"value": 4.0 * d * sample_pairs / dt / 1e12, "unit": "TFLOP/s",
+                               "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": f"the last {n} query rows of sequence 0, all heads, fp64 oracle, {dt:.2f} s"}
+    print(json.dumps(rec), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -135,10 +216,15 @@ def main():
                     help="branching workloads: use the plain entry point instead of the shared-prefix aware one")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a device copy of known size (counter calibration for profiler runs)")
+    ap.add_argument("--prefill", action="store_true",
+                    help="time the causal multi-query pass at a resume shape instead of the decode step")
+    ap.add_argument("--prefill-kv", choices=["bf16", "fp8"], default="bf16")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
+    if args.prefill:
+        return prefill_main(args)
 
     import numpy as np
     import torch

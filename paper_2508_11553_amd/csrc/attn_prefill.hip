@@ -113,7 +113,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void prefill_kernel(PrefillArgs a)
             if (rd + 1 < rounds) issue(r, na, nb);
             __syncthreads();
             if (active) {
-#pragma unroll 1
+#pragma unroll 2
                 for (int j = 0; j < kWaves; ++j) {
                     const int tok0 = (kWaves * rd + j) * kTileTokens;
                     if (tok0 >= wave_max_end) break;  // wave-uniform
