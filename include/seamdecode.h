@@ -145,6 +145,25 @@ int kv_append_fp8(const sd_shape *shape, const void *k_new, const void *v_new,
                   const int32_t *block_table, void *stream);
 
 /*
+ * kv_copy_pages -- copy whole pages inside the pool.
+ *
+ * A session that branches where its last page is partly filled cannot share
+ * that page: every branch will write its own next token into it.  Each new
+ * branch gets a private copy (sessions branch into trajectories that continue a
+ * common prefix, Data Plane; see sd_tree_fork).  For i < num_copies the K and V
+ * tiles of all KV heads of page src_pages[i], and for SD_FP8_E4M3 its scales,
+ * are copied to page dst_pages[i], bit for bit.
+ *
+ *   src_pages, dst_pages  i32 [num_copies] (device); a pair with an id outside
+ *                         [0, num_pages) or with src == dst is skipped
+ * A page that is the destination of one pair and the source or destination of
+ * another pair of the same call races.
+ */
+int kv_copy_pages(const sd_shape *shape, const int32_t *src_pages, const int32_t *dst_pages,
+                  int32_t num_copies, void *k_pages, void *v_pages, float *k_scales, float *v_scales,
+                  void *stream);
+
+/*
  * paged_decode_attention -- one decode step of attention for every sequence.
  *
  * For each sequence b with L = min(context_lens[b], max_context_len) tokens
@@ -261,6 +280,15 @@ int paged_prefill_attention(const sd_shape *shape, const void *q, const int32_t 
  *                         appended from that position on only.
  *   sd_tree_match         the same count without storing anything
  *   sd_tree_release       drops a trajectory; unreferenced pages return to the pool
+ *   sd_tree_fork          a second trajectory with the same tokens (a session branching):
+ *                         shares every full page; a partly filled last page gets a
+ *                         fresh private page, reported as *copy_src -> *copy_dst (-1, -1
+ *                         when there is none) for kv_copy_pages.  Returns the new id,
+ *                         SD_EINVAL or SD_EWORKSPACE
+ *   sd_tree_append        one more token (a decode step); *page / *slot (optional) = where
+ *                         its K/V rows go.  Takes a page from the pool when the last one
+ *                         was full (SD_EWORKSPACE if none).  A page that fills up becomes
+ *                         shareable by later inserts unless an equal one already is
  *   sd_tree_block_table   writes min(pages, cap) page ids, returns the page count
  *   sd_tree_token_at      token id / model version stored at a position
  *   sd_tree_batch_groups  for trajectories in batch order: consecutive ones that
@@ -277,6 +305,8 @@ int32_t sd_tree_match(const sd_tree *t, const int32_t *tokens, const uint32_t *v
 int32_t sd_tree_insert(sd_tree *t, const int32_t *tokens, const uint32_t *versions, int32_t n,
                        int32_t *matched_tokens);
 int sd_tree_release(sd_tree *t, int32_t traj);
+int32_t sd_tree_fork(sd_tree *t, int32_t traj, int32_t *copy_src, int32_t *copy_dst);
+int sd_tree_append(sd_tree *t, int32_t traj, int32_t token, uint32_t version, int32_t *page, int32_t *slot);
 int32_t sd_tree_length(const sd_tree *t, int32_t traj);
 int32_t sd_tree_block_table(const sd_tree *t, int32_t traj, int32_t *pages_out, int32_t cap);
 int sd_tree_token_at(const sd_tree *t, int32_t traj, int32_t pos, int32_t *token, uint32_t *version);

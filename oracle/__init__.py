@@ -173,6 +173,19 @@ def kv_append(k_new, v_new, seq_ids, positions, k_pages, v_pages, block_table):
        ctypes.c_int(T), _p(k_pages), _p(v_pages), _p(block_table))
 
 
+def kv_copy_pages(src_pages, dst_pages, k_pages, v_pages, k_scales=None, v_scales=None):
+    """In-place copy of whole pages src -> dst (K, V, and the scales of fp8 pools)."""
+    assert k_pages.flags.c_contiguous and v_pages.flags.c_contiguous and k_pages.flags.writeable
+    src_pages, dst_pages = _c(src_pages, np.int32), _c(dst_pages, np.int32)
+    assert len(src_pages) == len(dst_pages)
+    num_pages, Hkv, _, d = k_pages.shape
+    fn = lib().oracle_kv_copy_pages
+    fn.restype = None
+    fn(ctypes.c_int(num_pages), ctypes.c_int(Hkv), ctypes.c_int(d), ctypes.c_int(k_pages.dtype.itemsize),
+       _p(src_pages), _p(dst_pages), ctypes.c_int(len(src_pages)), _p(k_pages), _p(v_pages),
+       _p(k_scales) if k_scales is not None else None, _p(v_scales) if v_scales is not None else None)
+
+
 def float_to_e4m3fn(y: float) -> int:
     f = lib().oracle_float_to_e4m3fn
     f.restype = ctypes.c_uint8

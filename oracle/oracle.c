@@ -88,6 +88,31 @@ void oracle_kv_append(int Hkv, int d, int max_blocks, int elem_bytes,
     }
 }
 
+/*
+ * Whole-page copy inside the pool (a branch of a session whose last page is
+ * partly filled gets a private copy of that page): for each pair, every byte
+ * of page src -- all KV heads, K and V -- and, when the pool has scales, its
+ * Hkv scales go to page dst.  Pairs are taken in order; a pair with an id
+ * outside [0, num_pages) or with src == dst does nothing.
+ */
+void oracle_kv_copy_pages(int num_pages, int Hkv, int d, int elem_bytes,
+                          const int32_t *src_pages, const int32_t *dst_pages, int n,
+                          void *k_pages, void *v_pages, float *k_scales, float *v_scales)
+{
+    size_t page = (size_t)Hkv * ORACLE_PAGE * (size_t)d * (size_t)elem_bytes;
+    for (int i = 0; i < n; ++i) {
+        int s = src_pages[i], t = dst_pages[i];
+        if (s < 0 || t < 0 || s >= num_pages || t >= num_pages || s == t) continue;
+        memcpy((char *)k_pages + (size_t)t * page, (const char *)k_pages + (size_t)s * page, page);
+        memcpy((char *)v_pages + (size_t)t * page, (const char *)v_pages + (size_t)s * page, page);
+        if (k_scales && v_scales)
+            for (int g = 0; g < Hkv; ++g) {
+                k_scales[(size_t)t * Hkv + g] = k_scales[(size_t)s * Hkv + g];
+                v_scales[(size_t)t * Hkv + g] = v_scales[(size_t)s * Hkv + g];
+            }
+    }
+}
+
 #define REAL double
 #define REAL_EXP exp
 #define NAME(x) x##_f64

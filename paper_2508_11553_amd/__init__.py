@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     chunk_tokens,
     kv_append,
     kv_append_fp8,
+    kv_copy_pages,
     lib_path,
     load,
     paged_decode_attention,

@@ -72,6 +72,8 @@ def load():
     L.paged_decode_attention_prefix.restype = ctypes.c_int
     L.paged_decode_attention_prefix.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, vp, vp, sz,
                                                 vp, vp]
+    L.kv_copy_pages.restype = ctypes.c_int
+    L.kv_copy_pages.argtypes = [sp, vp, vp, i32, vp, vp, vp, vp, vp]
     L.paged_prefill_attention.restype = ctypes.c_int
     L.paged_prefill_attention.argtypes = [sp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp]
     L.sd_timer_create.restype = vp
@@ -206,6 +208,13 @@ def paged_decode_attention_prefix(shape: Shape, q, k_pages, v_pages, k_scales, v
         int(max_shared_len), float(scale), _ptr(out), _ptr(workspace), int(workspace_nbytes), _stream(stream),
         timer._h if timer is not None else None)
     _check(rc, "paged_decode_attention_prefix")
+
+
+def kv_copy_pages(shape: Shape, src_pages, dst_pages, num_copies: int, k_pages, v_pages, k_scales=None, v_scales=None,
+                  stream=None):
+    rc = load().kv_copy_pages(ctypes.byref(shape), _ptr(src_pages), _ptr(dst_pages), int(num_copies), _ptr(k_pages),
+                              _ptr(v_pages), _ptr(k_scales), _ptr(v_scales), _stream(stream))
+    _check(rc, "kv_copy_pages")
 
 
 def paged_prefill_attention(shape: Shape, q, q_start, total_q: int, max_q_len: int, k_pages, v_pages, k_scales,

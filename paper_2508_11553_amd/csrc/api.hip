@@ -190,6 +190,31 @@ int kv_append_fp8(const sd_shape *shape, const void *k_new, const void *v_new, c
     return e == hipSuccess ? SD_OK : hip_fail(e);
 }
 
+int kv_copy_pages(const sd_shape *shape, const int32_t *src_pages, const int32_t *dst_pages, int32_t num_copies,
+                  void *k_pages, void *v_pages, float *k_scales, float *v_scales, void *stream)
+{
+    const int rc = check_shape(shape);
+    if (rc) return rc;
+    if (num_copies < 0 || num_copies > 0x3fffffff) return SD_EINVAL;
+    if (num_copies == 0) return SD_OK;
+    if (bad_ptr(src_pages) || bad_ptr(dst_pages) || bad_ptr(k_pages) || bad_ptr(v_pages)) return SD_EINVAL;
+    const bool fp8 = shape->kv_dtype == SD_FP8_E4M3;
+    if (fp8 && (bad_ptr(k_scales) || bad_ptr(v_scales))) return SD_EINVAL;
+    sd::CopyPagesArgs a;
+    a.src_pages = src_pages;
+    a.dst_pages = dst_pages;
+    a.k_pages = static_cast<uint4 *>(k_pages);
+    a.v_pages = static_cast<uint4 *>(v_pages);
+    a.k_scales = fp8 ? k_scales : nullptr;
+    a.v_scales = fp8 ? v_scales : nullptr;
+    a.N = num_copies;
+    a.Hkv = shape->num_kv_heads;
+    a.num_pages = shape->num_pages;
+    a.page_words = shape->num_kv_heads * sd::kPage * shape->head_dim * (fp8 ? 1 : 2) / 16;
+    const hipError_t e = sd::launch_copy_pages(a, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SD_OK : hip_fail(e);
+}
+
 int paged_decode_attention_prefix(const sd_shape *shape, const void *q, const void *k_pages,
                                   const void *v_pages, const float *k_scales, const float *v_scales,
                                   const int32_t *block_table, const int32_t *context_lens,

@@ -87,6 +87,14 @@ struct AppendFp8Args {
     int32_t single_rows;         // every range has at most one row (the decode step)
 };
 
+struct CopyPagesArgs {
+    const int32_t *src_pages, *dst_pages;  // [N]
+    uint4 *k_pages, *v_pages;              // pools viewed as 16-byte words
+    float *k_scales, *v_scales;            // [num_pages][Hkv] or null
+    int32_t N, Hkv, num_pages;
+    int32_t page_words;                    // 16-byte words of one page over all heads
+};
+
 struct ProbeArgs {
     const void *k_pages, *v_pages;
     const int32_t *block_table, *context_lens;
@@ -107,6 +115,7 @@ hipError_t launch_prefill(const PrefillArgs &a, int head_dim, int kv_dtype, hipS
                           hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
 hipError_t launch_append(const AppendArgs &a, int head_dim, hipStream_t stream);
 hipError_t launch_append_fp8(const AppendFp8Args &a, hipStream_t stream);
+hipError_t launch_copy_pages(const CopyPagesArgs &a, hipStream_t stream);
 hipError_t launch_probe(const ProbeArgs &a, hipStream_t stream);
 
 }  // namespace sd

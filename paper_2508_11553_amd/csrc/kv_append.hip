@@ -240,4 +240,28 @@ hipError_t launch_append_fp8(const AppendFp8Args &a, hipStream_t stream)
     return hipGetLastError();
 }
 
+// Whole-page copies inside the pool: one workgroup per (pair, K or V); the page of
+// all heads is contiguous, so this is a straight 16-byte-per-lane copy.  The first
+// workgroup of a pair also copies the page's scales.
+__global__ __launch_bounds__(256) void copy_pages_kernel(CopyPagesArgs a)
+{
+    const int pair = blockIdx.x >> 1, is_v = blockIdx.x & 1;
+    const int src = a.src_pages[pair], dst = a.dst_pages[pair];
+    if (src < 0 || dst < 0 || src >= a.num_pages || dst >= a.num_pages || src == dst) return;
+    uint4 *pool = is_v ? a.v_pages : a.k_pages;
+    const uint4 *from = pool + (int64_t)src * a.page_words;
+    uint4 *to = pool + (int64_t)dst * a.page_words;
+    for (int i = threadIdx.x; i < a.page_words; i += 256) to[i] = from[i];
+    float *scales = is_v ? a.v_scales : a.k_scales;
+    if (scales)
+        for (int i = threadIdx.x; i < a.Hkv; i += 256) scales[(int64_t)dst * a.Hkv + i] = scales[(int64_t)src * a.Hkv + i];
+}
+
+hipError_t launch_copy_pages(const CopyPagesArgs &a, hipStream_t stream)
+{
+    if (a.N <= 0) return hipSuccess;
+    hipLaunchKernelGGL(copy_pages_kernel, dim3(2u * (unsigned)a.N), dim3(256), 0, stream, a);
+    return hipGetLastError();
+}
+
 }  // namespace sd

@@ -40,6 +40,8 @@ struct Node {
     int32_t page = -1;
     int32_t parent = -1;  // node index, -1 for children of the root
     int32_t refs = 0;     // trajectories whose path contains this node
+    bool listed = true;   // reachable through its parent's child map (a page that filled up during
+                          // decoding next to an equal, already listed page stays unlisted)
     PageKey key;
     std::map<PageKey, int32_t> children;
 };
@@ -188,13 +190,94 @@ int sd_tree_release(sd_tree *t, int32_t traj)
     for (int32_t i = (int32_t)tr.path.size() - 1; i >= 0; --i) {
         const int32_t node = tr.path[i];
         if (--t->nodes[node].refs == 0) {
-            t->kids(t->nodes[node].parent).erase(t->nodes[node].key);
+            if (t->nodes[node].listed) t->kids(t->nodes[node].parent).erase(t->nodes[node].key);
             t->give_page(t->nodes[node].page);
             t->free_nodes.push_back(node);
         }
     }
     if (tr.tail_page >= 0) t->give_page(tr.tail_page);
     tr = Traj();
+    return SD_OK;
+}
+
+// A second trajectory with the same tokens: it shares every full page of `traj`;
+// a partly filled last page is private, so the copy gets a fresh page and the
+// caller must copy the old one into it (kv_copy_pages) before either side appends.
+// *copy_src / *copy_dst receive that page pair, or -1 / -1 when there is nothing
+// to copy.  Returns the new trajectory id, SD_EINVAL, or SD_EWORKSPACE (no free
+// page; nothing is changed then).
+int32_t sd_tree_fork(sd_tree *t, int32_t traj, int32_t *copy_src, int32_t *copy_dst)
+{
+    if (!t || traj < 0 || traj >= (int32_t)t->trajs.size() || !t->trajs[traj].live) return SD_EINVAL;
+    Traj copy = t->trajs[traj];
+    int32_t src = -1, dst = -1;
+    if (copy.tail_page >= 0) {
+        dst = t->take_page();
+        if (dst < 0) return SD_EWORKSPACE;
+        src = copy.tail_page;
+        copy.tail_page = dst;
+    }
+    for (int32_t node : copy.path) t->nodes[node].refs++;
+    if (copy_src) *copy_src = src;
+    if (copy_dst) *copy_dst = dst;
+    for (size_t i = 0; i < t->trajs.size(); ++i)
+        if (!t->trajs[i].live) {
+            t->trajs[i] = std::move(copy);
+            return (int32_t)i;
+        }
+    t->trajs.push_back(std::move(copy));
+    return (int32_t)t->trajs.size() - 1;
+}
+
+// One more token at the end of a trajectory (a decode step).  *page / *slot
+// (optional) receive where its K/V rows go: the trajectory's last page, which is
+// taken from the pool when the previous one was full.  A page that fills up
+// becomes a tree node: listed under its parent (later inserts can share it)
+// unless an equal page is already listed there, in which case it stays private.
+// Returns SD_OK, SD_EINVAL, or SD_EWORKSPACE (no free page; nothing is changed).
+int sd_tree_append(sd_tree *t, int32_t traj, int32_t token, uint32_t version, int32_t *page, int32_t *slot)
+{
+    if (!t || traj < 0 || traj >= (int32_t)t->trajs.size() || !t->trajs[traj].live) return SD_EINVAL;
+    if (t->trajs[traj].tail_page < 0) {
+        const int32_t fresh = t->take_page();
+        if (fresh < 0) return SD_EWORKSPACE;
+        t->trajs[traj].tail_page = fresh;
+    }
+    Traj &tr = t->trajs[traj];
+    if (page) *page = tr.tail_page;
+    if (slot) *slot = (int32_t)tr.tail_tok.size();
+    tr.tail_tok.push_back(token);
+    tr.tail_ver.push_back(version);
+    tr.length++;
+    if ((int32_t)tr.tail_tok.size() < kPage) return SD_OK;
+
+    PageKey k;
+    for (int i = 0; i < kPage; ++i) {
+        k.tok[i] = tr.tail_tok[i];
+        k.ver[i] = tr.tail_ver[i];
+    }
+    const int32_t parent = tr.path.empty() ? -1 : tr.path.back();
+    int32_t node;
+    if (!t->free_nodes.empty()) {
+        node = t->free_nodes.back();
+        t->free_nodes.pop_back();
+        t->nodes[node] = Node();
+    } else {
+        node = (int32_t)t->nodes.size();
+        t->nodes.emplace_back();
+    }
+    Node &nd = t->nodes[node];
+    nd.page = tr.tail_page;
+    nd.parent = parent;
+    nd.key = k;
+    nd.refs = 1;
+    auto &level = t->kids(parent);  // after emplace_back: nodes may have moved
+    nd.listed = level.find(k) == level.end();
+    if (nd.listed) level[k] = node;
+    tr.path.push_back(node);
+    tr.tail_page = -1;
+    tr.tail_tok.clear();
+    tr.tail_ver.clear();
     return SD_OK;
 }
 

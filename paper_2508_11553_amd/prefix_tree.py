@@ -18,6 +18,8 @@ def _lib():
         L.sd_tree_match.restype, L.sd_tree_match.argtypes = i32, [vp, vp, vp, i32]
         L.sd_tree_insert.restype, L.sd_tree_insert.argtypes = i32, [vp, vp, vp, i32, vp]
         L.sd_tree_release.restype, L.sd_tree_release.argtypes = ctypes.c_int, [vp, i32]
+        L.sd_tree_fork.restype, L.sd_tree_fork.argtypes = i32, [vp, i32, vp, vp]
+        L.sd_tree_append.restype, L.sd_tree_append.argtypes = ctypes.c_int, [vp, i32, i32, ctypes.c_uint32, vp, vp]
         L.sd_tree_length.restype, L.sd_tree_length.argtypes = i32, [vp, i32]
         L.sd_tree_block_table.restype, L.sd_tree_block_table.argtypes = i32, [vp, i32, vp, i32]
         L.sd_tree_token_at.restype, L.sd_tree_token_at.argtypes = ctypes.c_int, [vp, i32, i32, vp, vp]
@@ -73,6 +75,23 @@ class PrefixTree:
         rc = int(_lib().sd_tree_release(self._h, int(traj)))
         if rc:
             raise sd.SeamDecodeError(rc, "sd_tree_release")
+
+    def fork(self, traj: int):
+        """-> (new trajectory id, page to copy from, page to copy to); the pages are -1 if nothing is to be copied."""
+        src, dst = ctypes.c_int32(-1), ctypes.c_int32(-1)
+        rc = int(_lib().sd_tree_fork(self._h, int(traj), ctypes.byref(src), ctypes.byref(dst)))
+        if rc < 0:
+            raise sd.SeamDecodeError(rc, "sd_tree_fork")
+        return rc, int(src.value), int(dst.value)
+
+    def append(self, traj: int, token: int, version: int = 0):
+        """One more token; -> (page, slot) its K/V rows go to."""
+        page, slot = ctypes.c_int32(-1), ctypes.c_int32(-1)
+        rc = int(_lib().sd_tree_append(self._h, int(traj), int(token), int(version), ctypes.byref(page),
+                                       ctypes.byref(slot)))
+        if rc:
+            raise sd.SeamDecodeError(rc, "sd_tree_append")
+        return int(page.value), int(slot.value)
 
     def length(self, traj: int) -> int:
         return int(_lib().sd_tree_length(self._h, int(traj)))

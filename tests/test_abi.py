@@ -117,6 +117,19 @@ def test_prefill_arguments_are_checked_on_the_host(lib):
     assert lib.paged_prefill_attention(ctypes.byref(s8), *args) == -1  # fp8 needs scales
 
 
+def test_copy_pages_arguments_are_checked_on_the_host(lib):
+    s = good_shape()
+    assert lib.kv_copy_pages(ctypes.byref(s), None, None, 0, None, None, None, None, None) == 0
+    assert lib.kv_copy_pages(ctypes.byref(s), 16, 32, -1, 48, 64, None, None, None) == -1
+    for i in range(2):
+        for j in (0, 1, 3, 4):
+            args = [16, 32, 2, 48, 64, None, None, None]
+            args[j] = (None, 24)[i]
+            assert lib.kv_copy_pages(ctypes.byref(s), *args) == -1
+    s8 = good_shape(kv_dtype=sd.SD_FP8_E4M3, head_dim=128)
+    assert lib.kv_copy_pages(ctypes.byref(s8), 16, 32, 2, 48, 64, None, None, None) == -1  # fp8 pools come with scales
+
+
 def test_empty_calls_are_noops(lib):
     s = good_shape(batch=0)
     assert lib.paged_decode_attention(ctypes.byref(s), None, None, None, None, None, None, None, 1.0, None, None, 0, None) == 0

@@ -117,3 +117,71 @@ def test_batch_groups_describe_common_pages():
         if g + 1 < len(gs) - 1:
             a, b = gs[g], gs[g + 1]
             assert len(want_tr[a]) < 16 or len(want_tr[b]) < 16 or tables[a][0] != tables[b][0]
+
+
+def test_fork_shares_full_pages_and_copies_the_partial_one():
+    t = PrefixTree(64)
+    toks = list(range(40))                      # two full pages and a tail of 8
+    a, _ = t.insert(toks)
+    used = t.pages_in_use
+    b, src, dst = t.fork(a)
+    ta, tb = t.block_table(a), t.block_table(b)
+    assert (ta[:2] == tb[:2]).all() and ta[2] != tb[2]
+    assert (src, dst) == (ta[2], tb[2]) and t.pages_in_use == used + 1
+    assert t.length(b) == 40 and [t.token_at(b, i)[0] for i in range(40)] == toks
+    # a fork at a page boundary has nothing to copy
+    c, _ = t.insert(list(range(100, 132)))
+    d, src, dst = t.fork(c)
+    assert (src, dst) == (-1, -1) and (t.block_table(c) == t.block_table(d)).all()
+    # the branches form one group that shares the full pages
+    gs, sh = t.batch_groups([a, b])
+    assert gs.tolist() == [0, 2] and sh.tolist() == [32, 32]
+    t.release(a)
+    assert t.block_table(b).tolist() == tb.tolist()     # shared pages survive the release of one branch
+    t.release(b); t.release(c); t.release(d)
+    assert t.pages_in_use == 0
+
+
+def test_append_walks_pages_and_fills_the_tree_like_an_insert():
+    """Decoding token by token ends in the same state as inserting the final sequence: same sharing, same
+    tokens, same page count; the reported (page, slot) is where the block table says the token lives."""
+    rng = np.random.default_rng(5)
+    t = PrefixTree(256)
+    prompt = rng.integers(0, 50, size=21).tolist()
+    a, _ = t.insert(prompt)
+    b, src, dst = t.fork(a)
+    grown = {a: list(prompt), b: list(prompt)}
+    for step in range(45):
+        for tr in (a, b):
+            tok = int(rng.integers(0, 50)) if step > 12 or tr == a else grown[a][len(grown[b])]  # b copies a's next tokens for a while
+            page, slot = t.append(tr, tok, version=step // 20)
+            grown[tr].append(tok)
+            pos = len(grown[tr]) - 1
+            assert slot == pos % 16 and t.length(tr) == pos + 1
+            assert t.block_table(tr)[pos // 16] == page
+            assert t.token_at(tr, pos) == (tok, step // 20)
+    # b decoded the same tokens as a up to position 21 + 13 = 34: the page that filled up at 32 tokens is equal in
+    # both, but each branch wrote its own copy, so only one of them is listed and the other stays private
+    ta, tb = t.block_table(a), t.block_table(b)
+    assert ta[0] == tb[0] and ta[1] != tb[1]
+    # a later insert of a's tokens finds all of a's full pages
+    vers = [0] * 21 + [s // 20 for s in range(45)]
+    c, matched = t.insert(grown[a], vers)
+    assert matched == len(grown[a]) // 16 * 16
+    assert (t.block_table(c)[:matched // 16] == ta[:matched // 16]).all()
+    for tr in (a, b, c):
+        t.release(tr)
+    assert t.pages_in_use == 0
+
+
+def test_fork_and_append_report_an_exhausted_pool():
+    from paper_2508_11553_amd.binding import SeamDecodeError
+    t = PrefixTree(3)
+    a, _ = t.insert(list(range(40)))            # 3 pages: pool full
+    with pytest.raises(SeamDecodeError):
+        t.fork(a)                               # needs a page for the tail copy
+    for i in range(8):
+        t.append(a, i)                          # fills the tail: no new page needed
+    with pytest.raises(SeamDecodeError):
+        t.append(a, 99)
+    assert t.length(a) == 48 and t.pages_in_use == 3
