@@ -216,6 +216,8 @@ def main():
                     help="branching workloads: use the plain entry point instead of the shared-prefix aware one")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a device copy of known size (counter calibration for profiler runs)")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay each step from a captured HIP graph instead of launching its kernels one by one")
     ap.add_argument("--prefill", action="store_true",
                     help="time the causal multi-query pass at a resume shape instead of the decode step")
     ap.add_argument("--prefill-kv", choices=["bf16", "fp8"], default="bf16")
@@ -268,9 +270,30 @@ def main():
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
+    run_step = step
+    if args.graph:
+        # One HIP graph per pool holds the whole step (append, split pass, merge pass); the timed
+        # loop replays them in rotation.  The library's launches neither allocate nor synchronise.
+        side = torch.cuda.Stream()
+        graphs = []
+        with torch.cuda.stream(side):
+            for i in range(npools):
+                g = torch.cuda.CUDAGraph()
+                stream, keep = side, stream
+                step(i)  # warm-up on the capture stream
+                side.synchronize()
+                with torch.cuda.graph(g, stream=side):
+                    step(i)
+                stream = keep
+                graphs.append(g)
+        torch.cuda.synchronize()
+        run_step = lambda i: graphs[i % npools].replay()
+        for i in range(npools):
+            run_step(i)
+        torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(i)
+        run_step(i)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
