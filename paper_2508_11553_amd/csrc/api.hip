@@ -345,7 +345,11 @@ int paged_prefill_attention(const sd_shape *shape, const void *q, const int32_t 
     a.block_table = block_table;
     a.context_lens = context_lens;
     a.out = out;
-    a.scale_log2e = scale * 1.4426950408889634f;
+    // the kernel folds a non-negative scale into its exponent; a negative one is the same problem with -q
+    a.scale_log2e = (scale < 0 ? -scale : scale) * 1.4426950408889634f;
+    a.q_flip = scale < 0 ? 0x80008000u : 0u;
+    a.q_keep = scale == 0 ? 0u : 0xffffffffu;
+    if (scale == 0) a.scale_log2e = 1.0f;  // zero queries give the same all-zero scores without 0 * inf in the mask
     a.B = shape->batch;
     a.Hq = shape->num_q_heads;
     a.Hkv = shape->num_kv_heads;

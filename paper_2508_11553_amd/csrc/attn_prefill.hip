@@ -82,7 +82,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void prefill_kernel(PrefillArgs a)
         row_end[c] = row_ok ? base + i + 1 : L;
 #pragma unroll
         for (int s = 0; s < D / 32; ++s)
-            qop[c][s] = row_ok ? *reinterpret_cast<const u32x4 *>(a.q + row * D + P::q_offset(s, lane))
+            qop[c][s] = row_ok ? (*reinterpret_cast<const u32x4 *>(a.q + row * D + P::q_offset(s, lane)) & a.q_keep) ^ a.q_flip
                                : u32x4{0, 0, 0, 0};
         reset(st[c]);
     }

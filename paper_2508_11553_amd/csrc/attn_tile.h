@@ -337,44 +337,70 @@ struct Bf16Path {
     }
 
     // attend_n with the V^T operands read from `vslot`; the weight sum is one more
-    // accumulator fed an all-ones operand, so it is the sum of the rounded weights exactly
+    // accumulator fed an all-ones operand, so it is the sum of the rounded weights
+    // exactly.  The score scale c = scale * log2(e) must be positive here: it is
+    // folded into the exponent, p = exp2(s * c - m), with one fused multiply-add
+    // per score, and the running max is taken over the raw scores.  The V^T
+    // operands are requested before the softmax arithmetic so that the LDS
+    // latency passes behind it.
     template <int NB>
     SD_DEV static void attend_parked(const u32x4 (&ka)[D / 32], const u32x4 (&kb)[D / 32], const char *vslot,
-                                     const u32x4 (&qop)[NB][D / 32], ParkedState (&st)[NB], float scale_log2e,
-                                     int tok0, int lane, const int (&row_end)[NB], bool mask)
+                                     const u32x4 (&qop)[NB][D / 32], ParkedState (&st)[NB], float c, int tok0,
+                                     int lane, const int (&row_end)[NB], bool mask)
     {
         const int qd = lane >> 4;
         f32x4 sa[NB], sb[NB];
 #pragma unroll
-        for (int c = 0; c < NB; ++c) sa[c] = sb[c] = f32x4{0, 0, 0, 0};
+        for (int b = 0; b < NB; ++b) sa[b] = sb[b] = f32x4{0, 0, 0, 0};
 #pragma unroll
         for (int s = 0; s < D / 32; ++s)
 #pragma unroll
-            for (int c = 0; c < NB; ++c) {
-                sa[c] = mfma_bf16_k32(ka[s], qop[c][s], sa[c]);
-                sb[c] = mfma_bf16_k32(kb[s], qop[c][s], sb[c]);
+            for (int b = 0; b < NB; ++b) {
+                sa[b] = mfma_bf16_k32(ka[s], qop[b][s], sa[b]);
+                sb[b] = mfma_bf16_k32(kb[s], qop[b][s], sb[b]);
             }
+        u32x4 va[D / 16];
+#pragma unroll
+        for (int k = 0; k < D / 16; ++k) va[k] = *reinterpret_cast<const u32x4 *>(vslot + k * 1024 + lane * 16);
+        __builtin_amdgcn_sched_barrier(0);
         u32x4 pop[NB];
 #pragma unroll
-        for (int c = 0; c < NB; ++c) {
-            float x[8], p[8];
+        for (int b = 0; b < NB; ++b) {
+            float x[8];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                x[e] = sa[c][e] * scale_log2e;
-                x[4 + e] = sb[c][e] * scale_log2e;
+                x[e] = sa[b][e];
+                x[4 + e] = sb[b][e];
             }
-            online_softmax(x, p, st[c], mask, tok0, row_end[c], qd);
+            if (mask) {  // by position, never by content
 #pragma unroll
-            for (int e = 0; e < 8; e += 2) pop[c][e >> 1] = cvt_pk_bf16(p[e], p[e + 1]);
+                for (int e = 0; e < 4; ++e) {
+                    if (tok0 + 4 * qd + e >= row_end[b]) x[e] = -INFINITY;
+                    if (tok0 + 16 + 4 * qd + e >= row_end[b]) x[4 + e] = -INFINITY;
+                }
+            }
+            float tmax = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+            tmax = head_max(tmax);
+            const float m_new = fmaxf(st[b].m, tmax * c);
+            const float alpha = __builtin_amdgcn_exp2f(st[b].m - m_new);
+            st[b].m = m_new;
+            float p[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(x[e], c, -m_new));
+            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f)) {
+#pragma unroll
+                for (int i = 0; i < ParkedState::kAcc; ++i) st[b].acc[i] *= alpha;
+            }
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) pop[b][e >> 1] = cvt_pk_bf16(p[e], p[e + 1]);
         }
         const u32x4 ones = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};  // bf16 1.0 pairs
 #pragma unroll
-        for (int c = 0; c < NB; ++c) st[c].acc[D / 16] = mfma_bf16_k32(ones, pop[c], st[c].acc[D / 16]);
+        for (int b = 0; b < NB; ++b) st[b].acc[D / 16] = mfma_bf16_k32(ones, pop[b], st[b].acc[D / 16]);
 #pragma unroll
         for (int k = 0; k < D / 16; ++k) {
-            const u32x4 a = *reinterpret_cast<const u32x4 *>(vslot + k * 1024 + lane * 16);
 #pragma unroll
-            for (int c = 0; c < NB; ++c) st[c].acc[k] = mfma_bf16_k32(a, pop[c], st[c].acc[k]);
+            for (int b = 0; b < NB; ++b) st[b].acc[k] = mfma_bf16_k32(va[k], pop[b], st[b].acc[k]);
         }
     }
     SD_DEV static float weight_sum(const ParkedState &st) { return st.acc[D / 16][0]; }

@@ -62,7 +62,9 @@ struct PrefillArgs {
     const float *k_scales, *v_scales;
     const int32_t *block_table, *context_lens;
     float *out;                  // [total_q][Hq][D]
-    float scale_log2e;
+    float scale_log2e;           // |scale| * log2(e); the sign of scale travels in q_flip
+    uint32_t q_flip;             // 0x80008000 when scale < 0: every query element changes sign as it is loaded
+    uint32_t q_keep;             // 0 when scale == 0 (all scores are zero: zero queries, scale 1), else all ones
     int32_t B, Hq, Hkv, G, max_blocks, max_context_len;
     int32_t total_q, max_q_len;  // rows of q; host-known bound on the rows of one sequence
     int32_t q_blocks;            // workgroups (4 waves x kPrefillBlocks x 16/G query tokens each) that cover max_q_len

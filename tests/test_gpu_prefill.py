@@ -54,6 +54,18 @@ def test_ragged_query_counts_over_several_tiles(sd, Hq, Hkv, d, kv_dtype):
     check(gpu(wl, q, q_start), ref(wl, q, q_start), kv_dtype)
 
 
+@pytest.mark.parametrize("kv_dtype", ["bf16", "fp8"])
+@pytest.mark.parametrize("scale", [-0.11, 0.0])
+def test_negative_and_zero_scale(sd, scale, kv_dtype):
+    # the kernel works with |scale| and sign-flipped (or zeroed) queries; the result must be the oracle's for the scale given
+    lens, nq = [100, 33, 257], [40, 33, 9]
+    wl = workloads.make_custom(lens, 8, 2, 128, kv_dtype, seed=61, scale=scale)
+    rng = np.random.default_rng(62)
+    q_start = np.concatenate([[0], np.cumsum(nq)]).astype(np.int32)
+    q = f32_to_bf16_bits(rng.standard_normal((int(q_start[-1]), 8, 128)).astype(np.float32))
+    check(gpu(wl, q, q_start), ref(wl, q, q_start), kv_dtype)
+
+
 def test_one_query_per_sequence_equals_the_decode_step(sd):
     import torch
     lens = [1, 15, 16, 17, 200, 513, 1500]
