@@ -207,7 +207,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=1, help="workload index (BASELINE configs), default 1")
+    ap.add_argument("--config", type=int, default=1, help="workload index 0-4 (see workloads.CONFIG_NAMES), default 1")
     ap.add_argument("--chunk", type=int, default=0, help="split-K chunk override (tokens)")
     ap.add_argument("--pools", type=int, default=0, help="number of rotating K/V pools (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
