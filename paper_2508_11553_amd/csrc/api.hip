@@ -253,6 +253,9 @@ int paged_decode_attention_prefix(const sd_shape *shape, const void *q, const vo
     sa.ws_l = reinterpret_cast<float *>(ws + w.l_off);
     sa.ws_acc = reinterpret_cast<float *>(ws + w.acc_off);
     sa.scale_log2e = scale * 1.4426950408889634f;
+    sa.abs_scale_log2e = scale == 0 ? 1.0f : (scale < 0 ? -scale : scale) * 1.4426950408889634f;
+    sa.q_flip = scale < 0 ? 0x80008000u : 0u;
+    sa.q_keep = scale == 0 ? 0u : 0xffffffffu;
     sa.B = shape->batch;
     sa.Hq = shape->num_q_heads;
     sa.Hkv = shape->num_kv_heads;

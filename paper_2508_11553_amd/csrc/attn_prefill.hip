@@ -25,7 +25,7 @@ template <class P>
 __global__ __launch_bounds__(kWaves * 64, 2) void prefill_kernel(PrefillArgs a)
 {
     constexpr int D = P::kDim;
-    constexpr int kSlot = Lds<P>::kParkedSlotBytes;
+    constexpr int kSlot = Lds<P>::kSlotBytes;
     constexpr int NB = kPrefillBlocks;
     __shared__ __attribute__((aligned(16))) char lds[kWaves * kSlot];
 

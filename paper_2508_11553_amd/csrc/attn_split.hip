@@ -37,7 +37,7 @@ namespace sd {
 // masked by position).  `bt` points at the table entry of the chunk's first page.
 template <class P, bool STREAM>
 SD_DEV void stream_tiles(const SplitArgs &a, const int32_t *bt, int g, int t0, int t1, int first, int stride,
-                         const u32x4 (&qop)[P::kDim / 32], WaveState<P::kDim> &st, char *scratch, int lane)
+                         const u32x4 (&qop)[P::kDim / 32], typename P::State &st, char *scratch, int lane)
 {
     const int ntiles = (t1 - t0 + kTileTokens - 1) / kTileTokens;
     const int nt = ntiles > first ? (ntiles - first + stride - 1) / stride : 0;
@@ -66,7 +66,7 @@ SD_DEV void stream_tiles(const SplitArgs &a, const int32_t *bt, int g, int t0, i
         P::k_fetch(scratch, lane, ka, kb);
         wave_lds_fence();
         const int tok0 = t0 + (first + stride * i) * kTileTokens;
-        P::attend(ka, kb, r, qop, st, a.scale_log2e, tok0, t1, lane, t1, tok0 + kTileTokens > t1);
+        P::attend(ka, kb, r, qop, st, a.scale_log2e, tok0, t1, lane);
     };
     typename P::Tile ra, rb;
     int pa, pb;
@@ -135,8 +135,9 @@ SD_DEV void shared_item(const SplitArgs &a, char *lds, int lane, int wave)
     u32x4 qop[D / 32];
 #pragma unroll
     for (int s = 0; s < D / 32; ++s)
-        qop[s] = row_ok ? *reinterpret_cast<const u32x4 *>(a.q + row * D + P::q_offset(s, lane)) : u32x4{0, 0, 0, 0};
-    WaveState<D> st;
+        qop[s] = row_ok ? (*reinterpret_cast<const u32x4 *>(a.q + row * D + P::q_offset(s, lane)) & a.q_keep) ^ a.q_flip
+                        : u32x4{0, 0, 0, 0};
+    typename P::ParkedState st;
     reset(st);
 
     const int32_t *bt = a.block_table + (int64_t)gs * a.max_blocks + t0 / kPage;
@@ -159,32 +160,33 @@ SD_DEV void shared_item(const SplitArgs &a, char *lds, int lane, int wave)
         const int tn = kWaves * min(rd + 1, rounds - 1) + wave;
         const int na = bt[min(2 * tn, last_page)], nb = bt[min(2 * tn + 1, last_page)];
         P::k_store(r, mine, lane);
-        P::v_store(r, mine + P::kScratchBytes, lane);
+        P::v_park(r, mine + P::kScratchBytes, lane, t0 + (kWaves * rd + wave) * kTileTokens, t1);
         if (rd + 1 < rounds) issue(r, na, nb);
         __syncthreads();
         if (active) {
+            const int ends[1] = {t1};
 #pragma unroll 1
             for (int j = 0; j < kWaves; ++j) {
-                if (t0 + (kWaves * rd + j) * kTileTokens >= t1) break;  // wave-uniform
+                const int tok0 = t0 + (kWaves * rd + j) * kTileTokens;
+                if (tok0 >= t1) break;  // wave-uniform
                 const char *slot = lds + j * kSlot;
                 u32x4 ka[D / 32], kb[D / 32];
-                typename P::Tile t;
                 P::k_fetch(slot, lane, ka, kb);
-                P::v_fetch(t, slot + P::kScratchBytes, lane);
-                const int tok0 = t0 + (kWaves * rd + j) * kTileTokens;
-                P::attend(ka, kb, t, qop, st, a.scale_log2e, tok0, t1, lane, t1, tok0 + kTileTokens > t1);
+                P::template attend_parked<1>(ka, kb, slot + P::kScratchBytes, reinterpret_cast<const u32x4 (&)[1][D / 32]>(qop),
+                                             reinterpret_cast<typename P::ParkedState (&)[1]>(st), a.abs_scale_log2e, tok0,
+                                             lane, ends, tok0 + kTileTokens > t1);
             }
         }
         __syncthreads();
     }
     if (!active) return;
-    st.l = head_sum(st.l);
+    const float l = P::weight_sum(st);
     if (row_ok) {
         const int64_t slot = row * a.S + c;
         P::store_acc(st, a.ws_acc + slot * D, lane >> 4);
         if ((lane >> 4) == 0) {
             a.ws_m[slot] = st.m;
-            a.ws_l[slot] = st.l;
+            a.ws_l[slot] = l;
         }
     }
 }
@@ -242,7 +244,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void split_kernel(SplitArgs a)
             qop[s] = (n < a.G) ? *reinterpret_cast<const u32x4 *>(qrow + P::q_offset(s, lane)) : u32x4{0, 0, 0, 0};
     }
 
-    WaveState<D> st;
+    typename P::State st;
     reset(st);
     const int32_t *bt = a.block_table + (int64_t)b * a.max_blocks + t0 / kPage;
     stream_tiles<P, true>(a, bt, g, t0, t1, wave, kWaves, qop, st, s_k, lane);

@@ -1,7 +1,22 @@
 // Tile-level building blocks shared by the attention kernels of libseamdecode
 // (gfx950, wave64): MFMA wrappers, the online softmax of one 32-token tile, and
 // the two storage paths (bf16 pools, fp8 e4m3fn pools) with their loads, LDS
-// layouts and operand formation.  See attn_split.hip for how they are used.
+// layouts and operand formation.
+//
+// Every kernel computes the transposed products of one 32-token tile,
+//   S^T[token][row] = K[token][d] . Q^T[d][row]        mfma 16x16x32 bf16
+//   O^T[d][row]    += V^T[d][token] . P^T[token][row]   mfma 16x16x32 bf16
+// so that the accumulator layout of the first (lane = row, registers = tokens)
+// is the B-operand layout of the second and the weights never leave their
+// lanes.  A "row" is one query row: a query head in the decode pass, a (query
+// token, head) pair in the causal pass.  There are two ways to run the step:
+//
+//   attend         the wave owns the tile: K operands from its LDS scratch, V^T
+//                  operands formed in registers from the V rows it loaded
+//   attend_parked  the tile sits in an LDS slot that several waves consume: the
+//                  loading wave has parked the K image (k_store) and the
+//                  ready-made V^T operands (v_park); NB column blocks of 16 rows
+//                  share every operand read
 #pragma once
 #include "kernels.h"
 
@@ -46,9 +61,8 @@ SD_DEV unsigned cvt_pk_bf16_fp8(unsigned w)
 
 // K/V bytes that one wave uses once per launch are loaded with the
 // non-temporal hint, so that they stream through the caches instead of
-// displacing each other (STREAM = true).  Bytes that the four waves of a
-// workgroup all read (shared-prefix items) take ordinary loads: the first wave
-// to ask brings a line in and the caches serve the other three.
+// displacing each other (STREAM = true).  Bytes that other workgroups will ask
+// for again soon (the causal pass) take ordinary loads.
 template <bool STREAM, typename T>
 SD_DEV T kv_load(const T *p)
 {
@@ -56,7 +70,7 @@ SD_DEV T kv_load(const T *p)
     return *p;
 }
 
-// Reductions over the four lanes {n, n+16, n+32, n+48} that share a head.
+// Reductions over the four lanes {n, n+16, n+32, n+48} that share a row.
 // v_permlane16_swap exchanges rows 1<->0' and 3<->2' of its two operands and
 // v_permlane32_swap the upper half of one with the lower half of the other;
 // fed the same value twice they return (x, x from the partner row/half).
@@ -88,41 +102,77 @@ SD_DEV void wave_lds_fence()
 template <int D, int EXTRA = 0>
 struct WaveState {
     static constexpr int kAcc = D / 16 + EXTRA;
-    float m;             // running max of this lane's head (same in the 4 lanes of a head)
+    float m;             // running max of this lane's row, log2 domain (same in the 4 lanes of a row)
     float l;             // this lane's share of the weight sum
     f32x4 acc[kAcc];     // O^T accumulators; which d each one holds is the path's business
                          // (EXTRA = 1: one more that accumulates the weights themselves)
 };
 
-// Scores of one tile -> weights.  x holds, for row lane&15, the scaled scores
+template <class State>
+SD_DEV void reset(State &st)
+{
+    st.m = -INFINITY;
+    st.l = 0.f;
+#pragma unroll
+    for (int i = 0; i < State::kAcc; ++i) st.acc[i] = f32x4{0, 0, 0, 0};
+}
+
+// Positional mask of one tile's scores.  x holds, for row lane&15, the scores
 // of tokens tok0 + 4qd + e (e < 4, first page) and tok0 + 16 + 4qd + e - 4
 // (second page).  Tokens >= row_end (this lane's row: the end of the sequence
-// for a decode query, position + 1 for a causal one) are masked when `mask` is
-// set (wave-uniform: some row of the wave ends inside the tile).  Updates the
-// running max and rescales the accumulators when some row's max moved.
-// Returns exp2(x - m) in p.
-template <class State>
-SD_DEV void online_softmax(float (&x)[8], float (&p)[8], State &st, bool mask, int tok0, int row_end, int qd)
+// for a decode query, position + 1 for a causal one) become -inf: by position,
+// never by content.
+SD_DEV void mask_scores(float (&x)[8], int tok0, int row_end, int qd)
 {
-    if (mask) {  // mask by position, never by content
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            if (tok0 + 4 * qd + e >= row_end) x[e] = -INFINITY;
-            if (tok0 + 16 + 4 * qd + e >= row_end) x[4 + e] = -INFINITY;
-        }
+    for (int e = 0; e < 4; ++e) {
+        if (tok0 + 4 * qd + e >= row_end) x[e] = -INFINITY;
+        if (tok0 + 16 + 4 * qd + e >= row_end) x[4 + e] = -INFINITY;
     }
-    float tmax = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-    tmax = head_max(tmax);
-    const float m_new = fmaxf(st.m, tmax);
-    const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
-    st.m = m_new;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(x[e] - m_new);
+}
+
+SD_DEV float max8(const float (&x)[8])
+{
+    return fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+}
+
+// The running max moved by m_old -> m_new: everything accumulated so far shrinks
+// by alpha = exp2(m_old - m_new).  Skipped when no row of the wave moved.
+template <class State>
+SD_DEV void rescale(State &st, float alpha)
+{
     st.l *= alpha;
     if (__builtin_amdgcn_ballot_w64(alpha != 1.0f)) {
 #pragma unroll
         for (int i = 0; i < State::kAcc; ++i) st.acc[i] *= alpha;
     }
+}
+
+// Scaled scores x (log2 domain) of one tile -> weights p = exp2(x - m), with the
+// running max and the accumulators brought up to date.
+template <class State>
+SD_DEV void online_softmax(const float (&x)[8], float (&p)[8], State &st)
+{
+    const float m_new = fmaxf(st.m, head_max(max8(x)));
+    const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
+    st.m = m_new;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(x[e] - m_new);
+    rescale(st, alpha);
+}
+
+// The same for raw scores and a positive scale c (log2 domain) folded into the
+// exponent: p = exp2(s * c - m), one fused multiply-add per score; the max runs
+// over the raw scores.
+template <class State>
+SD_DEV void online_softmax_folded(const float (&s)[8], float c, float (&p)[8], State &st)
+{
+    const float m_new = fmaxf(st.m, head_max(max8(s)) * c);
+    const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
+    st.m = m_new;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], c, -m_new));
+    rescale(st, alpha);
 }
 
 // ---------------------------------------------------------------------------
@@ -131,18 +181,20 @@ SD_DEV void online_softmax(float (&x)[8], float (&p)[8], State &st, bool mask, i
 template <int D>
 struct Bf16Path {
     static constexpr int kDim = D;
-    static constexpr int kTileBytes = kPage * D * 2;     // one (page, head) tile
+    static constexpr int kTileBytes = kPage * D * 2;      // one (page, head) tile
     static constexpr int kScratchBytes = 2 * kTileBytes;  // K of one 32-token tile in LDS
-    static constexpr int kVBytes = 2 * kTileBytes;        // V registers of one tile parked in LDS
+    static constexpr int kOpsBytes = (D / 16) * 1024;     // the V^T operands of one tile in LDS
     static constexpr int kPieces = D / 8;                 // 16-byte pieces per K row
     static constexpr int kRowsPerLoad = 64 / kPieces;     // K rows one 1024-byte load covers
+    typedef WaveState<D> State;
+    typedef WaveState<D, 1> ParkedState;  // acc[D/16] sums the rounded weights through the MFMA
 
     struct Tile {
         u32x4 k[2][D / 32];     // [page][j]: 16 bytes at byte offset 1024*j + 16*lane of the K tile
         u32x2 v[2][D / 64][4];  // [page][half][j]: V row 4*(lane>>4)+j, d = 64*half + 4*(lane&15) .. +4
     };
 
-    // Q^T operand of step s: head lane&15, d = 32*s + 8*(lane>>4) .. +8
+    // Q^T operand of step s: row lane&15, d = 32*s + 8*(lane>>4) .. +8
     SD_DEV static int q_offset(int s, int lane) { return 32 * s + 8 * (lane >> 4); }
 
     template <bool STREAM>
@@ -187,162 +239,90 @@ struct Bf16Path {
         }
     }
 
-    // V registers (the same for every wave that consumes the tile) parked in LDS, lane-linear
-    SD_DEV static void v_store(const Tile &r, char *vslot, int lane)
+    // V rows of tokens that do not exist (>= t_end) may hold anything, NaN
+    // included; they are zeroed so that weight 0 times them is 0.
+    SD_DEV static void v_sanitise(Tile &r, int tok0, int t_end, int qd)
     {
+        if (tok0 + kTileTokens <= t_end) return;  // wave-uniform
 #pragma unroll
         for (int pg = 0; pg < 2; ++pg)
 #pragma unroll
-            for (int h = 0; h < D / 64; ++h)
+            for (int j = 0; j < 4; ++j)
+                if (tok0 + 16 * pg + 4 * qd + j >= t_end) {
 #pragma unroll
-                for (int jj = 0; jj < 2; ++jj) {
-                    const u32x4 w = {r.v[pg][h][2 * jj][0], r.v[pg][h][2 * jj][1], r.v[pg][h][2 * jj + 1][0],
-                                     r.v[pg][h][2 * jj + 1][1]};
-                    *reinterpret_cast<u32x4 *>(vslot + ((pg * (D / 64) + h) * 2 + jj) * 1024 + lane * 16) = w;
+                    for (int h = 0; h < D / 64; ++h) r.v[pg][h][j] = u32x2{0, 0};
                 }
     }
-    SD_DEV static void v_fetch(Tile &r, const char *vslot, int lane)
+
+    // V^T operand k = 4h + i of the second product, formed inside the lane with
+    // byte permutes: it feeds acc[k][r] = O[row lane&15][d = 64h + 16qd + 4r + i].
+    SD_DEV static u32x4 v_operand(const Tile &r, int h, int i)
     {
-#pragma unroll
-        for (int pg = 0; pg < 2; ++pg)
-#pragma unroll
-            for (int h = 0; h < D / 64; ++h)
-#pragma unroll
-                for (int jj = 0; jj < 2; ++jj) {
-                    const u32x4 w = *reinterpret_cast<const u32x4 *>(vslot + ((pg * (D / 64) + h) * 2 + jj) * 1024 + lane * 16);
-                    r.v[pg][h][2 * jj] = u32x2{w[0], w[1]};
-                    r.v[pg][h][2 * jj + 1] = u32x2{w[2], w[3]};
-                }
+        const auto &v = r.v;
+        const int w = i >> 1;
+        if (i & 1)
+            return u32x4{pack_hi(v[0][h][0][w], v[0][h][1][w]), pack_hi(v[0][h][2][w], v[0][h][3][w]),
+                         pack_hi(v[1][h][0][w], v[1][h][1][w]), pack_hi(v[1][h][2][w], v[1][h][3][w])};
+        return u32x4{pack_lo(v[0][h][0][w], v[0][h][1][w]), pack_lo(v[0][h][2][w], v[0][h][3][w]),
+                     pack_lo(v[1][h][0][w], v[1][h][1][w]), pack_lo(v[1][h][2][w], v[1][h][3][w])};
     }
 
     // Scores, online softmax and weighted V sum of one 32-token tile (tokens
-    // tok0 .. tok0+31) for NB column blocks of 16 rows each, which share the K
-    // operands ka/kb and the V registers r.v.  Tokens >= t_end do not exist
-    // (their V is zeroed); the row of block c in this lane additionally ends at
-    // row_end[c] <= t_end; `mask` (wave-uniform) says some row ends inside the tile.
-    template <int NB>
-    SD_DEV static void attend_n(const u32x4 (&ka)[D / 32], const u32x4 (&kb)[D / 32], Tile &r,
-                                const u32x4 (&qop)[NB][D / 32], WaveState<D> (&st)[NB], float scale_log2e, int tok0,
-                                int t_end, int lane, const int (&row_end)[NB], bool mask)
+    // tok0 .. tok0+31, those < t_end exist) for the wave that loaded it.
+    SD_DEV static void attend(const u32x4 (&ka)[D / 32], const u32x4 (&kb)[D / 32], Tile &r,
+                              const u32x4 (&qop)[D / 32], State &st, float scale_log2e, int tok0, int t_end, int lane)
     {
         const int qd = lane >> 4;
-        f32x4 sa[NB], sb[NB];
+        f32x4 sa = {0, 0, 0, 0}, sb = {0, 0, 0, 0};
 #pragma unroll
-        for (int c = 0; c < NB; ++c) sa[c] = sb[c] = f32x4{0, 0, 0, 0};
-#pragma unroll
-        for (int s = 0; s < D / 32; ++s)
-#pragma unroll
-            for (int c = 0; c < NB; ++c) {
-                sa[c] = mfma_bf16_k32(ka[s], qop[c][s], sa[c]);
-                sb[c] = mfma_bf16_k32(kb[s], qop[c][s], sb[c]);
-            }
-        const bool ragged = tok0 + kTileTokens > t_end;  // wave-uniform
-        u32x4 pop[NB];
-#pragma unroll
-        for (int c = 0; c < NB; ++c) {
-            float x[8], p[8];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                x[e] = sa[c][e] * scale_log2e;
-                x[4 + e] = sb[c][e] * scale_log2e;
-            }
-            online_softmax(x, p, st[c], mask, tok0, row_end[c], qd);
-            float psum = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; e += 2) {
-                const unsigned w = cvt_pk_bf16(p[e], p[e + 1]);
-                pop[c][e >> 1] = w;
-                // the sum runs over the rounded weights, the ones the product below uses
-                psum += __builtin_bit_cast(float, w << 16) + __builtin_bit_cast(float, w & 0xffff0000u);
-            }
-            st[c].l += psum;
+        for (int s = 0; s < D / 32; ++s) {
+            sa = mfma_bf16_k32(ka[s], qop[s], sa);
+            sb = mfma_bf16_k32(kb[s], qop[s], sb);
         }
-
-        auto &v = r.v;
-        if (ragged) {  // slots past the end may hold anything, NaN included: 0 * NaN must not happen
+        float x[8], p[8];
 #pragma unroll
-            for (int pg = 0; pg < 2; ++pg)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (tok0 + 16 * pg + 4 * qd + j >= t_end) {
-#pragma unroll
-                        for (int h = 0; h < D / 64; ++h) v[pg][h][j] = u32x2{0, 0};
-                    }
+        for (int e = 0; e < 4; ++e) {
+            x[e] = sa[e] * scale_log2e;
+            x[4 + e] = sb[e] * scale_log2e;
         }
-        // acc[4h + i][r] = O[row lane&15][d = 64h + 16qd + 4r + i]
+        if (tok0 + kTileTokens > t_end) mask_scores(x, tok0, t_end, qd);  // wave-uniform
+        online_softmax(x, p, st);
+        u32x4 pop;
+        float psum = 0.f;
 #pragma unroll
-        for (int h = 0; h < D / 64; ++h) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int w = i >> 1;
-                u32x4 a;
-                if (i & 1) {
-                    a[0] = pack_hi(v[0][h][0][w], v[0][h][1][w]);
-                    a[1] = pack_hi(v[0][h][2][w], v[0][h][3][w]);
-                    a[2] = pack_hi(v[1][h][0][w], v[1][h][1][w]);
-                    a[3] = pack_hi(v[1][h][2][w], v[1][h][3][w]);
-                } else {
-                    a[0] = pack_lo(v[0][h][0][w], v[0][h][1][w]);
-                    a[1] = pack_lo(v[0][h][2][w], v[0][h][3][w]);
-                    a[2] = pack_lo(v[1][h][0][w], v[1][h][1][w]);
-                    a[3] = pack_lo(v[1][h][2][w], v[1][h][3][w]);
-                }
-#pragma unroll
-                for (int c = 0; c < NB; ++c) st[c].acc[4 * h + i] = mfma_bf16_k32(a, pop[c], st[c].acc[4 * h + i]);
-            }
+        for (int e = 0; e < 8; e += 2) {
+            const unsigned w = cvt_pk_bf16(p[e], p[e + 1]);
+            pop[e >> 1] = w;
+            // the sum runs over the rounded weights, the ones the product below uses
+            psum += __builtin_bit_cast(float, w << 16) + __builtin_bit_cast(float, w & 0xffff0000u);
         }
-    }
-
-    // --- V^T operands formed once by the wave that loaded the tile -------------
-    // When several waves consume a tile from LDS, the loading wave turns its V
-    // registers into the D/16 A operands of the second product (tokens >= t_end
-    // zeroed) and parks those; each consumer then reads an operand with one
-    // 16-byte LDS load per lane instead of re-forming it with byte permutes.
-    static constexpr int kOpsBytes = (D / 16) * 1024;
-    typedef WaveState<D, 1> ParkedState;  // acc[D/16] sums the rounded weights through the MFMA
-
-    SD_DEV static void v_park(Tile &r, char *vslot, int lane, int tok0, int t_end)
-    {
-        const int qd = lane >> 4;
-        auto &v = r.v;
-        if (tok0 + kTileTokens > t_end) {
-#pragma unroll
-            for (int pg = 0; pg < 2; ++pg)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (tok0 + 16 * pg + 4 * qd + j >= t_end) {
-#pragma unroll
-                        for (int h = 0; h < D / 64; ++h) v[pg][h][j] = u32x2{0, 0};
-                    }
-        }
+        st.l += psum;
+        v_sanitise(r, tok0, t_end, qd);
 #pragma unroll
         for (int h = 0; h < D / 64; ++h)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int w = i >> 1;
-                u32x4 a;
-                if (i & 1) {
-                    a[0] = pack_hi(v[0][h][0][w], v[0][h][1][w]);
-                    a[1] = pack_hi(v[0][h][2][w], v[0][h][3][w]);
-                    a[2] = pack_hi(v[1][h][0][w], v[1][h][1][w]);
-                    a[3] = pack_hi(v[1][h][2][w], v[1][h][3][w]);
-                } else {
-                    a[0] = pack_lo(v[0][h][0][w], v[0][h][1][w]);
-                    a[1] = pack_lo(v[0][h][2][w], v[0][h][3][w]);
-                    a[2] = pack_lo(v[1][h][0][w], v[1][h][1][w]);
-                    a[3] = pack_lo(v[1][h][2][w], v[1][h][3][w]);
-                }
-                *reinterpret_cast<u32x4 *>(vslot + (4 * h + i) * 1024 + lane * 16) = a;
-            }
+            for (int i = 0; i < 4; ++i) st.acc[4 * h + i] = mfma_bf16_k32(v_operand(r, h, i), pop, st.acc[4 * h + i]);
     }
 
-    // attend_n with the V^T operands read from `vslot`; the weight sum is one more
-    // accumulator fed an all-ones operand, so it is the sum of the rounded weights
-    // exactly.  The score scale c = scale * log2(e) must be positive here: it is
-    // folded into the exponent, p = exp2(s * c - m), with one fused multiply-add
-    // per score, and the running max is taken over the raw scores.  The V^T
-    // operands are requested before the softmax arithmetic so that the LDS
-    // latency passes behind it.
+    // The loading wave's half of a shared tile: the V^T operands, one 16-byte
+    // piece per lane and operand, ready for attend_parked.
+    SD_DEV static void v_park(Tile &r, char *vslot, int lane, int tok0, int t_end)
+    {
+        v_sanitise(r, tok0, t_end, lane >> 4);
+#pragma unroll
+        for (int h = 0; h < D / 64; ++h)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                *reinterpret_cast<u32x4 *>(vslot + (4 * h + i) * 1024 + lane * 16) = v_operand(r, h, i);
+    }
+
+    // The tile step for NB column blocks of 16 rows over a parked tile.  The row
+    // of block b in this lane ends at row_end[b]; `mask` (wave-uniform) says some
+    // row ends inside the tile.  c = |scale| * log2(e) > 0 is folded into the
+    // exponent.  The weight sum is one more accumulator fed an all-ones operand,
+    // i.e. the sum of the rounded weights exactly.  The V^T operands are
+    // requested before the softmax arithmetic so that the LDS latency passes
+    // behind it.
     template <int NB>
     SD_DEV static void attend_parked(const u32x4 (&ka)[D / 32], const u32x4 (&kb)[D / 32], const char *vslot,
                                      const u32x4 (&qop)[NB][D / 32], ParkedState (&st)[NB], float c, int tok0,
@@ -366,31 +346,14 @@ struct Bf16Path {
         u32x4 pop[NB];
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
-            float x[8];
+            float x[8], p[8];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 x[e] = sa[b][e];
                 x[4 + e] = sb[b][e];
             }
-            if (mask) {  // by position, never by content
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    if (tok0 + 4 * qd + e >= row_end[b]) x[e] = -INFINITY;
-                    if (tok0 + 16 + 4 * qd + e >= row_end[b]) x[4 + e] = -INFINITY;
-                }
-            }
-            float tmax = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-            tmax = head_max(tmax);
-            const float m_new = fmaxf(st[b].m, tmax * c);
-            const float alpha = __builtin_amdgcn_exp2f(st[b].m - m_new);
-            st[b].m = m_new;
-            float p[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(x[e], c, -m_new));
-            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f)) {
-#pragma unroll
-                for (int i = 0; i < ParkedState::kAcc; ++i) st[b].acc[i] *= alpha;
-            }
+            if (mask) mask_scores(x, tok0, row_end[b], qd);
+            online_softmax_folded(x, c, p, st[b]);
 #pragma unroll
             for (int e = 0; e < 8; e += 2) pop[b][e >> 1] = cvt_pk_bf16(p[e], p[e + 1]);
         }
@@ -398,26 +361,15 @@ struct Bf16Path {
 #pragma unroll
         for (int b = 0; b < NB; ++b) st[b].acc[D / 16] = mfma_bf16_k32(ones, pop[b], st[b].acc[D / 16]);
 #pragma unroll
-        for (int k = 0; k < D / 16; ++k) {
+        for (int k = 0; k < D / 16; ++k)
 #pragma unroll
             for (int b = 0; b < NB; ++b) st[b].acc[k] = mfma_bf16_k32(va[k], pop[b], st[b].acc[k]);
-        }
     }
     SD_DEV static float weight_sum(const ParkedState &st) { return st.acc[D / 16][0]; }
 
-    // one column block
-    SD_DEV static void attend(const u32x4 (&ka)[D / 32], const u32x4 (&kb)[D / 32], Tile &r,
-                              const u32x4 (&qop)[D / 32], WaveState<D> &st, float scale_log2e, int tok0, int t_end,
-                              int lane, int row_end, bool mask)
-    {
-        const int ends[1] = {row_end};
-        attend_n<1>(ka, kb, r, reinterpret_cast<const u32x4 (&)[1][D / 32]>(qop),
-                    reinterpret_cast<WaveState<D> (&)[1]>(st), scale_log2e, tok0, t_end, lane, ends, mask);
-    }
-
-    // this lane's accumulators -> row `dst` ([D] floats) of its head
-    template <class State>
-    SD_DEV static void store_acc(const State &st, float *dst, int qd)
+    // this lane's accumulators -> row `dst` ([D] floats)
+    template <class S>
+    SD_DEV static void store_acc(const S &st, float *dst, int qd)
     {
 #pragma unroll
         for (int h = 0; h < D / 64; ++h)
@@ -430,14 +382,18 @@ struct Bf16Path {
 };
 
 // ---------------------------------------------------------------------------
-// fp8 e4m3fn pools, head_dim 128: rows of 128 bytes, tiles of 2 KB
+// fp8 e4m3fn pools, head_dim 128: rows of 128 bytes, tiles of 2 KB.  The codes
+// are converted to bf16 in registers, which is exact; the K scale multiplies a
+// page's scores and the V scale its weights.
 // ---------------------------------------------------------------------------
 struct Fp8Path {
     static constexpr int D = 128;
     static constexpr int kDim = D;
     static constexpr int kTileBytes = kPage * D;
     static constexpr int kScratchBytes = 2 * kTileBytes;
-    static constexpr int kVBytes = 2 * kTileBytes + 16;  // codes + the four page scales
+    static constexpr int kOpsBytes = 8 * 1024 + 16;  // eight bf16 V^T operands and the four page scales
+    typedef WaveState<D> State;
+    typedef WaveState<D> ParkedState;
 
     struct Tile {
         u32x4 k[2][2];  // [page][j]: 16 bytes at byte offset 1024*j + 16*lane of the K tile
@@ -497,121 +453,24 @@ struct Fp8Path {
         }
     }
 
-    // V registers and the four page scales parked in LDS (scales after the 4 KB of codes)
-    SD_DEV static void v_store(const Tile &r, char *vslot, int lane)
+    SD_DEV static void v_sanitise(Tile &r, int tok0, int t_end, int qd)
     {
+        if (tok0 + kTileTokens <= t_end) return;  // wave-uniform
 #pragma unroll
         for (int pg = 0; pg < 2; ++pg)
 #pragma unroll
-            for (int jj = 0; jj < 2; ++jj) {
-                const u32x4 w = {r.v[pg][2 * jj][0], r.v[pg][2 * jj][1], r.v[pg][2 * jj + 1][0], r.v[pg][2 * jj + 1][1]};
-                *reinterpret_cast<u32x4 *>(vslot + (pg * 2 + jj) * 1024 + lane * 16) = w;
-            }
-        if (lane == 0) *reinterpret_cast<f32x4 *>(vslot + 4096) = f32x4{r.ks[0], r.ks[1], r.vs[0], r.vs[1]};
-    }
-    SD_DEV static void v_fetch(Tile &r, const char *vslot, int lane)
-    {
-#pragma unroll
-        for (int pg = 0; pg < 2; ++pg)
-#pragma unroll
-            for (int jj = 0; jj < 2; ++jj) {
-                const u32x4 w = *reinterpret_cast<const u32x4 *>(vslot + (pg * 2 + jj) * 1024 + lane * 16);
-                r.v[pg][2 * jj] = u32x2{w[0], w[1]};
-                r.v[pg][2 * jj + 1] = u32x2{w[2], w[3]};
-            }
-        const f32x4 sc = *reinterpret_cast<const f32x4 *>(vslot + 4096);
-        r.ks[0] = sc[0];
-        r.ks[1] = sc[1];
-        r.vs[0] = sc[2];
-        r.vs[1] = sc[3];
+            for (int j = 0; j < 4; ++j)
+                if (tok0 + 16 * pg + 4 * qd + j >= t_end) r.v[pg][j] = u32x2{0, 0};
     }
 
-    // as Bf16Path::attend_n; the K scale multiplies a page's scores, the V scale its weights
-    template <int NB>
-    SD_DEV static void attend_n(const u32x4 (&ka)[4], const u32x4 (&kb)[4], Tile &r, const u32x4 (&qop)[NB][4],
-                                WaveState<D> (&st)[NB], float scale_log2e, int tok0, int t_end, int lane,
-                                const int (&row_end)[NB], bool mask)
+    // The eight V^T operands, handed to `use(k, operand)`; operand k feeds
+    // acc[k][r] = O[row lane&15][d = 8*(4qd + r) + k].  Codes k, k+1 of four tokens
+    // at a time: converting to f32 and packing two tokens' values per register is
+    // the transposition.
+    template <class F>
+    SD_DEV static void v_operands(const Tile &r, F use)
     {
-        const int qd = lane >> 4;
-        f32x4 sa[NB], sb[NB];
-#pragma unroll
-        for (int c = 0; c < NB; ++c) sa[c] = sb[c] = f32x4{0, 0, 0, 0};
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
-#pragma unroll
-            for (int c = 0; c < NB; ++c) {
-                sa[c] = mfma_bf16_k32(ka[s], qop[c][s], sa[c]);
-                sb[c] = mfma_bf16_k32(kb[s], qop[c][s], sb[c]);
-            }
-        const bool ragged = tok0 + kTileTokens > t_end;
-        const float ca = scale_log2e * r.ks[0], cb = scale_log2e * r.ks[1];
-        u32x4 pop[NB];
-#pragma unroll
-        for (int c = 0; c < NB; ++c) {
-            float x[8], p[8];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                x[e] = sa[c][e] * ca;
-                x[4 + e] = sb[c][e] * cb;
-            }
-            online_softmax(x, p, st[c], mask, tok0, row_end[c], qd);
-            // the weight sum takes the unscaled weights; the product takes them times the page's V scale
-            st[c].l += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
-            pop[c][0] = cvt_pk_bf16(p[0] * r.vs[0], p[1] * r.vs[0]);
-            pop[c][1] = cvt_pk_bf16(p[2] * r.vs[0], p[3] * r.vs[0]);
-            pop[c][2] = cvt_pk_bf16(p[4] * r.vs[1], p[5] * r.vs[1]);
-            pop[c][3] = cvt_pk_bf16(p[6] * r.vs[1], p[7] * r.vs[1]);
-        }
-
-        auto &v = r.v;
-        if (ragged) {
-#pragma unroll
-            for (int pg = 0; pg < 2; ++pg)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (tok0 + 16 * pg + 4 * qd + j >= t_end) v[pg][j] = u32x2{0, 0};
-        }
-        // acc[i][r] = O[row lane&15][d = 8*(4qd + r) + i]: codes i, i+1 of four tokens at a time;
-        // converting to f32 and packing two tokens' values per register is the transposition.
-#pragma unroll
-        for (int w = 0; w < 2; ++w) {
-#pragma unroll
-            for (int hi = 0; hi < 2; ++hi) {
-                f32x2 f[2][4];
-#pragma unroll
-                for (int pg = 0; pg < 2; ++pg)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        f[pg][j] = hi ? __builtin_amdgcn_cvt_pk_f32_fp8(v[pg][j][w], true)
-                                      : __builtin_amdgcn_cvt_pk_f32_fp8(v[pg][j][w], false);
-#pragma unroll
-                for (int ii = 0; ii < 2; ++ii) {
-                    const int i = 4 * w + 2 * hi + ii;
-                    const u32x4 a = {cvt_pk_bf16(f[0][0][ii], f[0][1][ii]), cvt_pk_bf16(f[0][2][ii], f[0][3][ii]),
-                                     cvt_pk_bf16(f[1][0][ii], f[1][1][ii]), cvt_pk_bf16(f[1][2][ii], f[1][3][ii])};
-#pragma unroll
-                    for (int c = 0; c < NB; ++c) st[c].acc[i] = mfma_bf16_k32(a, pop[c], st[c].acc[i]);
-                }
-            }
-        }
-    }
-
-    // --- V^T operands formed once by the wave that loaded the tile (see Bf16Path) ---
-    // Eight bf16 operands (exact conversions of the codes) and the four page scales.
-    static constexpr int kOpsBytes = 8 * 1024 + 16;
-    typedef WaveState<D> ParkedState;
-
-    SD_DEV static void v_park(Tile &r, char *vslot, int lane, int tok0, int t_end)
-    {
-        const int qd = lane >> 4;
-        auto &v = r.v;
-        if (tok0 + kTileTokens > t_end) {
-#pragma unroll
-            for (int pg = 0; pg < 2; ++pg)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (tok0 + 16 * pg + 4 * qd + j >= t_end) v[pg][j] = u32x2{0, 0};
-        }
+        const auto &v = r.v;
 #pragma unroll
         for (int w = 0; w < 2; ++w)
 #pragma unroll
@@ -624,69 +483,97 @@ struct Fp8Path {
                         f[pg][j] = hi ? __builtin_amdgcn_cvt_pk_f32_fp8(v[pg][j][w], true)
                                       : __builtin_amdgcn_cvt_pk_f32_fp8(v[pg][j][w], false);
 #pragma unroll
-                for (int ii = 0; ii < 2; ++ii) {
-                    const int i = 4 * w + 2 * hi + ii;
-                    const u32x4 a = {cvt_pk_bf16(f[0][0][ii], f[0][1][ii]), cvt_pk_bf16(f[0][2][ii], f[0][3][ii]),
-                                     cvt_pk_bf16(f[1][0][ii], f[1][1][ii]), cvt_pk_bf16(f[1][2][ii], f[1][3][ii])};
-                    *reinterpret_cast<u32x4 *>(vslot + i * 1024 + lane * 16) = a;
-                }
+                for (int ii = 0; ii < 2; ++ii)
+                    use(4 * w + 2 * hi + ii,
+                        u32x4{cvt_pk_bf16(f[0][0][ii], f[0][1][ii]), cvt_pk_bf16(f[0][2][ii], f[0][3][ii]),
+                              cvt_pk_bf16(f[1][0][ii], f[1][1][ii]), cvt_pk_bf16(f[1][2][ii], f[1][3][ii])});
             }
+    }
+
+    // weights of one block -> P^T operand (times the page's V scale) and the
+    // unscaled weight sum
+    SD_DEV static u32x4 weight_operand(const float (&p)[8], float va, float vb, float &l)
+    {
+        l += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+        return u32x4{cvt_pk_bf16(p[0] * va, p[1] * va), cvt_pk_bf16(p[2] * va, p[3] * va),
+                     cvt_pk_bf16(p[4] * vb, p[5] * vb), cvt_pk_bf16(p[6] * vb, p[7] * vb)};
+    }
+
+    SD_DEV static void attend(const u32x4 (&ka)[4], const u32x4 (&kb)[4], Tile &r, const u32x4 (&qop)[4], State &st,
+                              float scale_log2e, int tok0, int t_end, int lane)
+    {
+        const int qd = lane >> 4;
+        f32x4 sa = {0, 0, 0, 0}, sb = {0, 0, 0, 0};
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            sa = mfma_bf16_k32(ka[s], qop[s], sa);
+            sb = mfma_bf16_k32(kb[s], qop[s], sb);
+        }
+        const float ca = scale_log2e * r.ks[0], cb = scale_log2e * r.ks[1];
+        float x[8], p[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            x[e] = sa[e] * ca;
+            x[4 + e] = sb[e] * cb;
+        }
+        if (tok0 + kTileTokens > t_end) mask_scores(x, tok0, t_end, qd);  // wave-uniform
+        online_softmax(x, p, st);
+        const u32x4 pop = weight_operand(p, r.vs[0], r.vs[1], st.l);
+        v_sanitise(r, tok0, t_end, qd);
+        v_operands(r, [&](int k, u32x4 a) { st.acc[k] = mfma_bf16_k32(a, pop, st.acc[k]); });
+    }
+
+    SD_DEV static void v_park(Tile &r, char *vslot, int lane, int tok0, int t_end)
+    {
+        v_sanitise(r, tok0, t_end, lane >> 4);
+        v_operands(r, [&](int k, u32x4 a) { *reinterpret_cast<u32x4 *>(vslot + k * 1024 + lane * 16) = a; });
         if (lane == 0) *reinterpret_cast<f32x4 *>(vslot + 8 * 1024) = f32x4{r.ks[0], r.ks[1], r.vs[0], r.vs[1]};
     }
 
+    // as Bf16Path::attend_parked; the scores are scaled per page before the mask
+    // (a page of zeros has scale 0), so nothing is folded here
     template <int NB>
     SD_DEV static void attend_parked(const u32x4 (&ka)[4], const u32x4 (&kb)[4], const char *vslot,
-                                     const u32x4 (&qop)[NB][4], ParkedState (&st)[NB], float scale_log2e, int tok0,
-                                     int lane, const int (&row_end)[NB], bool mask)
+                                     const u32x4 (&qop)[NB][4], ParkedState (&st)[NB], float c, int tok0, int lane,
+                                     const int (&row_end)[NB], bool mask)
     {
         const int qd = lane >> 4;
         const f32x4 sc = *reinterpret_cast<const f32x4 *>(vslot + 8 * 1024);  // k scales, v scales of the two pages
         f32x4 sa[NB], sb[NB];
 #pragma unroll
-        for (int c = 0; c < NB; ++c) sa[c] = sb[c] = f32x4{0, 0, 0, 0};
+        for (int b = 0; b < NB; ++b) sa[b] = sb[b] = f32x4{0, 0, 0, 0};
 #pragma unroll
         for (int s = 0; s < 4; ++s)
 #pragma unroll
-            for (int c = 0; c < NB; ++c) {
-                sa[c] = mfma_bf16_k32(ka[s], qop[c][s], sa[c]);
-                sb[c] = mfma_bf16_k32(kb[s], qop[c][s], sb[c]);
+            for (int b = 0; b < NB; ++b) {
+                sa[b] = mfma_bf16_k32(ka[s], qop[b][s], sa[b]);
+                sb[b] = mfma_bf16_k32(kb[s], qop[b][s], sb[b]);
             }
-        const float ca = scale_log2e * sc[0], cb = scale_log2e * sc[1];
+        const float ca = c * sc[0], cb = c * sc[1];
         u32x4 pop[NB];
 #pragma unroll
-        for (int c = 0; c < NB; ++c) {
+        for (int b = 0; b < NB; ++b) {
             float x[8], p[8];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                x[e] = sa[c][e] * ca;
-                x[4 + e] = sb[c][e] * cb;
+                x[e] = sa[b][e] * ca;
+                x[4 + e] = sb[b][e] * cb;
             }
-            online_softmax(x, p, st[c], mask, tok0, row_end[c], qd);
-            st[c].l += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
-            pop[c][0] = cvt_pk_bf16(p[0] * sc[2], p[1] * sc[2]);
-            pop[c][1] = cvt_pk_bf16(p[2] * sc[2], p[3] * sc[2]);
-            pop[c][2] = cvt_pk_bf16(p[4] * sc[3], p[5] * sc[3]);
-            pop[c][3] = cvt_pk_bf16(p[6] * sc[3], p[7] * sc[3]);
+            if (mask) mask_scores(x, tok0, row_end[b], qd);
+            online_softmax(x, p, st[b]);
+            pop[b] = weight_operand(p, sc[2], sc[3], st[b].l);
         }
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const u32x4 a = *reinterpret_cast<const u32x4 *>(vslot + k * 1024 + lane * 16);
 #pragma unroll
-            for (int c = 0; c < NB; ++c) st[c].acc[k] = mfma_bf16_k32(a, pop[c], st[c].acc[k]);
+            for (int b = 0; b < NB; ++b) st[b].acc[k] = mfma_bf16_k32(a, pop[b], st[b].acc[k]);
         }
     }
     SD_DEV static float weight_sum(const ParkedState &st) { return head_sum(st.l); }
 
-    SD_DEV static void attend(const u32x4 (&ka)[4], const u32x4 (&kb)[4], Tile &r, const u32x4 (&qop)[4],
-                              WaveState<D> &st, float scale_log2e, int tok0, int t_end, int lane, int row_end, bool mask)
-    {
-        const int ends[1] = {row_end};
-        attend_n<1>(ka, kb, r, reinterpret_cast<const u32x4 (&)[1][4]>(qop), reinterpret_cast<WaveState<D> (&)[1]>(st),
-                    scale_log2e, tok0, t_end, lane, ends, mask);
-    }
-
-    template <class State>
-    SD_DEV static void store_acc(const State &st, float *dst, int qd)
+    template <class S>
+    SD_DEV static void store_acc(const S &st, float *dst, int qd)
     {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -698,25 +585,15 @@ struct Fp8Path {
     }
 };
 
-template <class State>
-SD_DEV void reset(State &st)
-{
-    st.m = -INFINITY;
-    st.l = 0.f;
-#pragma unroll
-    for (int i = 0; i < State::kAcc; ++i) st.acc[i] = f32x4{0, 0, 0, 0};
-}
-
-// LDS of one workgroup.  Plain items: per-wave K scratch plus the merge
-// buffers.  Shared-prefix items: four tile slots (K image + parked V
-// registers), one filled by each wave and read by all.
+// LDS of one workgroup of the split pass.  Plain items: per-wave K scratch plus
+// the merge buffers.  Shared items (and the causal pass): four tile slots (K
+// image + V^T operands), one filled by each wave and read by all.
 template <class P>
 struct Lds {
     static constexpr int kRow = P::kDim + 4;  // padded: 16 rows x float4 stores hit 64 distinct banks
-    static constexpr int kSlotBytes = P::kScratchBytes + ((P::kVBytes + 15) / 16) * 16;
+    static constexpr int kSlotBytes = P::kScratchBytes + ((P::kOpsBytes + 15) / 16) * 16;
     static constexpr int kPlainBytes = kWaves * P::kScratchBytes + kWaves * kMaxGroup * kRow * 4 + 2 * kWaves * kMaxGroup * 4;
     static constexpr int kSharedBytes = kWaves * kSlotBytes;
-    static constexpr int kParkedSlotBytes = P::kScratchBytes + ((P::kOpsBytes + 15) / 16) * 16;  // K image + V^T operands
     static constexpr int kBytes = kPlainBytes > kSharedBytes ? kPlainBytes : kSharedBytes;
 };
 

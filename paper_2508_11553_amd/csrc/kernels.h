@@ -34,6 +34,10 @@ struct SplitArgs {
     float *ws_l;                 // [B][Hq][S]   sum of weights
     float *ws_acc;               // [B][Hq][S][D] weighted V sum
     float scale_log2e;           // scale * log2(e)
+    // the shared-prefix items fold a non-negative scale into their exponent: |scale| * log2(e), the sign as a
+    // bit flip of the queries (0x80008000 when scale < 0), and zeroed queries with scale 1 when scale == 0
+    float abs_scale_log2e;
+    uint32_t q_flip, q_keep;
     int32_t B, Hq, Hkv, G;
     int32_t max_blocks, S, chunk_tokens, max_context_len;
     // shared-prefix groups (all zero / null when the call has none)

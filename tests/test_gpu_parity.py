@@ -396,6 +396,21 @@ def test_prefix_entry_point_fp8(sd):
     check_fp8(gpu_attend_prefix(wl, chunk_tokens=512), oracle_full(wl))
 
 
+@pytest.mark.parametrize("kv_dtype", ["bf16", "fp8"])
+@pytest.mark.parametrize("scale", [-0.09, 0.0])
+def test_prefix_entry_point_with_negative_and_zero_scale(sd, scale, kv_dtype):
+    """The shared-prefix items work with |scale| and sign-flipped (or zeroed) queries; the plain items
+    with the scale itself.  Both must give the oracle's result for the scale that was passed."""
+    sizes = [5, 2]
+    session_of = np.repeat(np.arange(2), sizes)
+    prefix_len = np.repeat([512, 256], sizes)
+    lens = prefix_len + np.random.default_rng(9).integers(1, 300, size=len(session_of))
+    wl = workloads.make_custom(lens, 8, 2, 128, kv_dtype, seed=420, session_of=session_of, prefix_len=prefix_len,
+                               scale=scale)
+    got, want = gpu_attend_prefix(wl, chunk_tokens=256), oracle_full(wl)
+    (check_fp8 if kv_dtype == "fp8" else check)(got, want)
+
+
 def test_prefix_entry_point_without_groups_is_the_plain_call(sd):
     import torch
     wl = workloads.make_custom([700, 1500, 64], 8, 2, 128, seed=420)
