@@ -208,7 +208,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=1, help="workload index 0-4 (see workloads.CONFIG_NAMES), default 1")
-    ap.add_argument("--chunk", type=int, default=0, help="split-K chunk override (tokens)")
+    ap.add_argument("--chunk", type=int, default=0, help="split-K chunk override (tokens); default: sd_chunk_for_batch of the batch's token count")
     ap.add_argument("--pools", type=int, default=0, help="number of rotating K/V pools (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-append", action="store_true")
@@ -245,7 +245,7 @@ def main():
     wl = workloads.make_config(cfg, append=do_append)
     pool_bytes = 2 * wl.k_pages.nbytes
     npools = args.pools or (4 if pool_bytes < SMALL_POOL_BYTES else 1)
-    dw = DeviceWorkload(wl, chunk_tokens=args.chunk)
+    dw = DeviceWorkload(wl, chunk_tokens=args.chunk, balance_for_batch=True)
     pools = [(dw.k_pages, dw.v_pages, dw.k_scales, dw.v_scales)]
     for i in range(1, npools):
         k, v, ks, vs = draw_extra_pool(wl, seed=1000 + i)
@@ -346,6 +346,7 @@ def main():
             "attended_tokens": wl.attended_tokens, "unique_tokens": wl.unique_tokens, "chunk_tokens": chunk,
             "pools_rotated": npools, "entry_point": "paged_decode_attention_prefix" if prefix_aware else
             "paged_decode_attention", "append_rows_per_step": int(wl.k_new.shape[0]) if do_append else 0, "seed": 0,
+            "merge_pass": bool(prefix_aware or chunk < wl.max_context_len),
         },
         "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
         "attended_kv_tokens_per_s": wl.attended_tokens / (ms_per_step * 1e-3),

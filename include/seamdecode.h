@@ -82,8 +82,17 @@ const char *sd_strerror(int code);
 /* hipError_t (as int) of the last failing HIP call made by this thread; 0 if none. */
 int sd_last_hip_error(void);
 
-/* The split-K chunk (tokens) the library uses for this shape; <= 0 is an SD_E* code. */
+/* The split-K chunk (tokens) the library uses for this shape; <= 0 is an SD_E* code.
+   With shape->chunk_tokens == 0 it is chosen from the shape alone, taking sequences
+   to average 55 % of max_context_len. */
 int sd_chunk_tokens(const sd_shape *shape);
+
+/* The chunk that balances the split pass for a batch whose sequences hold
+   `total_tokens` distinct K/V tokens per KV head in all (the sum of context_lens,
+   counting the tokens of a shared prefix once): a caller that tracks its
+   trajectories' lengths on the host puts the result into shape->chunk_tokens.
+   A multiple of 128; <= 0 is an SD_E* code. */
+int sd_chunk_for_batch(const sd_shape *shape, int64_t total_tokens);
 
 /*
  * Bytes of scratch paged_decode_attention needs for this shape (host-only

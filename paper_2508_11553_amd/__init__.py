@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     SeamDecodeError,
     Shape,
     KernelTimer,
+    chunk_for_batch,
     chunk_tokens,
     kv_append,
     kv_append_fp8,

@@ -59,6 +59,8 @@ def load():
     L.sd_last_hip_error.argtypes = []
     L.sd_chunk_tokens.restype = ctypes.c_int
     L.sd_chunk_tokens.argtypes = [sp]
+    L.sd_chunk_for_batch.restype = ctypes.c_int
+    L.sd_chunk_for_batch.argtypes = [sp, ctypes.c_int64]
     L.sd_workspace_bytes.restype = sz
     L.sd_workspace_bytes.argtypes = [sp]
     L.kv_append.restype = ctypes.c_int
@@ -128,6 +130,13 @@ def chunk_tokens(shape: Shape) -> int:
     rc = int(load().sd_chunk_tokens(ctypes.byref(shape)))
     if rc <= 0:
         raise SeamDecodeError(rc, "sd_chunk_tokens")
+    return rc
+
+
+def chunk_for_batch(shape: Shape, total_tokens: int) -> int:
+    rc = int(load().sd_chunk_for_batch(ctypes.byref(shape), int(total_tokens)))
+    if rc <= 0:
+        raise SeamDecodeError(rc, "sd_chunk_for_batch")
     return rc
 
 

@@ -24,7 +24,9 @@
 // page's scores and the V scale multiplies the page's weights.
 //
 // The four waves' (max, sum, O) are merged through LDS and written as one
-// partial per (b, head, chunk); the merge kernel finishes the softmax.
+// partial per (b, head, chunk); the merge kernel finishes the softmax.  When the
+// host knows that every sequence is a single chunk, the workgroup writes the
+// normalised output itself and no merge pass runs.
 #include "attn_tile.h"
 
 namespace sd {
@@ -229,7 +231,13 @@ __global__ __launch_bounds__(kWaves * 64, 2) void split_kernel(SplitArgs a)
     const int shared = a.shared_len ? shared_tokens(a, b) : 0;
     const int n_private = (L - shared + a.chunk_tokens - 1) / a.chunk_tokens;
     const int c_private = n_private - 1 - from_end;
-    if (c_private < 0) return;
+    if (c_private < 0) {
+        // single-chunk mode: an empty sequence still owes its zero rows
+        if (a.out_direct && L == 0 && from_end == 0)
+            for (int idx = tid; idx < a.G * D; idx += kWaves * 64)
+                a.out_direct[((int64_t)b * a.Hq + (int64_t)g * a.G) * D + idx] = 0.f;
+        return;
+    }
     const int c = shared_slots(shared, a.chunk_tokens) + c_private;  // slot of this chunk
     const int t0 = shared + c_private * a.chunk_tokens;
     const int t1 = min(L, t0 + a.chunk_tokens);
@@ -273,6 +281,10 @@ __global__ __launch_bounds__(kWaves * 64, 2) void split_kernel(SplitArgs a)
             const float wt = __builtin_amdgcn_exp2f(s_m[w][hn] - M);
             num += wt * s_acc[w][hn][dd];
             den += wt * s_l[w][hn];
+        }
+        if (a.out_direct) {  // the only chunk of its sequence: this is the result
+            a.out_direct[(row0 + hn) * D + dd] = num / den;
+            continue;
         }
         const int64_t slot = (row0 + hn) * a.S + c;
         a.ws_acc[slot * D + dd] = num;

@@ -33,6 +33,7 @@ struct SplitArgs {
     float *ws_m;                 // [B][Hq][S]   running max, log2 domain
     float *ws_l;                 // [B][Hq][S]   sum of weights
     float *ws_acc;               // [B][Hq][S][D] weighted V sum
+    float *out_direct;           // [B][Hq][D] or null: every sequence is one chunk, write the output instead of partials
     float scale_log2e;           // scale * log2(e)
     // the shared-prefix items fold a non-negative scale into their exponent: |scale| * log2(e), the sign as a
     // bit flip of the queries (0x80008000 when scale < 0), and zeroed queries with scale 1 when scale == 0

@@ -20,7 +20,10 @@ def _to_dev(a: np.ndarray, device) -> torch.Tensor:
 class DeviceWorkload:
     """Anything with the fields of workloads.Workload can be uploaded."""
 
-    def __init__(self, wl, device="cuda:0", chunk_tokens: int = 0, upload_pools: bool = True):
+    def __init__(self, wl, device="cuda:0", chunk_tokens: int = 0, upload_pools: bool = True,
+                 balance_for_batch: bool = False):
+        """chunk_tokens = 0 leaves the chunk to the library; balance_for_batch asks it for the chunk that
+        fits this batch's token count (which a scheduler knows on the host) instead of the shape-only guess."""
         self.wl = wl
         self.device = torch.device(device)
         self.shape = sd.Shape(
@@ -28,6 +31,8 @@ class DeviceWorkload:
             page_size=wl.page_size, num_pages=wl.num_pages, max_blocks_per_seq=wl.max_blocks_per_seq,
             kv_dtype=sd.SD_FP8_E4M3 if wl.kv_dtype == "fp8" else sd.SD_BF16,
             max_context_len=wl.max_context_len, chunk_tokens=chunk_tokens)
+        if balance_for_batch and not chunk_tokens:
+            self.shape.chunk_tokens = sd.chunk_for_batch(self.shape, int(wl.unique_tokens))
         self.scale = float(wl.scale)
         self.q = _to_dev(wl.q, self.device)
         self.block_table = _to_dev(wl.block_table, self.device)

@@ -130,6 +130,21 @@ def test_copy_pages_arguments_are_checked_on_the_host(lib):
     assert lib.kv_copy_pages(ctypes.byref(s8), 16, 32, 2, 48, 64, None, None, None) == -1  # fp8 pools come with scales
 
 
+def test_chunk_for_batch_is_a_bounded_monotone_multiple_of_128(lib):
+    lib.sd_chunk_for_batch.argtypes = [ctypes.c_void_p, ctypes.c_int64]
+    s = good_shape(batch=64, max_blocks_per_seq=512, max_context_len=8192)
+    prev = 0
+    for total in (0, 1000, 10_000, 100_000, 300_000, 1_000_000, 10**9):
+        c = lib.sd_chunk_for_batch(ctypes.byref(s), total)
+        assert c % 128 == 0 and 128 <= c <= 8192 and c >= prev
+        prev = c
+    assert prev == 8192                                   # a huge batch: the cap, which is also the longest sequence
+    short = good_shape(batch=4096, max_blocks_per_seq=64, max_context_len=1000)
+    assert lib.sd_chunk_for_batch(ctypes.byref(short), 4096 * 800) == 1024   # covers every sequence: one chunk each
+    assert lib.sd_chunk_for_batch(ctypes.byref(s), -1) == -1
+    assert lib.sd_chunk_for_batch(None, 5) == -1
+
+
 def test_empty_calls_are_noops(lib):
     s = good_shape(batch=0)
     assert lib.paged_decode_attention(ctypes.byref(s), None, None, None, None, None, None, None, 1.0, None, None, 0, None) == 0

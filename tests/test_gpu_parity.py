@@ -96,6 +96,30 @@ def test_zero_length_sequences_give_zero_rows(sd):
     check(got, oracle_full(wl))
 
 
+@pytest.mark.parametrize("kv_dtype,d", [("bf16", 64), ("bf16", 128), ("fp8", 128)])
+def test_single_chunk_batches_skip_the_merge_pass(sd, kv_dtype, d):
+    """A chunk that covers the longest sequence makes the split pass write `out` itself.  The result must be
+    bit-identical to the two-pass result of the same chunking (the merge of one slot is the identity), empty
+    sequences must still get their zero rows, and every element of `out` must be written."""
+    import torch
+    lens = [0, 40, 1, 513, 0, 640, 639, 16, 17]
+    wl = workloads.make_custom(lens, 8, 2, d, kv_dtype, seed=12, max_blocks_per_seq=41)
+    direct = device_workload(wl, chunk_tokens=640)            # 640 >= max length: one chunk per sequence
+    direct.out.fill_(float("nan"))
+    got = direct.attend().clone()
+    # the same chunking through the merge pass: a longer length bound keeps the second slot alive
+    two = device_workload(wl, chunk_tokens=640)
+    two.shape.max_context_len = 641
+    two.ws_bytes = sd.workspace_bytes(two.shape)
+    two.workspace = torch.empty(two.ws_bytes, dtype=torch.uint8, device=two.device)
+    want = two.attend().clone()
+    torch.cuda.synchronize()
+    assert torch.equal(got, want)
+    g = got.cpu().numpy()
+    assert not g[0].any() and not g[4].any()
+    (check_fp8 if kv_dtype == "fp8" else check)(g, oracle_full(wl))
+
+
 def test_length_one_returns_v_row_bit_exact(sd):
     wl = workloads.make_custom([1, 1, 1, 1, 1], 8, 2, 128, seed=10)
     got = gpu_attend(wl)
