@@ -77,7 +77,32 @@ def test_one_query_per_sequence_equals_the_decode_step(sd):
     # different split of the token range, same arithmetic: equal up to the rounding of the partial sums
     ref_ = oracle.paged_decode_attention(wl.q, wl.k_pages, wl.v_pages, wl.block_table, wl.context_lens, wl.scale)
     check(pre.cpu().numpy(), ref_)
-    np.testing.assert_allclose(pre.cpu().numpy(), dec.cpu().numpy(), atol=2e-3)
+    # the two kernels round their weights at slightly different points (one fuses the scale into the exponent):
+    # a weight that lands on the other side of a bf16 rounding boundary moves a short row by up to 2^-8 of its V
+    diff = np.abs(pre.cpu().numpy() - dec.cpu().numpy())
+    assert (diff <= 2 * (3e-4 + 2.0 ** -8 * np.abs(ref_).max(axis=-1, keepdims=True))).all()
+
+
+@pytest.mark.parametrize("kv_dtype,d", [("bf16", 64), ("bf16", 128), ("fp8", 128)])
+def test_constant_v_returns_the_constant(sd, kv_dtype, d):
+    """Every row is a convex combination of V rows; for bf16 pools it is normalised by the sum of the very
+    weights the product uses, so with all V rows equal the result is that row up to fp32 rounding, however the
+    weights round."""
+    lens, nq = [70, 300, 33], [70, 40, 33]
+    wl, q, q_start = make(lens, nq, 8, 2, d, kv_dtype, seed=51)
+    if kv_dtype == "bf16":
+        cst = f32_to_bf16_bits(np.float32([0.37]))[0]
+        wl.v_pages[...] = cst
+        want = float(workloads.bf16_bits_to_f32(np.uint16([cst]))[0])
+    else:
+        wl.v_pages[...] = 0x38            # e4m3fn 1.0
+        wl.v_scales[...] = np.float32(0.25)
+        want = 0.25
+    got = gpu(wl, q, q_start)
+    # fp8 pools: the product takes bf16(weight * page scale) while the sum takes the weights themselves, so the
+    # constant comes back to bf16 rounding only
+    tol = 2.0 ** -8 * want if kv_dtype == "fp8" else 2e-6 * abs(want) + 1e-7
+    assert np.abs(got - want).max() <= tol
 
 
 def test_sequences_without_queries_with_too_many_and_empty(sd):
