@@ -81,6 +81,17 @@ def stored_traffic(kernel_sources, workload_key):
     return None
 
 
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(cfg, wall_target=10.0):
     """The oracle (fp64 build, OpenMP over rows) on the host cores over the
     first sequences of the same workload: as many as about `wall_target`
@@ -115,6 +126,7 @@ def cpu_baseline(cfg, wall_target=10.0):
     dt = float(np.mean(times))
     return {
         "value": wl.attended_tokens * wl.token_bytes / dt / 1e9, "unit": "GB/s", "cores": nthreads, "kind": "oracle",
+        "cpu_model": cpu_model(),
         "sample": f"first {nb} of {len(lens)} sequences of the workload ({wl.attended_tokens} attended tokens, all "
                   f"query heads), fp64 oracle, mean of {len(times)} passes of {dt:.2f} s",
         "attended_kv_tokens_per_s": wl.attended_tokens / dt,
@@ -333,6 +345,12 @@ def main():
         del src_t, dst_t
 
     value = ab["step"] / (ms_per_step * 1e-3) / 1e9
+    # MFMA flops the split pass issues: QK^T and PV on 16-row tiles, 2 * 16 * d * 2 flops per token and KV head;
+    # plain items run one tile per (sequence, KV head), shared items one per 16 / G sequences
+    issued_tokens = float(wl.attended_tokens) if not prefix_aware else (
+        float(wl.attended_tokens - int(wl.shared_len.astype(np.int64).sum())) +
+        float(wl.shared_len.astype(np.int64).sum()) * (wl.num_q_heads // wl.num_kv_heads) / 16.0)
+    issued_flops = issued_tokens * wl.num_kv_heads * 64.0 * wl.head_dim
     achieved = ab["split"] / (split_avg * 1e-3) / 1e9
     src = [os.path.join(ROOT, "paper_2508_11553_amd", "csrc", f) for f in ("attn_split.hip", "attn_tile.h", "kernels.h")]
     rec = {
@@ -358,6 +376,12 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": stored_traffic(src, f"configs[{cfg}]"),
                      "kernel": "split pass (sd::split_*_kernel)", "algorithmic_bytes_per_launch": ab["split"]},
+        "mfma": {"issued_tflops": issued_flops / (split_avg * 1e-3) / 1e12,
+                 "useful_tflops": 4.0 * wl.head_dim * wl.num_q_heads * wl.attended_tokens / (split_avg * 1e-3) / 1e12,
+                 "peak_tflops": MFMA_BF16_PEAK_TFLOPS,
+                 "issued_frac_of_peak": issued_flops / (split_avg * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                 "what": "split pass; issued = 64*d flops per (token, KV head): both products on 16-row tiles "
+                         "(rows beyond G are padding); shared-prefix tokens counted once per 16 rows"},
         "input_generation_s": t_gen,
     }
     if not args.no_cpu_baseline:

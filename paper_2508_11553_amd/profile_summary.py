@@ -62,6 +62,7 @@ def main():
     ap.add_argument("--kernel-trace", required=True)
     ap.add_argument("--fetch", required=True)
     ap.add_argument("--write", required=True)
+    ap.add_argument("--mfma", default=None, help="optional fourth run: --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CU_CYCLES")
     ap.add_argument("--bench-args", default="--steps 100 --warmup 10 --no-cpu-baseline",
                     help="arguments bench.py was given in the kernel-trace run (for the header)")
     ap.add_argument("--pmc-bench-args", default="--steps 20 --warmup 2 --no-cpu-baseline --copy-calibration")
@@ -72,8 +73,11 @@ def main():
     print(f"    rocprofv3 --kernel-trace --stats --output-format csv -d {a.kernel_trace} -o run -- python3 bench.py {a.bench_args}")
     print(f"    rocprofv3 --pmc FETCH_SIZE --output-format csv -d {a.fetch} -o run -- python3 bench.py {a.pmc_bench_args}")
     print(f"    rocprofv3 --pmc WRITE_SIZE --output-format csv -d {a.write} -o run -- python3 bench.py {a.pmc_bench_args}")
+    if a.mfma:
+        print(f"    rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CU_CYCLES --output-format csv -d {a.mfma} -o run -- "
+              f"python3 bench.py {a.pmc_bench_args}")
     print(f"    python -m paper_2508_11553_amd.profile_summary --workload '{a.workload}' --kernel-trace {a.kernel_trace} "
-          f"--fetch {a.fetch} --write {a.write}\n")
+          f"--fetch {a.fetch} --write {a.write}" + (f" --mfma {a.mfma}" if a.mfma else "") + "\n")
 
     print("## Kernel durations (--kernel-trace --stats)\n")
     print("| kernel | calls | avg us | min us | max us | % of GPU time |")
@@ -103,6 +107,18 @@ def main():
         total[name] = rd + wrb
         short = name if len(name) <= 70 else name[:67] + "..."
         print(f"| `{short}` | {len(fetch[name])} | {fr:.1f} | {wr:.1f} | {rd / 1e6:.2f} | {wrb / 1e6:.2f} |")
+    if a.mfma:
+        busy, cu = counters(a.mfma, "SQ_VALU_MFMA_BUSY_CYCLES"), counters(a.mfma, "SQ_BUSY_CU_CYCLES")
+        print("\n## Matrix-core utilisation (--pmc)\n")
+        print("MFMA busy cycles summed over the SIMDs, against 4 SIMDs x the cycles a CU was busy.\n")
+        print("| kernel | SQ_VALU_MFMA_BUSY_CYCLES | SQ_BUSY_CU_CYCLES | MFMA busy, % of SIMD cycles |")
+        print("|---|---|---|---|")
+        for name in busy:
+            if name not in cu or "split_kernel" not in name and "prefill" not in name:
+                continue
+            bz, cz = statistics.mean(busy[name]), statistics.mean(cu[name])
+            short = name if len(name) <= 70 else name[:67] + "..."
+            print(f"| `{short}` | {bz:.3g} | {cz:.3g} | {100.0 * bz / (4.0 * cz):.1f} |")
     print()
     tag = source_hash()
     for name, t in total.items():
