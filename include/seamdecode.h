@@ -323,6 +323,22 @@ int32_t sd_tree_batch_groups(const sd_tree *t, const int32_t *trajs, int32_t B, 
                              int32_t *shared_len_out);
 
 /*
+ * sd_validate_tables -- optional check of a batch's tables before they are used.
+ *
+ * The attention and append kernels trust block_table: an entry that does not
+ * name a page of the pool is an out-of-bounds access.  A caller that builds
+ * tables from untrusted bookkeeping can run this first (two tiny launches on
+ * `stream`): report[0] receives the number of entries a launch would
+ * dereference -- pages 0 .. ceil(L/16)-1 of every sequence, L clamped to
+ * [0, max_context_len] -- that lie outside [0, num_pages), report[1] the
+ * number of sequences whose context_lens is outside [0, max_context_len].
+ *
+ *   report   i32 [2] (device), 16-byte aligned; read it back after the stream has run
+ */
+int sd_validate_tables(const sd_shape *shape, const int32_t *block_table, const int32_t *context_lens,
+                       int32_t *report, void *stream);
+
+/*
  * Measurement aids (not part of the decode step).
  *
  * sd_timer owns HIP events (host objects; no device memory).  The _timed

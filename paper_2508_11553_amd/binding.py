@@ -78,6 +78,8 @@ def load():
     L.kv_copy_pages.argtypes = [sp, vp, vp, i32, vp, vp, vp, vp, vp]
     L.paged_prefill_attention.restype = ctypes.c_int
     L.paged_prefill_attention.argtypes = [sp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp]
+    L.sd_validate_tables.restype = ctypes.c_int
+    L.sd_validate_tables.argtypes = [sp, vp, vp, vp, vp]
     L.sd_timer_create.restype = vp
     L.sd_timer_create.argtypes = [i32]
     L.sd_timer_destroy.restype = None
@@ -234,6 +236,12 @@ def paged_prefill_attention(shape: Shape, q, q_start, total_q: int, max_q_len: i
         _ptr(k_scales), _ptr(v_scales), _ptr(block_table), _ptr(context_lens), float(scale), _ptr(out),
         _stream(stream), timer._h if timer is not None else None)
     _check(rc, "paged_prefill_attention")
+
+
+def validate_tables(shape: Shape, block_table, context_lens, report, stream=None):
+    rc = load().sd_validate_tables(ctypes.byref(shape), _ptr(block_table), _ptr(context_lens), _ptr(report),
+                                   _stream(stream))
+    _check(rc, "sd_validate_tables")
 
 
 def probe_read(shape: Shape, k_pages, v_pages, block_table, context_lens, sink, stream=None):

@@ -454,6 +454,25 @@ int sd_timer_read(sd_timer *t, float *split_ms, float *merge_ms, int32_t cap)
     return n;
 }
 
+int sd_validate_tables(const sd_shape *shape, const int32_t *block_table, const int32_t *context_lens,
+                       int32_t *report, void *stream)
+{
+    const int rc = check_shape(shape);
+    if (rc) return rc;
+    if (bad_ptr(report)) return SD_EINVAL;
+    if (shape->batch > 0 && (bad_ptr(block_table) || bad_ptr(context_lens))) return SD_EINVAL;
+    sd::ValidateArgs a;
+    a.block_table = block_table;
+    a.context_lens = context_lens;
+    a.report = report;
+    a.B = shape->batch;
+    a.max_blocks = shape->max_blocks_per_seq;
+    a.num_pages = shape->num_pages;
+    a.max_context_len = shape->max_context_len;
+    const hipError_t e = sd::launch_validate(a, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SD_OK : hip_fail(e);
+}
+
 size_t sd_probe_sink_words(const sd_shape *shape)
 {
     if (check_shape(shape)) return 0;

@@ -102,6 +102,12 @@ struct CopyPagesArgs {
     int32_t page_words;                    // 16-byte words of one page over all heads
 };
 
+struct ValidateArgs {
+    const int32_t *block_table, *context_lens;
+    int32_t *report;             // [2]: bad table entries in use, bad lengths
+    int32_t B, max_blocks, num_pages, max_context_len;
+};
+
 struct ProbeArgs {
     const void *k_pages, *v_pages;
     const int32_t *block_table, *context_lens;
@@ -123,6 +129,7 @@ hipError_t launch_prefill(const PrefillArgs &a, int head_dim, int kv_dtype, hipS
 hipError_t launch_append(const AppendArgs &a, int head_dim, hipStream_t stream);
 hipError_t launch_append_fp8(const AppendFp8Args &a, hipStream_t stream);
 hipError_t launch_copy_pages(const CopyPagesArgs &a, hipStream_t stream);
+hipError_t launch_validate(const ValidateArgs &a, hipStream_t stream);
 hipError_t launch_probe(const ProbeArgs &a, hipStream_t stream);
 
 }  // namespace sd

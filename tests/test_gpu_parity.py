@@ -583,6 +583,33 @@ def test_fp8_decode_step_append_then_attend(sd):
     check_fp8(out.cpu().numpy(), oracle_full(wl))
 
 
+# ---------------------------------------------------------------- table check
+def test_validate_tables_counts_what_a_launch_would_dereference(sd):
+    import torch
+    from paper_2508_11553_amd.device import _to_dev
+    wl = workloads.make_custom([40, 0, 513, 16, 700], 8, 2, 64, seed=70)
+    dw = device_workload(wl)
+    report = torch.full((4,), 77, dtype=torch.int32, device=dw.device)
+    sd.validate_tables(dw.shape, dw.block_table, dw.context_lens, report)
+    torch.cuda.synchronize()
+    assert report.cpu().tolist()[:2] == [0, 0]
+    # corrupt entries inside and outside the used part of the rows, and two lengths
+    bt, lens = wl.block_table.copy(), wl.context_lens.copy()
+    bt[0, 1] = -1                      # used (40 tokens = 3 pages)
+    bt[0, 5] = wl.num_pages + 9        # not used
+    bt[2, 32] = wl.num_pages           # used (513 tokens = 33 pages)
+    bt[4, 0] = 1 << 30                 # used
+    bt[1, 0] = -5                      # not used: the sequence is empty
+    lens[3] = -2
+    lens[4] = wl.max_context_len + 1   # clamped: its first 44 pages count, among them bt[4, 0]
+    sd.validate_tables(dw.shape, _to_dev(bt, dw.device), _to_dev(lens, dw.device), report)
+    torch.cuda.synchronize()
+    used = (np.clip(lens, 0, wl.max_context_len) + 15) // 16
+    want_bad = sum(int(((bt[b, :used[b]] < 0) | (bt[b, :used[b]] >= wl.num_pages)).sum()) for b in range(wl.batch))
+    assert want_bad == 3
+    assert report.cpu().tolist()[:2] == [want_bad, 2]
+
+
 # ---------------------------------------------------------------- HIP graph capture
 def test_decode_step_replays_from_a_hip_graph(sd):
     """The library neither allocates nor synchronises, so a whole decode step (append + attention) can be
