@@ -270,7 +270,7 @@ def sampled_rows(wl, n, seed=0):
 @pytest.mark.parametrize("cfg", [1, 2])
 def test_full_size_config_sampled_rows(sd, cfg):
     wl = workloads.make_config(cfg)
-    got = gpu_attend(wl)
+    got = gpu_attend(wl, balance_for_batch=True)  # the launch configuration bench.py times
     assert not np.isnan(got).any()
     rows = sampled_rows(wl, 96)
     ref = oracle.attend_rows(wl.q, wl.k_pages, wl.v_pages, wl.block_table, wl.context_lens, wl.scale, rows)
@@ -280,7 +280,7 @@ def test_full_size_config_sampled_rows(sd, cfg):
 def test_full_size_branching_mix_with_append(sd):
     import torch
     wl = workloads.make_config(3)
-    dw = device_workload(wl)
+    dw = device_workload(wl, balance_for_batch=True)
     dw.append()
     out = dw.attend()
     torch.cuda.synchronize()
@@ -374,12 +374,23 @@ def test_fp8_head_dim_64_is_reported_unsupported(sd):
 
 
 def test_full_size_fp8_large_batch(sd):
-    wl = workloads.make_config(4)
-    got = gpu_attend(wl)
+    """The step bench.py times at this workload: quantising append of one token per sequence, then attention
+    with one chunk per sequence (no merge pass)."""
+    import torch
+    wl = workloads.make_config(4, append=True)
+    dw = device_workload(wl, balance_for_batch=True)
+    assert dw.chunk_tokens() >= wl.max_context_len
+    dw.append()
+    got = dw.attend()
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
     assert not np.isnan(got).any()
+    k, v, ks, vs = wl.k_pages, wl.v_pages, wl.k_scales, wl.v_scales
+    oracle.kv_append_fp8(wl.k_new, wl.v_new, wl.seq_ids, wl.positions, np.arange(len(wl.seq_ids) + 1, dtype=np.int32),
+                         k, v, ks, vs, wl.block_table)
+    assert np.array_equal(dw.k_pages.cpu().numpy(), k) and np.array_equal(dw.v_pages.cpu().numpy(), v)
     rows = sampled_rows(wl, 128)
-    ref = oracle.attend_rows(wl.q, wl.k_pages, wl.v_pages, wl.block_table, wl.context_lens, wl.scale, rows,
-                             wl.k_scales, wl.v_scales, "fp8")
+    ref = oracle.attend_rows(wl.q, k, v, wl.block_table, wl.context_lens, wl.scale, rows, ks, vs, "fp8")
     check_fp8(got[rows[:, 0], rows[:, 1]], ref)
 
 
@@ -450,7 +461,7 @@ def test_prefix_entry_point_without_groups_is_the_plain_call(sd):
 def test_full_size_branching_mix_prefix_aware(sd):
     import torch
     wl = workloads.make_config(3)
-    dw = device_workload(wl)
+    dw = device_workload(wl, balance_for_batch=True)
     dw.append()
     out = dw.attend_prefix()
     torch.cuda.synchronize()
