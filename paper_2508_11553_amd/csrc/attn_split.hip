@@ -106,10 +106,12 @@ SD_DEV int shared_tokens(const SplitArgs &a, int b)
 // column block w (G heads each of 16/G consecutive sequences of the group).
 // The pages are the same for every member, so the first member's table row is
 // read.  Per round each wave loads a different 32-token tile from HBM (one
-// round prefetched ahead), parks it in its LDS slot, and after a barrier every
-// wave attends all four tiles from LDS with its own rows: each byte leaves HBM
-// once per workgroup and the four-fold reuse is paid in LDS bandwidth.  Every
-// wave writes the partials of its own rows; nothing is merged across waves.
+// round prefetched ahead), parks its K image and the ready-made V^T operands
+// in its LDS slot, and after a barrier every wave attends all four tiles from
+// LDS with its own rows: each byte leaves HBM once per workgroup and the
+// four-fold reuse is paid in LDS bandwidth.  These items fold |scale| into the
+// exponent and take the sign of the scale through the queries (q_flip, q_keep).
+// Every wave writes the partials of its own rows; nothing is merged across waves.
 template <class P>
 SD_DEV void shared_item(const SplitArgs &a, char *lds, int lane, int wave)
 {
