@@ -371,6 +371,7 @@ def main():
         },
         "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
         "attended_kv_tokens_per_s": wl.attended_tokens / (ms_per_step * 1e-3),
+        "attended_kv_head_tokens_per_s": wl.attended_tokens * wl.num_kv_heads / (ms_per_step * 1e-3),
         "step_bytes": ab, "logical_GBps": ab_logical["step"] / (ms_per_step * 1e-3) / 1e9,
         "kernel_ms": {"split": split_avg, "merge": merge_avg, "split_p10_p50_p90":
                       [float(np.percentile(split_ms, p)) for p in (10, 50, 90)]},
