@@ -61,7 +61,8 @@ extern "C" {
 typedef struct {
     int32_t batch;              /* B >= 0 (0: the call is a no-op) */
     int32_t num_q_heads;        /* Hq */
-    int32_t num_kv_heads;       /* Hkv; Hq % Hkv == 0 and Hq / Hkv <= 16 */
+    int32_t num_kv_heads;       /* Hkv; Hq % Hkv == 0 and Hq / Hkv <= 64 (above 16 the K/V of a head
+                                   is read once per block of 16 query heads, mostly from cache) */
     int32_t head_dim;           /* 64 or 128 (fp8 pools: 128 only) */
     int32_t page_size;          /* must be 16 */
     int32_t num_pages;          /* extent of the pools */

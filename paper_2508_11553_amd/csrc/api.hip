@@ -37,7 +37,7 @@ int check_shape(const sd_shape *s)
         return SD_EINVAL;
     if (s->head_dim != 64 && s->head_dim != 128) return SD_EUNSUPPORTED;
     if (s->kv_dtype == SD_FP8_E4M3 && s->head_dim != 128) return SD_EUNSUPPORTED;
-    if (s->num_q_heads / s->num_kv_heads > sd::kMaxGroup) return SD_EUNSUPPORTED;
+    if (s->num_q_heads / s->num_kv_heads > sd::kMaxGroup * sd::kMaxHeadBlocks) return SD_EUNSUPPORTED;
     return SD_OK;
 }
 
@@ -282,20 +282,22 @@ int paged_decode_attention_prefix(const sd_shape *shape, const void *q, const vo
     sa.Hq = shape->num_q_heads;
     sa.Hkv = shape->num_kv_heads;
     sa.G = shape->num_q_heads / shape->num_kv_heads;
+    sa.HB = sd::head_blocks(sa.G);
     sa.max_blocks = shape->max_blocks_per_seq;
     sa.S = S;
     sa.chunk_tokens = chunk;
     sa.max_context_len = shape->max_context_len;
     // shared-prefix items: whole chunks of each group's shared prefix, 4 waves x (16 / G) sequences per workgroup
     const int shared_chunks = num_groups > 0 ? (max_shared_len + chunk - 1) / chunk : 0;
-    const int seqs_per_wg = sd::kWaves * (sa.G <= sd::kMaxGroup / 2 ? sd::kMaxGroup / sa.G : 1);
+    const int seqs_per_wg = sd::kWaves * sd::units_per_block(sa.G);
     sa.group_start = shared_chunks ? group_start : nullptr;
     sa.shared_len = shared_chunks ? shared_len : nullptr;
     sa.num_groups = shared_chunks ? num_groups : 0;
     sa.group_subs = shared_chunks ? (max_group_size + seqs_per_wg - 1) / seqs_per_wg : 0;
-    const uint64_t group_items = (uint64_t)shared_chunks * (uint64_t)sa.num_groups * (uint64_t)sa.group_subs * (uint64_t)sa.Hkv;
+    const uint64_t group_items = (uint64_t)shared_chunks * (uint64_t)sa.num_groups * (uint64_t)sa.group_subs *
+                                 (uint64_t)(sa.Hkv * sa.HB);
     sa.grid_chunks = shared_chunks ? S : S - 1;  // the extra slot exists only where a shared prefix splits a chunk
-    const uint64_t plain_items = (uint64_t)sa.grid_chunks * (uint64_t)shape->batch * (uint64_t)shape->num_kv_heads;
+    const uint64_t plain_items = (uint64_t)sa.grid_chunks * (uint64_t)shape->batch * (uint64_t)(sa.Hkv * sa.HB);
     if (group_items + plain_items > 0x7fffffffull) return SD_EUNSUPPORTED;
     sa.group_items = (uint32_t)group_items;
     sa.max_shared_len = max_shared_len;
@@ -388,13 +390,14 @@ int paged_prefill_attention(const sd_shape *shape, const void *q, const int32_t 
     a.Hq = shape->num_q_heads;
     a.Hkv = shape->num_kv_heads;
     a.G = shape->num_q_heads / shape->num_kv_heads;
+    a.HB = sd::head_blocks(a.G);
     a.max_blocks = shape->max_blocks_per_seq;
     a.max_context_len = shape->max_context_len;
     a.total_q = total_q;
     a.max_q_len = max_q_len < total_q ? max_q_len : total_q;
-    const int tokens_per_wg = sd::kWaves * sd::kPrefillBlocks * (a.G <= sd::kMaxGroup / 2 ? sd::kMaxGroup / a.G : 1);
+    const int tokens_per_wg = sd::kWaves * sd::kPrefillBlocks * sd::units_per_block(a.G);
     a.q_blocks = (a.max_q_len + tokens_per_wg - 1) / tokens_per_wg;
-    if ((uint64_t)a.q_blocks * (uint64_t)a.B * (uint64_t)a.Hkv > 0x7ffffff0ull) return SD_EUNSUPPORTED;
+    if ((uint64_t)a.q_blocks * (uint64_t)a.B * (uint64_t)(a.Hkv * a.HB) > 0x7ffffff0ull) return SD_EUNSUPPORTED;
     hipEvent_t none[2] = {nullptr, nullptr};
     hipEvent_t *ev = timer ? &timer->ev[(size_t)timer->calls * 4] : none;
     const hipError_t e = sd::launch_prefill(a, shape->head_dim, shape->kv_dtype, static_cast<hipStream_t>(stream), ev[0], ev[1]);

@@ -37,11 +37,13 @@ __global__ __launch_bounds__(kWaves * 64, 2) void prefill_kernel(PrefillArgs a)
     // range at about the same pace, and all but the first find the tiles in that L2.
     const unsigned per_xcd = gridDim.x / kXcds;  // the grid is padded to a multiple of kXcds
     const unsigned item = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
-    if (item >= (unsigned)a.q_blocks * (unsigned)a.B * (unsigned)a.Hkv) return;
+    const int Hv = a.Hkv * a.HB;
+    if (item >= (unsigned)a.q_blocks * (unsigned)a.B * (unsigned)Hv) return;
     const int jb = a.q_blocks - 1 - (int)(item % a.q_blocks);
-    const int g = (item / a.q_blocks) % a.Hkv;
-    const int b = item / ((unsigned)a.q_blocks * a.Hkv);
-    const int tpb = a.G <= kMaxGroup / 2 ? kMaxGroup / a.G : 1;  // query tokens per column block
+    const HeadBlock hb = head_block((item / a.q_blocks) % Hv, a.G, a.HB);
+    const int g = hb.g;
+    const int b = item / ((unsigned)a.q_blocks * Hv);
+    const int tpb = units_per_block(a.G);  // query tokens per column block
     const int tpw = kPrefillBlocks * tpb;                        // and per wave
 
     // everything below up to the loop is workgroup-uniform
@@ -64,10 +66,10 @@ __global__ __launch_bounds__(kWaves * 64, 2) void prefill_kernel(PrefillArgs a)
     // row of column block c in this lane: query token, whether it exists, whether it sees a token
     // (recomputed where needed rather than kept in registers across the loop)
     auto locate = [&](int c, bool &in_range, bool &row_ok, int64_t &row) {
-        const int i = iw0 + c * tpb + n / a.G;
-        in_range = n / a.G < tpb && i < nq;
+        const int i = iw0 + c * tpb + n / hb.rows;
+        in_range = n / hb.rows < tpb && i < nq;
         row_ok = in_range && base + i >= 0;
-        row = ((int64_t)qs + i) * a.Hq + g * a.G + n % a.G;
+        row = ((int64_t)qs + i) * a.Hq + hb.head0 + n % hb.rows;
         return i;
     };
     int row_end[NB];
@@ -145,7 +147,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void prefill_kernel(PrefillArgs a)
 hipError_t launch_prefill(const PrefillArgs &a, int head_dim, int kv_dtype, hipStream_t stream, hipEvent_t start,
                           hipEvent_t stop)
 {
-    const unsigned items = (unsigned)a.q_blocks * (unsigned)a.B * (unsigned)a.Hkv;
+    const unsigned items = (unsigned)a.q_blocks * (unsigned)a.B * (unsigned)(a.Hkv * a.HB);
     if (items == 0) return hipSuccess;
     const unsigned grid = (items + kXcds - 1) / kXcds * kXcds;
     const dim3 g(grid), b(kWaves * 64);

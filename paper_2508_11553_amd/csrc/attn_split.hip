@@ -117,13 +117,15 @@ SD_DEV void shared_item(const SplitArgs &a, char *lds, int lane, int wave)
 {
     constexpr int D = P::kDim;
     constexpr int kSlot = Lds<P>::kSlotBytes;
-    const unsigned item = blockIdx.x;  // (chunk, group, block of 4 column blocks, kv head), kv head fastest
-    const int g = item % a.Hkv;
-    const int sub = (item / a.Hkv) % a.group_subs;
-    const int grp = (item / (a.Hkv * a.group_subs)) % a.num_groups;
-    const int c = item / (a.Hkv * a.group_subs * a.num_groups);
+    const unsigned item = blockIdx.x;  // (chunk, group, block of 4 column blocks, head block), head block fastest
+    const int Hv = a.Hkv * a.HB;
+    const HeadBlock hb = head_block(item % Hv, a.G, a.HB);
+    const int g = hb.g;
+    const int sub = (item / Hv) % a.group_subs;
+    const int grp = (item / (Hv * a.group_subs)) % a.num_groups;
+    const int c = item / (Hv * a.group_subs * a.num_groups);
     const int gs = a.group_start[grp], ge = a.group_start[grp + 1];
-    const int spw = a.G <= kMaxGroup / 2 ? kMaxGroup / a.G : 1;  // sequences per column block
+    const int spw = units_per_block(a.G);  // sequences per column block
     if (gs + sub * kWaves * spw >= ge) return;                    // workgroup-uniform
     const int shared = shared_tokens(a, gs);
     const int t0 = c * a.chunk_tokens;
@@ -133,9 +135,9 @@ SD_DEV void shared_item(const SplitArgs &a, char *lds, int lane, int wave)
     const int seq0 = gs + (sub * kWaves + wave) * spw;
     const bool active = seq0 < ge;  // wave-uniform; idle waves still load their tile and meet the barriers
     const int n = lane & 15;
-    const int row_seq = seq0 + n / a.G;
-    const int64_t row = (int64_t)row_seq * a.Hq + g * a.G + n % a.G;
-    const bool row_ok = active && n / a.G < spw && row_seq < ge;
+    const int row_seq = seq0 + n / hb.rows;
+    const int64_t row = (int64_t)row_seq * a.Hq + hb.head0 + n % hb.rows;
+    const bool row_ok = active && n / hb.rows < spw && row_seq < ge;
     u32x4 qop[D / 32];
 #pragma unroll
     for (int s = 0; s < D / 32; ++s)
@@ -224,9 +226,11 @@ __global__ __launch_bounds__(kWaves * 64, 2) void split_kernel(SplitArgs a)
     // hold every sequence's last chunk, which is the short one, so the workgroups that run
     // while the machine drains are the small ones.
     const unsigned item = blockIdx.x - a.group_items;
-    const int g = item % a.Hkv;
-    const int b = (item / a.Hkv) % a.B;
-    const int from_end = a.grid_chunks - 1 - (int)(item / (a.Hkv * a.B));
+    const int Hv = a.Hkv * a.HB;
+    const HeadBlock hb = head_block(item % Hv, a.G, a.HB);
+    const int g = hb.g;
+    const int b = (item / Hv) % a.B;
+    const int from_end = a.grid_chunks - 1 - (int)(item / (Hv * a.B));
 
     const int L = min(a.context_lens[b], a.max_context_len);
     // slots of a shared prefix belong to the shared-prefix items; the others start where the prefix ends
@@ -236,22 +240,22 @@ __global__ __launch_bounds__(kWaves * 64, 2) void split_kernel(SplitArgs a)
     if (c_private < 0) {
         // single-chunk mode: an empty sequence still owes its zero rows
         if (a.out_direct && L == 0 && from_end == 0)
-            for (int idx = tid; idx < a.G * D; idx += kWaves * 64)
-                a.out_direct[((int64_t)b * a.Hq + (int64_t)g * a.G) * D + idx] = 0.f;
+            for (int idx = tid; idx < hb.rows * D; idx += kWaves * 64)
+                a.out_direct[((int64_t)b * a.Hq + hb.head0) * D + idx] = 0.f;
         return;
     }
     const int c = shared_slots(shared, a.chunk_tokens) + c_private;  // slot of this chunk
     const int t0 = shared + c_private * a.chunk_tokens;
     const int t1 = min(L, t0 + a.chunk_tokens);
 
-    // Q^T operand: lane&15 = head n; heads >= G are zero rows
+    // Q^T operand: lane&15 = head n of the block; rows past the block's heads are zero
     const int n = lane & 15;
     u32x4 qop[D / 32];
     {
-        const uint16_t *qrow = a.q + ((int64_t)b * a.Hq + (int64_t)g * a.G + n) * D;
+        const uint16_t *qrow = a.q + ((int64_t)b * a.Hq + hb.head0 + n) * D;
 #pragma unroll
         for (int s = 0; s < D / 32; ++s)
-            qop[s] = (n < a.G) ? *reinterpret_cast<const u32x4 *>(qrow + P::q_offset(s, lane)) : u32x4{0, 0, 0, 0};
+            qop[s] = (n < hb.rows) ? *reinterpret_cast<const u32x4 *>(qrow + P::q_offset(s, lane)) : u32x4{0, 0, 0, 0};
     }
 
     typename P::State st;
@@ -271,8 +275,8 @@ __global__ __launch_bounds__(kWaves * 64, 2) void split_kernel(SplitArgs a)
     __syncthreads();
 
     // merge the four waves; wave 0 always saw at least one token, so the max is finite
-    const int64_t row0 = (int64_t)b * a.Hq + (int64_t)g * a.G;
-    for (int idx = tid; idx < a.G * D; idx += kWaves * 64) {
+    const int64_t row0 = (int64_t)b * a.Hq + hb.head0;
+    for (int idx = tid; idx < hb.rows * D; idx += kWaves * 64) {
         const int hn = idx / D, dd = idx % D;
         float M = s_m[0][hn];
 #pragma unroll
@@ -311,7 +315,7 @@ static void launch_one(const SplitArgs &a, dim3 g, dim3 b, hipStream_t stream, h
 hipError_t launch_split(const SplitArgs &a, int head_dim, int kv_dtype, hipStream_t stream,
                         hipEvent_t start, hipEvent_t stop)
 {
-    const unsigned grid = a.group_items + (unsigned)a.grid_chunks * (unsigned)a.B * (unsigned)a.Hkv;
+    const unsigned grid = a.group_items + (unsigned)a.grid_chunks * (unsigned)a.B * (unsigned)(a.Hkv * a.HB);
     if (grid == 0) return hipSuccess;
     const dim3 g(grid), b(kWaves * 64);
     if (kv_dtype == 0 && head_dim == 128)

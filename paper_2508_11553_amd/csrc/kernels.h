@@ -11,6 +11,25 @@ constexpr int kPage = 16;           // tokens per page
 constexpr int kWaves = 4;           // waves per workgroup of the split pass
 constexpr int kTileTokens = 32;     // tokens one wave consumes per iteration (two pages)
 constexpr int kMaxGroup = 16;       // query heads per KV head that fit one MFMA tile
+constexpr int kMaxHeadBlocks = 4;   // a KV head with more query heads is served as up to 4 blocks of 16
+
+// A KV head with G > 16 query heads is split into HB = ceil(G / 16) "virtual" KV heads that read the
+// same K/V tiles: virtual head gv = g * HB + hb owns the query heads g * G + 16 * hb .. (16 of them, the
+// last block G - 16 * (HB - 1)).  With G <= 16 there is one block and gv == g.
+struct HeadBlock {
+    int g;       // KV head (addresses the pools)
+    int head0;   // first query head of the block
+    int rows;    // query heads in the block (<= 16)
+};
+__host__ __device__ inline int head_blocks(int G) { return (G + kMaxGroup - 1) / kMaxGroup; }
+__host__ __device__ inline HeadBlock head_block(int gv, int G, int HB)
+{
+    const int g = gv / HB, hb = gv - g * HB;
+    const int left = G - hb * kMaxGroup;
+    return HeadBlock{g, g * G + hb * kMaxGroup, left < kMaxGroup ? left : kMaxGroup};
+}
+// Sequences (decode) or query tokens (causal pass) that share one 16-row column block.
+__host__ __device__ inline int units_per_block(int G) { return G <= kMaxGroup / 2 ? kMaxGroup / G : 1; }
 constexpr int kXcds = 8;            // accelerator dies, each with its own L2; workgroup i runs on die i % 8
 constexpr int kPrefillBlocks = 2;   // 16-row column blocks one wave of the causal pass carries
 
@@ -40,6 +59,7 @@ struct SplitArgs {
     float abs_scale_log2e;
     uint32_t q_flip, q_keep;
     int32_t B, Hq, Hkv, G;
+    int32_t HB;                  // head blocks per KV head: ceil(G / 16)
     int32_t max_blocks, S, chunk_tokens, max_context_len;
     // shared-prefix groups (all zero / null when the call has none)
     const int32_t *group_start;  // [num_groups + 1] first sequence of each group
@@ -70,7 +90,7 @@ struct PrefillArgs {
     float scale_log2e;           // |scale| * log2(e); the sign of scale travels in q_flip
     uint32_t q_flip;             // 0x80008000 when scale < 0: every query element changes sign as it is loaded
     uint32_t q_keep;             // 0 when scale == 0 (all scores are zero: zero queries, scale 1), else all ones
-    int32_t B, Hq, Hkv, G, max_blocks, max_context_len;
+    int32_t B, Hq, Hkv, G, HB, max_blocks, max_context_len;  // HB: head blocks per KV head, ceil(G / 16)
     int32_t total_q, max_q_len;  // rows of q; host-known bound on the rows of one sequence
     int32_t q_blocks;            // workgroups (4 waves x kPrefillBlocks x 16/G query tokens each) that cover max_q_len
 };

@@ -63,7 +63,7 @@ def test_config0_tiny_paged_decode(sd):
 
 
 @pytest.mark.parametrize("d", [64, 128])
-@pytest.mark.parametrize("Hq,Hkv", [(1, 1), (4, 1), (8, 2), (28, 4), (16, 2), (32, 2)])
+@pytest.mark.parametrize("Hq,Hkv", [(1, 1), (4, 1), (8, 2), (28, 4), (16, 2), (32, 2), (17, 1), (32, 1), (40, 2), (64, 1)])
 def test_group_sizes_and_head_dims(sd, Hq, Hkv, d):
     lens = [1, 2, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 300, 511, 512, 513, 1025]
     wl = workloads.make_custom(lens, Hq, Hkv, d, seed=100 + Hq + d)
@@ -403,7 +403,7 @@ def gpu_attend_prefix(wl, **kw):
     return out.cpu().numpy()
 
 
-@pytest.mark.parametrize("Hq,Hkv,d", [(8, 2, 128), (28, 4, 128), (8, 1, 64), (16, 1, 128), (3, 1, 128)])
+@pytest.mark.parametrize("Hq,Hkv,d", [(8, 2, 128), (28, 4, 128), (8, 1, 64), (16, 1, 128), (3, 1, 128), (40, 2, 128)])
 @pytest.mark.parametrize("chunk", [128, 512])
 def test_prefix_entry_point_matches_oracle(sd, Hq, Hkv, d, chunk):
     """Groups of 1, 2, 5, 16 and 19 sequences; shared prefixes that are shorter than a chunk, end inside

@@ -45,7 +45,7 @@ def gpu(wl, q, q_start):
 
 
 @pytest.mark.parametrize("kv_dtype,d", [("bf16", 64), ("bf16", 128), ("fp8", 128)])
-@pytest.mark.parametrize("Hq,Hkv", [(1, 1), (4, 2), (8, 1), (28, 4), (6, 2), (16, 1), (32, 4)])
+@pytest.mark.parametrize("Hq,Hkv", [(1, 1), (4, 2), (8, 1), (28, 4), (6, 2), (16, 1), (32, 4), (17, 1), (40, 2), (64, 1)])
 def test_ragged_query_counts_over_several_tiles(sd, Hq, Hkv, d, kv_dtype):
     # query counts below, at and above a workgroup's block, context lengths across page, tile and round edges
     lens = [1, 7, 16, 33, 64, 129, 130, 257, 300, 511, 640, 1000]

@@ -11,7 +11,8 @@ from tests.test_gpu_parity import check, check_fp8, device_workload, gpu_attend,
 
 pytestmark = pytest.mark.gpu
 
-HEADS = [(1, 1), (2, 1), (3, 1), (4, 2), (6, 2), (7, 1), (8, 2), (8, 8), (16, 1), (12, 4), (28, 4), (32, 2)]
+HEADS = [(1, 1), (2, 1), (3, 1), (4, 2), (6, 2), (7, 1), (8, 2), (8, 8), (16, 1), (12, 4), (28, 4), (32, 2),
+         (17, 1), (32, 1), (40, 2), (64, 1), (48, 2)]   # the last five: more than 16 query heads per KV head
 
 
 def draw_lens(rng, n, hi):
