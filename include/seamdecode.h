@@ -20,7 +20,8 @@
  *     stream) and returns.
  *   - Return value: SD_OK (0) or a negative SD_E* code.  On a validation
  *     error nothing is enqueued and no output is written.
- *   - No global state: calls from several host threads are independent.
+ *   - No global state (paged_decode_attention_static excepted, which owns one
+ *     scratch array per GPU): calls from several host threads are independent.
  *     Calls that write the same output/workspace/pages must be ordered by the
  *     caller (same stream or events).
  *
@@ -198,6 +199,32 @@ int paged_decode_attention(const sd_shape *shape, const void *q,
                            const int32_t *block_table, const int32_t *context_lens,
                            float scale, float *out,
                            void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * paged_decode_attention_static -- paged_decode_attention without a workspace
+ * argument, for callers that cannot allocate device memory: code running under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ *
+ * The split pass's partials go to an array of SD_STATIC_SCRATCH_BYTES bytes that
+ * is part of the library itself (every GPU the library runs on holds its own
+ * copy until the process ends).  The call allocates and frees nothing; the
+ * first call on a device looks the array's address up (current device = the
+ * device of `stream`), so make that first call outside graph capture.  Same
+ * kernels, same arithmetic and bit-identical results as paged_decode_attention
+ * with the same shape.
+ *
+ * Returns SD_EWORKSPACE, before anything is enqueued, when the shape needs more
+ * scratch than the array holds (sd_workspace_bytes(shape) >
+ * SD_STATIC_SCRATCH_BYTES; shapes whose every sequence is one chunk need none).
+ * All calls on one GPU share the one array: calls that overlap in time on the
+ * same GPU (different streams, different host threads) race; order them.
+ */
+#define SD_STATIC_SCRATCH_BYTES (32u << 20)
+int paged_decode_attention_static(const sd_shape *shape, const void *q,
+                                  const void *k_pages, const void *v_pages,
+                                  const float *k_scales, const float *v_scales,
+                                  const int32_t *block_table, const int32_t *context_lens,
+                                  float scale, float *out, void *stream);
 
 /*
  * paged_decode_attention_prefix -- the same result as paged_decode_attention

@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     load,
     paged_decode_attention,
     paged_decode_attention_prefix,
+    paged_decode_attention_static,
     paged_prefill_attention,
     probe_read,
     strerror,

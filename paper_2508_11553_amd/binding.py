@@ -67,6 +67,8 @@ def load():
     L.kv_append.argtypes = [sp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
     L.paged_decode_attention.restype = ctypes.c_int
     L.paged_decode_attention.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, sz, vp]
+    L.paged_decode_attention_static.restype = ctypes.c_int
+    L.paged_decode_attention_static.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp]
     L.paged_decode_attention_timed.restype = ctypes.c_int
     L.paged_decode_attention_timed.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, sz, vp, vp]
     L.kv_append_fp8.restype = ctypes.c_int
@@ -207,6 +209,14 @@ def paged_decode_attention(shape: Shape, q, k_pages, v_pages, k_scales, v_scales
                                             float(scale), _ptr(out), _ptr(workspace), int(workspace_nbytes),
                                             _stream(stream), timer._h)
     _check(rc, "paged_decode_attention")
+
+
+def paged_decode_attention_static(shape: Shape, q, k_pages, v_pages, k_scales, v_scales, block_table, context_lens,
+                                  scale: float, out, stream=None):
+    rc = load().paged_decode_attention_static(ctypes.byref(shape), _ptr(q), _ptr(k_pages), _ptr(v_pages),
+                                              _ptr(k_scales), _ptr(v_scales), _ptr(block_table), _ptr(context_lens),
+                                              float(scale), _ptr(out), _stream(stream))
+    _check(rc, "paged_decode_attention_static")
 
 
 def paged_decode_attention_prefix(shape: Shape, q, k_pages, v_pages, k_scales, v_scales, block_table, context_lens,

@@ -5,8 +5,14 @@
 #include "kernels.h"
 
 #include <algorithm>
+#include <atomic>
 #include <new>
 #include <vector>
+
+// Scratch of paged_decode_attention_static: one array per GPU, part of the library's code object, so it
+// exists on a device from the moment the library is loaded there until the process ends.  In host
+// code the array's name is only a handle, not a device address.
+static __device__ __align__(256) unsigned char scratch[SD_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -98,6 +104,28 @@ WsLayout ws_layout(const sd_shape *s, int S)
     w.acc_off = w.l_off + ((rows * 4 + 255) & ~(size_t)255);
     w.total = w.acc_off + rows * (size_t)s->head_dim * 4;
     return w;
+}
+
+// The device address of `scratch` is asked for once per device, with that device current, and kept.
+constexpr size_t kStaticScratchBytes = SD_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+// Address of the current device's scratch array.
+int static_scratch(void **ptr)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev < 0 || dev >= kMaxDevices) return SD_EUNSUPPORTED;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return hip_fail(e == hipSuccess ? hipErrorInvalidSymbol : e);
+        g_scratch_ptr[dev].store(p, std::memory_order_release);  // every thread gets the same address
+    }
+    *ptr = p;
+    return SD_OK;
 }
 
 }  // namespace
@@ -237,12 +265,18 @@ int kv_copy_pages(const sd_shape *shape, const int32_t *src_pages, const int32_t
     return e == hipSuccess ? SD_OK : hip_fail(e);
 }
 
-int paged_decode_attention_prefix(const sd_shape *shape, const void *q, const void *k_pages,
-                                  const void *v_pages, const float *k_scales, const float *v_scales,
-                                  const int32_t *block_table, const int32_t *context_lens,
-                                  const int32_t *group_start, const int32_t *shared_len, int32_t num_groups,
-                                  int32_t max_group_size, int32_t max_shared_len, float scale, float *out,
-                                  void *workspace, size_t workspace_bytes, void *stream, sd_timer *timer)
+}  // extern "C"
+
+namespace {
+
+// The decode step behind every attention entry point.  `own_scratch`: the workspace is the
+// library's own per-device array (looked up here, after validation); only the bytes the launch
+// really uses are checked against its size.
+int attend_impl(const sd_shape *shape, const void *q, const void *k_pages, const void *v_pages,
+                const float *k_scales, const float *v_scales, const int32_t *block_table,
+                const int32_t *context_lens, const int32_t *group_start, const int32_t *shared_len,
+                int32_t num_groups, int32_t max_group_size, int32_t max_shared_len, float scale, float *out,
+                void *workspace, size_t workspace_bytes, void *stream, sd_timer *timer, bool own_scratch)
 {
     const int rc = check_shape(shape);
     if (rc) return rc;
@@ -250,7 +284,7 @@ int paged_decode_attention_prefix(const sd_shape *shape, const void *q, const vo
         return SD_EINVAL;
     if (shape->batch == 0) return SD_OK;
     if (bad_ptr(q) || bad_ptr(k_pages) || bad_ptr(v_pages) || bad_ptr(block_table) || bad_ptr(context_lens) ||
-        bad_ptr(out) || bad_ptr(workspace))
+        bad_ptr(out) || (!own_scratch && bad_ptr(workspace)))
         return SD_EINVAL;
     if (shape->kv_dtype == SD_FP8_E4M3 && (bad_ptr(k_scales) || bad_ptr(v_scales))) return SD_EINVAL;
     if (num_groups > 0 && (bad_ptr(group_start) || bad_ptr(shared_len) || max_group_size < 1)) return SD_EINVAL;
@@ -258,7 +292,16 @@ int paged_decode_attention_prefix(const sd_shape *shape, const void *q, const vo
     const int chunk = pick_chunk(shape);
     const int S = num_chunks(shape, chunk);
     const WsLayout w = ws_layout(shape, S);
-    if (workspace_bytes < w.total) return SD_EWORKSPACE;
+    // every sequence fits one chunk and nothing is shared: the split pass normalises and writes `out` itself
+    const int shared_chunks = num_groups > 0 ? (max_shared_len + chunk - 1) / chunk : 0;
+    const bool direct = !shared_chunks && shape->max_context_len <= chunk;
+    if (own_scratch) {
+        if (!direct && w.total > kStaticScratchBytes) return SD_EWORKSPACE;
+        const int src = static_scratch(&workspace);
+        if (src) return src;
+    } else if (workspace_bytes < w.total) {
+        return SD_EWORKSPACE;
+    }
     if (timer && timer->calls >= timer->max_calls) return SD_EINVAL;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -288,7 +331,6 @@ int paged_decode_attention_prefix(const sd_shape *shape, const void *q, const vo
     sa.chunk_tokens = chunk;
     sa.max_context_len = shape->max_context_len;
     // shared-prefix items: whole chunks of each group's shared prefix, 4 waves x (16 / G) sequences per workgroup
-    const int shared_chunks = num_groups > 0 ? (max_shared_len + chunk - 1) / chunk : 0;
     const int seqs_per_wg = sd::kWaves * sd::units_per_block(sa.G);
     sa.group_start = shared_chunks ? group_start : nullptr;
     sa.shared_len = shared_chunks ? shared_len : nullptr;
@@ -301,8 +343,6 @@ int paged_decode_attention_prefix(const sd_shape *shape, const void *q, const vo
     if (group_items + plain_items > 0x7fffffffull) return SD_EUNSUPPORTED;
     sa.group_items = (uint32_t)group_items;
     sa.max_shared_len = max_shared_len;
-    // every sequence fits one chunk and nothing is shared: the split pass normalises and writes `out` itself
-    const bool direct = !shared_chunks && shape->max_context_len <= chunk;
     sa.out_direct = direct ? out : nullptr;
 
     sd::MergeArgs ma;
@@ -333,6 +373,30 @@ int paged_decode_attention_prefix(const sd_shape *shape, const void *q, const vo
     }
     if (timer) timer->calls++;
     return SD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int paged_decode_attention_prefix(const sd_shape *shape, const void *q, const void *k_pages,
+                                  const void *v_pages, const float *k_scales, const float *v_scales,
+                                  const int32_t *block_table, const int32_t *context_lens,
+                                  const int32_t *group_start, const int32_t *shared_len, int32_t num_groups,
+                                  int32_t max_group_size, int32_t max_shared_len, float scale, float *out,
+                                  void *workspace, size_t workspace_bytes, void *stream, sd_timer *timer)
+{
+    return attend_impl(shape, q, k_pages, v_pages, k_scales, v_scales, block_table, context_lens, group_start,
+                       shared_len, num_groups, max_group_size, max_shared_len, scale, out, workspace,
+                       workspace_bytes, stream, timer, false);
+}
+
+int paged_decode_attention_static(const sd_shape *shape, const void *q, const void *k_pages, const void *v_pages,
+                                  const float *k_scales, const float *v_scales, const int32_t *block_table,
+                                  const int32_t *context_lens, float scale, float *out, void *stream)
+{
+    return attend_impl(shape, q, k_pages, v_pages, k_scales, v_scales, block_table, context_lens, nullptr, nullptr,
+                       0, 0, 0, scale, out, nullptr, 0, stream, nullptr, true);
 }
 
 int paged_decode_attention_timed(const sd_shape *shape, const void *q, const void *k_pages,

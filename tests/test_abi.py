@@ -151,6 +151,15 @@ def test_empty_calls_are_noops(lib):
     assert lib.kv_append(ctypes.byref(good_shape()), None, None, None, None, 0, None, None, None, None) == 0
 
 
+def test_shapes_beyond_the_scratch_array_are_refused(lib):
+    """Rejected on the host before any HIP call; nothing is enqueued."""
+    s = sd.Shape(batch=4096, num_q_heads=64, num_kv_heads=8, head_dim=128, page_size=16, num_pages=16,
+                 max_blocks_per_seq=512, kv_dtype=sd.SD_BF16, max_context_len=8192, chunk_tokens=1024)
+    assert sd.workspace_bytes(s) > 32 << 20
+    rc = sd.load().paged_decode_attention_static(ctypes.byref(s), 16, 16, 16, None, None, 16, 16, 1.0, 16, None)
+    assert rc == -3
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     from paper_2508_11553_amd import binding
     monkeypatch.setattr(binding, "_lib", None)
