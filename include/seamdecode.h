@@ -1,10 +1,9 @@
 /*
  * libseamdecode -- paged decode attention for rollout on MI355X (gfx950).
  *
- * The paper's framework spends its run time in rollout: batched autoregressive
- * decoding inside the inference engine (System Overview, engine layer;
- * Pipeline Bubble Analysis: rollout takes much longer than training).  Each
- * decode step attends one new query token per sequence over that sequence's
+ * The paper's framework spends most of its run time in rollout, i.e. batched
+ * autoregressive decoding inside the inference engine (System Overview, engine
+ * layer; Pipeline Bubble Analysis).  Each decode step attends one new query token per sequence over that sequence's
  * KV cache.  Sequences have different lengths, are paused and resumed from
  * their stored tokens (Data Plane: Rollout Manager, Trajectory Manager) and
  * several trajectories of one session continue a common prefix (Trajectory
@@ -177,7 +176,12 @@ int kv_copy_pages(const sd_shape *shape, const int32_t *src_pages, const int32_t
 /*
  * paged_decode_attention -- one decode step of attention for every sequence.
  *
- * For each sequence b with L = min(context_lens[b], max_context_len) tokens
+ * The step rollout repeats for every generated token (System Overview,
+ * inference-engine layer; Data Plane: trajectories of different lengths that are
+ * paused, resumed and branched share one paged cache).
+ *
+ * For each sequence b with L = min(max(context_lens[b], 0), max_context_len)
+ * tokens (a negative length counts as 0, a length above the bound as the bound)
  * and each query head h (g = h / G):
  *     s_t = scale * <q[b][h], K_t>,  p = softmax_t(s),  out[b][h] = sum_t p_t V_t
  * with K_t, V_t the rows of KV head g at logical position t (fp8: code times

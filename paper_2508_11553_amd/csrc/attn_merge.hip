@@ -14,7 +14,7 @@ __global__ __launch_bounds__(D) void merge_kernel(MergeArgs a)
     const int row = blockIdx.x;  // b * Hq + h
     const int b = row / a.Hq;
     const int d = threadIdx.x;
-    const int L = min(a.context_lens[b], a.max_context_len);
+    const int L = max(0, min(a.context_lens[b], a.max_context_len));
     const int sh = a.shared_len ? max(0, min(min(a.shared_len[b], a.max_shared_len), L)) & ~(kPage - 1) : 0;
     const int n = shared_slots(sh, a.chunk_tokens) + (L - sh + a.chunk_tokens - 1) / a.chunk_tokens;
     float *o = a.out + (int64_t)row * D;

@@ -97,7 +97,7 @@ SD_DEV void stream_tiles(const SplitArgs &a, const int32_t *bt, int g, int t0, i
 // sequence has and never more than the host-side bound.
 SD_DEV int shared_tokens(const SplitArgs &a, int b)
 {
-    const int L = min(a.context_lens[b], a.max_context_len);
+    const int L = max(0, min(a.context_lens[b], a.max_context_len));
     return max(0, min(min(a.shared_len[b], a.max_shared_len), L)) & ~(kPage - 1);
 }
 
@@ -232,7 +232,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void split_kernel(SplitArgs a)
     const int b = (item / Hv) % a.B;
     const int from_end = a.grid_chunks - 1 - (int)(item / (Hv * a.B));
 
-    const int L = min(a.context_lens[b], a.max_context_len);
+    const int L = max(0, min(a.context_lens[b], a.max_context_len));
     // slots of a shared prefix belong to the shared-prefix items; the others start where the prefix ends
     const int shared = a.shared_len ? shared_tokens(a, b) : 0;
     const int n_private = (L - shared + a.chunk_tokens - 1) / a.chunk_tokens;

@@ -22,7 +22,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void probe_kernel(ProbeArgs a)
     const int g = item % a.Hkv;
     const int b = (item / a.Hkv) % a.B;
     const int c = item / (a.Hkv * a.B);
-    const int L = min(a.context_lens[b], a.max_context_len);
+    const int L = max(0, min(a.context_lens[b], a.max_context_len));
     const int t0 = c * a.chunk_tokens;
     if (t0 >= L) return;
     const int t1 = min(L, t0 + a.chunk_tokens);

@@ -1,12 +1,17 @@
 """Pins for the oracle's fp8 quantising append (CPU only).
 
 The encoder is pinned to torch's float8_e4m3fn conversion and to the input
-generator's own numpy encoder (three independent implementations); the append
-is pinned to a numpy transcription of its definition on whole-tile cases, and
-to properties that must hold whatever the arithmetic: scales never shrink,
-untouched slots keep their bits, values survive a scale change within the
-new quantisation step.
+generator's own numpy encoder (three independent implementations).  The append
+is pinned to what does not come from its own formula: fresh tiles to the recipe
+(absmax/448, nearest code); the re-encode branch (a tile whose scale must grow)
+to a table derived by hand from the format definition for power-of-two growth
+(tests/golden/e4m3fn_rescale.txt) and, for arbitrary growth, to the property
+that every old value lands on a nearest code of the new grid; plus scales never
+shrink and untouched slots keep their bits.  numpy_append below re-types the
+definition and only guards the tile bookkeeping (which slots change).
 """
+import os
+
 import numpy as np
 import pytest
 
@@ -85,6 +90,76 @@ def numpy_append(k_new, start, tile, scale):
     return tile, new_scale
 
 
+def assert_reencoded_to_a_nearest_code(old_codes, old_scale, new_codes, new_scale):
+    """The value an old code stood for, dec(c) * old_scale, expressed in units of the new scale, must
+    have gone to a code whose value is as near to it as any code's (computed in fp64 from the code
+    table: this is half a step of the format AT THAT MAGNITUDE, not of the top binade).  The fp32
+    ratio may move an exact tie by one part in 2^23, hence the slack."""
+    finite = np.array([c for c in range(256) if (c & 0x7F) != 0x7F])
+    vals = table()[finite].astype(np.float64)
+    y = table()[old_codes.ravel()].astype(np.float64) * np.float64(old_scale) / np.float64(new_scale)
+    got = table()[new_codes.ravel()].astype(np.float64)
+    best = np.abs(vals[None, :] - y[:, None]).min(axis=1)
+    assert (np.abs(got - y) <= best + 2.0 ** -20 * np.abs(y)).all()
+    assert (np.signbit(got) == np.signbit(y)).all()  # the sign survives, also when the value rounds to zero
+
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "e4m3fn_rescale.txt")
+
+
+@pytest.mark.parametrize("ratio,new_amax", [(0.5, 3.5), (0.25, 7.0)])
+def test_growth_by_a_power_of_two_shifts_exponents_as_derived_by_hand(ratio, new_amax):
+    """Pins the re-encode branch to values that do not come from its own formula: every finite code
+    (both signs) under a scale that doubles or quadruples, against the table derived by hand from the
+    format definition in tests/golden/e4m3fn_rescale.txt."""
+    want = {}
+    for line in open(GOLDEN):
+        if line.strip() and not line.startswith("#"):
+            r, c, n = line.split()
+            want[(float(r), int(c))] = int(n)
+    d = 128
+    pos = table()[:127].astype(np.float32) * np.float32(2.0 ** -8)   # dec(c) / 256 for c = 0 .. 126; 448 / 256 = 1.75
+    first = np.zeros((2, 1, d), np.float32)
+    first[0, 0, :127], first[1, 0, :127] = pos, -pos
+    bt = np.int32([[0]])
+    k, v, ks, vs = empty_pool(1, 1, d)
+    kn = f32_to_bf16_bits(first)
+    assert np.array_equal(bf16_bits_to_f32(kn), first)                # every value is a bf16 number
+    oracle.kv_append_fp8(kn, kn, np.int32([0]), np.int32([0]), np.int32([0, 2]), k, v, ks, vs, bt)
+    assert ks[0, 0] == np.float32(2.0 ** -8)                          # 1.75 / 448
+    assert np.array_equal(k[0, 0, 0, :127], np.arange(127, dtype=np.uint8))          # codes are stored as themselves
+    assert np.array_equal(k[0, 0, 1, :127], np.arange(127, dtype=np.uint8) | 0x80)
+    grow = np.zeros((1, 1, d), np.float32)
+    grow[0, 0, 5] = -new_amax
+    gn = f32_to_bf16_bits(grow)
+    oracle.kv_append_fp8(gn, gn, np.int32([0]), np.int32([2]), np.int32([0, 1]), k, v, ks, vs, bt)
+    assert ks[0, 0] == np.float32(2.0 ** -8 / ratio) and vs[0, 0] == ks[0, 0]
+    expect = np.array([want[(ratio, c)] for c in range(127)], dtype=np.uint8)
+    for pool in (k, v):
+        assert np.array_equal(pool[0, 0, 0, :127], expect)
+        assert np.array_equal(pool[0, 0, 1, :127], expect | 0x80)
+        assert pool[0, 0, 2, 5] == 0xFE and pool[0, 0, 2, 6] == 0     # the new row: -448 in units of the new scale
+
+
+def test_growth_by_arbitrary_ratios_lands_on_a_nearest_code():
+    """Random tiles, scales growing by 1.01x .. 300x: every old value goes to a nearest code of the new grid."""
+    rng = np.random.default_rng(11)
+    Hkv, d = 2, 128
+    bt = np.int32([[0]])
+    for factor in (1.01, 1.3, 2.0, 3.7, 17.0, 300.0):
+        k, v, ks, vs = empty_pool(1, Hkv, d)
+        first = rows(rng, 9, Hkv, d, 0.7)
+        oracle.kv_append_fp8(first, first, np.int32([0]), np.int32([0]), np.int32([0, 9]), k, v, ks, vs, bt)
+        k1, ks1 = k.copy(), ks.copy()
+        second = np.zeros((1, Hkv, d), np.float32)
+        second[0, :, 3] = ks1[0] * 448.0 * factor
+        sn = f32_to_bf16_bits(second)
+        oracle.kv_append_fp8(sn, sn, np.int32([0]), np.int32([9]), np.int32([0, 1]), k, v, ks, vs, bt)
+        for g in range(Hkv):
+            assert ks[0, g] > ks1[0, g]
+            assert_reencoded_to_a_nearest_code(k1[0, g, :9], ks1[0, g], k[0, g, :9], ks[0, g])
+
+
 @pytest.mark.parametrize("grow", [False, True])
 def test_append_into_a_partly_filled_page(grow):
     rng = np.random.default_rng(2 + grow)
@@ -104,10 +179,7 @@ def test_append_into_a_partly_filled_page(grow):
             assert (after[1, g, 8:] == 0x7F).all()  # slots past the range keep their bits
             if grow:
                 assert sa[1, g] > sb[1, g]
-                # old tokens survive the re-quantisation within half a step of the new grid
-                old_vals = table()[before[1, g, :5]] * sb[1, g]
-                new_vals = table()[after[1, g, :5]] * sa[1, g]
-                assert np.abs(new_vals - old_vals).max() <= sa[1, g] * 16.0 + 1e-12  # half of the top binade's step (32)
+                assert_reencoded_to_a_nearest_code(before[1, g, :5], sb[1, g], after[1, g, :5], sa[1, g])
             else:
                 assert sa[1, g] == sb[1, g] and np.array_equal(after[1, g, :5], before[1, g, :5])
     assert np.array_equal(k[0], k1[0]) and np.array_equal(v[0], v1[0])  # the other page
