@@ -259,7 +259,7 @@ def main():
     wl = workloads.make_config(cfg, append=do_append)
     pool_bytes = 2 * wl.k_pages.nbytes
     npools = args.pools or (4 if pool_bytes < SMALL_POOL_BYTES else 1)
-    dw = DeviceWorkload(wl, chunk_tokens=args.chunk, balance_for_batch=True)
+    dw = DeviceWorkload(wl, chunk_tokens=args.chunk, balance_for_batch=wl.group_start is not None and not args.no_prefix)
     pools = [(dw.k_pages, dw.v_pages, dw.k_scales, dw.v_scales)]
     for i in range(1, npools):
         k, v, ks, vs = draw_extra_pool(wl, seed=1000 + i)
@@ -329,10 +329,10 @@ def main():
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
     nprobe = max(10, min(args.steps, 50))
     for i in range(5):
-        probe_read(dw.shape, pools[i % npools][0], pools[i % npools][1], dw.block_table, dw.context_lens, sink, stream)
+        probe_read(dw.shape, *pools[i % npools], dw.block_table, dw.context_lens, sink, stream)
     ev[0].record(stream)
     for i in range(nprobe):
-        probe_read(dw.shape, pools[i % npools][0], pools[i % npools][1], dw.block_table, dw.context_lens, sink, stream)
+        probe_read(dw.shape, *pools[i % npools], dw.block_table, dw.context_lens, sink, stream)
     ev[1].record(stream)
     torch.cuda.synchronize()
     probe_ms = ev[0].elapsed_time(ev[1]) / nprobe

@@ -189,10 +189,18 @@ int kv_copy_pages(const sd_shape *shape, const int32_t *src_pages, const int32_t
  * fp32 from bf16 operands; softmax weights are rounded to bf16 before the
  * weighted sum and normalised by the sum of the rounded weights.
  *
- * Runs two kernels: a split-K pass over chunks of `chunk_tokens` tokens that
- * streams every K/V page once per (sequence, KV head) and leaves per-chunk
- * (max, sum, weighted sum) in `workspace`, and a merge pass that writes `out`.
- * Results do not depend on the physical placement of pages.
+ * Runs two kernels (batches of up to 4096 sequences).  Range pass: per KV head
+ * the batch's 32-token tiles form one line, sequence after sequence; the line
+ * is cut into as many equal ranges as the device runs waves at once and each
+ * wave streams one range, so every K/V page leaves HBM once per (sequence, KV
+ * head) and all waves carry the same load whatever the mix of lengths.  A wave
+ * that holds a whole sequence writes its `out` rows itself; of a sequence cut
+ * across ranges each wave leaves (max, sum, weighted sum) in `workspace`.  Merge
+ * pass: combines the parts of every cut sequence in range order (results are
+ * reproducible bit for bit).  shape->chunk_tokens, when non-zero, is the least
+ * number of tokens a range holds.  Larger batches take the chunked passes of
+ * paged_decode_attention_prefix.  Results do not depend on the physical
+ * placement of pages.
  *
  *   k_scales, v_scales  NULL for SD_BF16
  *   workspace           >= sd_workspace_bytes(shape) bytes, contents ignored on entry
@@ -209,9 +217,9 @@ int paged_decode_attention(const sd_shape *shape, const void *q,
  * argument, for callers that cannot allocate device memory: code running under
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
  *
- * The split pass's partials go to an array of SD_STATIC_SCRATCH_BYTES bytes that
- * is part of the library itself (every GPU the library runs on holds its own
- * copy until the process ends).  The call allocates and frees nothing; the
+ * The partial results of sequences that are cut across waves go to an array of
+ * SD_STATIC_SCRATCH_BYTES bytes that is part of the library itself (every GPU
+ * the library runs on holds its own copy until the process ends).  The call allocates and frees nothing; the
  * first call on a device looks the array's address up (current device = the
  * device of `stream`), so make that first call outside graph capture.  Same
  * kernels, same arithmetic and bit-identical results as paged_decode_attention
@@ -219,11 +227,11 @@ int paged_decode_attention(const sd_shape *shape, const void *q,
  *
  * Returns SD_EWORKSPACE, before anything is enqueued, when the shape needs more
  * scratch than the array holds (sd_workspace_bytes(shape) >
- * SD_STATIC_SCRATCH_BYTES; shapes whose every sequence is one chunk need none).
+ * SD_STATIC_SCRATCH_BYTES).
  * All calls on one GPU share the one array: calls that overlap in time on the
  * same GPU (different streams, different host threads) race; order them.
  */
-#define SD_STATIC_SCRATCH_BYTES (32u << 20)
+#define SD_STATIC_SCRATCH_BYTES (48u << 20)
 int paged_decode_attention_static(const sd_shape *shape, const void *q,
                                   const void *k_pages, const void *v_pages,
                                   const float *k_scales, const float *v_scales,
@@ -396,14 +404,16 @@ int paged_decode_attention_timed(const sd_shape *shape, const void *q,
                                  sd_timer *timer);
 
 /*
- * sd_probe_read -- streams exactly the K and V bytes paged_decode_attention
- * must read (same block-table walk, same chunking, 16-byte loads), does no
- * arithmetic on them beyond an XOR fold, and writes one word per workgroup to
- * `sink` (u32 [sd_probe_sink_words(shape)], device).  Its duration is the
- * bandwidth ceiling of this access pattern on the machine at hand.
+ * sd_probe_read -- the kernel of paged_decode_attention with the arithmetic
+ * taken out: same grid, same ranges, same loads of every K and V byte (and fp8
+ * scale) the decode step must read, folded with XOR; one word per wave goes to
+ * `sink` (u32 [sd_probe_sink_words(shape)], device).  Its duration is what the
+ * memory system delivers for this walk on the machine at hand, i.e. the ceiling
+ * for the decode step.  Batches above 4096 sequences: SD_EUNSUPPORTED.
  */
 size_t sd_probe_sink_words(const sd_shape *shape);
 int sd_probe_read(const sd_shape *shape, const void *k_pages, const void *v_pages,
+                  const float *k_scales, const float *v_scales,
                   const int32_t *block_table, const int32_t *context_lens,
                   uint32_t *sink, void *stream);
 

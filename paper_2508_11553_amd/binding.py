@@ -93,7 +93,7 @@ def load():
     L.sd_probe_sink_words.restype = sz
     L.sd_probe_sink_words.argtypes = [sp]
     L.sd_probe_read.restype = ctypes.c_int
-    L.sd_probe_read.argtypes = [sp, vp, vp, vp, vp, vp, vp]
+    L.sd_probe_read.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp]
     _lib = L
     return L
 
@@ -254,9 +254,9 @@ def validate_tables(shape: Shape, block_table, context_lens, report, stream=None
     _check(rc, "sd_validate_tables")
 
 
-def probe_read(shape: Shape, k_pages, v_pages, block_table, context_lens, sink, stream=None):
-    rc = load().sd_probe_read(ctypes.byref(shape), _ptr(k_pages), _ptr(v_pages), _ptr(block_table),
-                              _ptr(context_lens), _ptr(sink), _stream(stream))
+def probe_read(shape: Shape, k_pages, v_pages, k_scales, v_scales, block_table, context_lens, sink, stream=None):
+    rc = load().sd_probe_read(ctypes.byref(shape), _ptr(k_pages), _ptr(v_pages), _ptr(k_scales), _ptr(v_scales),
+                              _ptr(block_table), _ptr(context_lens), _ptr(sink), _stream(stream))
     _check(rc, "sd_probe_read")
 
 

@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libseamdecode.so")
-SOURCES = ["api.hip", "attn_split.hip", "attn_merge.hip", "attn_prefill.hip", "kv_append.hip", "probe.hip", "prefix_tree.cpp"]
+SOURCES = ["api.hip", "attn_split.hip", "attn_merge.hip", "attn_prefill.hip", "kv_append.hip", "validate.hip", "attn_range.hip", "prefix_tree.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall",

@@ -128,6 +128,56 @@ int static_scratch(void **ptr)
     return SD_OK;
 }
 
+// Workspace of the range pass (batches without shared prefixes): the sequences' tile offsets for
+// the merge pass, then the waves' partial slots.
+constexpr int kMaxRangeWorkgroups = 512;          // two per compute unit on a 256-CU device
+
+struct RangeLayout {
+    int rblocks;                 // workgroups per virtual head
+    size_t slots;                // partial slots: two per wave
+    size_t seq_off, m_off, l_off, acc_off, total;
+};
+
+// `workgroups`: how many the device takes at once (2 per compute unit), at most kMaxRangeWorkgroups.
+RangeLayout range_layout(const sd_shape *s, int workgroups)
+{
+    const int G = s->num_q_heads / s->num_kv_heads;
+    const int Hv = s->num_kv_heads * sd::head_blocks(G);
+    RangeLayout r;
+    r.rblocks = std::max(1, std::min(workgroups, kMaxRangeWorkgroups) / Hv);
+    r.slots = (size_t)2 * sd::kWaves * r.rblocks * Hv;
+    r.seq_off = (((size_t)s->batch + 1) * 4 + 255) & ~(size_t)255;
+    r.m_off = r.seq_off + ((r.slots / 2 * 16 + 255) & ~(size_t)255);
+    r.l_off = r.m_off + r.slots * sd::kMaxGroup * 4;
+    r.acc_off = r.l_off + r.slots * sd::kMaxGroup * 4;
+    r.total = r.acc_off + r.slots * (size_t)std::min(G, sd::kMaxGroup) * (size_t)s->head_dim * 4;
+    return r;
+}
+
+// The range pass serves every batch whose tile offsets fit a workgroup's LDS; larger batches take
+// the chunked split + merge passes.
+bool range_pass_fits(const sd_shape *s) { return s->batch <= sd::kMaxRangeBatch; }
+
+// Workgroups the current device runs at once with two per compute unit; asked once per device.
+std::atomic<int> g_workgroups[kMaxDevices];
+int device_workgroups(int *out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev < 0 || dev >= kMaxDevices) return SD_EUNSUPPORTED;
+    int w = g_workgroups[dev].load(std::memory_order_acquire);
+    if (!w) {
+        int cus = 0;
+        e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess || cus <= 0) return hip_fail(e == hipSuccess ? hipErrorInvalidDevice : e);
+        w = 2 * cus;
+        g_workgroups[dev].store(w, std::memory_order_release);
+    }
+    *out = w;
+    return SD_OK;
+}
+
 }  // namespace
 
 struct sd_timer {
@@ -172,7 +222,9 @@ size_t sd_workspace_bytes(const sd_shape *shape)
 {
     if (check_shape(shape)) return 0;
     const int chunk = pick_chunk(shape);
-    const size_t t = ws_layout(shape, num_chunks(shape, chunk)).total;
+    size_t t = ws_layout(shape, num_chunks(shape, chunk)).total;
+    // the range pass, sized for the largest grid it ever uses
+    if (range_pass_fits(shape)) t = std::max(t, range_layout(shape, kMaxRangeWorkgroups).total);
     return t ? t : 256;
 }
 
@@ -292,19 +344,86 @@ int attend_impl(const sd_shape *shape, const void *q, const void *k_pages, const
     const int chunk = pick_chunk(shape);
     const int S = num_chunks(shape, chunk);
     const WsLayout w = ws_layout(shape, S);
-    // every sequence fits one chunk and nothing is shared: the split pass normalises and writes `out` itself
     const int shared_chunks = num_groups > 0 ? (max_shared_len + chunk - 1) / chunk : 0;
+    // every sequence fits one chunk and nothing is shared: one workgroup per (sequence, KV head) is balanced
+    // as it is; the split pass normalises and writes `out` itself, no partials, no merge pass
     const bool direct = !shared_chunks && shape->max_context_len <= chunk;
+    // otherwise, when nothing is shared: the range pass and its merge pass
+    const bool ranged = !shared_chunks && !direct && range_pass_fits(shape);
+    if (timer && timer->calls >= timer->max_calls) return SD_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipEvent_t none[4] = {nullptr, nullptr, nullptr, nullptr};
+    hipEvent_t *ev = timer ? &timer->ev[(size_t)timer->calls * 4] : none;
+    hipError_t e;
+
+    if (ranged) {
+        // workspace checks use the largest layout (what sd_workspace_bytes reports), whatever the device
+        if (own_scratch ? range_layout(shape, kMaxRangeWorkgroups).total > kStaticScratchBytes
+                        : workspace_bytes < sd_workspace_bytes(shape))
+            return SD_EWORKSPACE;
+        int workgroups = 0;
+        int rc2 = device_workgroups(&workgroups);
+        if (rc2) return rc2;
+        if (own_scratch && (rc2 = static_scratch(&workspace))) return rc2;
+        const RangeLayout rl = range_layout(shape, workgroups);
+        char *ws = static_cast<char *>(workspace);
+        sd::RangeArgs ra;
+        ra.q = static_cast<const uint16_t *>(q);
+        ra.k_pages = k_pages;
+        ra.v_pages = v_pages;
+        ra.k_scales = k_scales;
+        ra.v_scales = v_scales;
+        ra.block_table = block_table;
+        ra.context_lens = context_lens;
+        ra.out = out;
+        ra.tile_off = reinterpret_cast<int32_t *>(ws);
+        ra.merge_rec = reinterpret_cast<int4 *>(ws + rl.seq_off);
+        ra.ws_m = reinterpret_cast<float *>(ws + rl.m_off);
+        ra.ws_l = reinterpret_cast<float *>(ws + rl.l_off);
+        ra.ws_acc = reinterpret_cast<float *>(ws + rl.acc_off);
+        ra.sink = nullptr;
+        ra.scale_log2e = scale * 1.4426950408889634f;
+        ra.B = shape->batch;
+        ra.Hq = shape->num_q_heads;
+        ra.Hkv = shape->num_kv_heads;
+        ra.G = shape->num_q_heads / shape->num_kv_heads;
+        ra.HB = sd::head_blocks(ra.G);
+        ra.max_blocks = shape->max_blocks_per_seq;
+        ra.max_context_len = shape->max_context_len;
+        ra.ranges = sd::kWaves * rl.rblocks;
+        ra.min_tiles = std::max(1, shape->chunk_tokens / sd::kTileTokens);
+        ra.rows_stride = std::min(ra.G, sd::kMaxGroup);
+        const unsigned grid = (unsigned)rl.rblocks * (unsigned)(ra.Hkv * ra.HB);
+        if ((e = sd::launch_range(ra, shape->head_dim, shape->kv_dtype, grid, false, st, ev[0], ev[1])) != hipSuccess)
+            return e == hipErrorNotSupported ? SD_EUNSUPPORTED : hip_fail(e);
+        sd::RangeMergeArgs rm;
+        rm.tile_off = ra.tile_off;
+        rm.merge_rec = ra.merge_rec;
+        rm.by_sequence = ra.B <= ra.ranges;
+        rm.ws_m = ra.ws_m;
+        rm.ws_l = ra.ws_l;
+        rm.ws_acc = ra.ws_acc;
+        rm.out = out;
+        rm.B = ra.B;
+        rm.Hq = ra.Hq;
+        rm.Hkv = ra.Hkv;
+        rm.G = ra.G;
+        rm.HB = ra.HB;
+        rm.ranges = ra.ranges;
+        rm.min_tiles = ra.min_tiles;
+        rm.rows_stride = ra.rows_stride;
+        if ((e = sd::launch_range_merge(rm, shape->head_dim, st, ev[2], ev[3])) != hipSuccess) return hip_fail(e);
+        if (timer) timer->calls++;
+        return SD_OK;
+    }
+
     if (own_scratch) {
         if (!direct && w.total > kStaticScratchBytes) return SD_EWORKSPACE;
         const int src = static_scratch(&workspace);
         if (src) return src;
-    } else if (workspace_bytes < w.total) {
+    } else if (workspace_bytes < sd_workspace_bytes(shape)) {
         return SD_EWORKSPACE;
     }
-    if (timer && timer->calls >= timer->max_calls) return SD_EINVAL;
-
-    hipStream_t st = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(workspace);
     sd::SplitArgs sa;
     sa.q = static_cast<const uint16_t *>(q);
@@ -359,9 +478,6 @@ int attend_impl(const sd_shape *shape, const void *q, const void *k_pages, const
     ma.shared_len = sa.shared_len;
     ma.max_shared_len = max_shared_len;
 
-    hipEvent_t none[4] = {nullptr, nullptr, nullptr, nullptr};
-    hipEvent_t *ev = timer ? &timer->ev[(size_t)timer->calls * 4] : none;
-    hipError_t e;
     if ((e = sd::launch_split(sa, shape->head_dim, shape->kv_dtype, st, ev[0], ev[1])) != hipSuccess)
         return e == hipErrorNotSupported ? SD_EUNSUPPORTED : hip_fail(e);
     if (direct) {
@@ -542,33 +658,45 @@ int sd_validate_tables(const sd_shape *shape, const int32_t *block_table, const 
 
 size_t sd_probe_sink_words(const sd_shape *shape)
 {
-    if (check_shape(shape)) return 0;
-    const size_t n = (size_t)num_chunks(shape, pick_chunk(shape)) * (size_t)shape->batch * (size_t)shape->num_kv_heads;
-    return n ? n : 1;
+    if (check_shape(shape) || !range_pass_fits(shape)) return 0;
+    return range_layout(shape, kMaxRangeWorkgroups).slots / 2;  // one word per wave
 }
 
-int sd_probe_read(const sd_shape *shape, const void *k_pages, const void *v_pages, const int32_t *block_table,
-                  const int32_t *context_lens, uint32_t *sink, void *stream)
+int sd_probe_read(const sd_shape *shape, const void *k_pages, const void *v_pages, const float *k_scales,
+                  const float *v_scales, const int32_t *block_table, const int32_t *context_lens, uint32_t *sink,
+                  void *stream)
 {
     const int rc = check_shape(shape);
     if (rc) return rc;
+    if (!range_pass_fits(shape)) return SD_EUNSUPPORTED;
     if (shape->batch == 0) return SD_OK;
     if (bad_ptr(k_pages) || bad_ptr(v_pages) || bad_ptr(block_table) || bad_ptr(context_lens) || bad_ptr(sink))
         return SD_EINVAL;
-    sd::ProbeArgs a;
-    a.k_pages = k_pages;
-    a.v_pages = v_pages;
-    a.block_table = block_table;
-    a.context_lens = context_lens;
-    a.sink = sink;
-    a.B = shape->batch;
-    a.Hkv = shape->num_kv_heads;
-    a.max_blocks = shape->max_blocks_per_seq;
-    a.chunk_tokens = pick_chunk(shape);
-    a.S = num_chunks(shape, a.chunk_tokens);
-    a.max_context_len = shape->max_context_len;
-    a.tile_bytes = sd::kPage * shape->head_dim * (shape->kv_dtype == SD_BF16 ? 2 : 1);
-    const hipError_t e = sd::launch_probe(a, static_cast<hipStream_t>(stream));
+    if (shape->kv_dtype == SD_FP8_E4M3 && (bad_ptr(k_scales) || bad_ptr(v_scales))) return SD_EINVAL;
+    int workgroups = 0;
+    const int rc2 = device_workgroups(&workgroups);
+    if (rc2) return rc2;
+    const RangeLayout rl = range_layout(shape, workgroups);
+    sd::RangeArgs ra = {};
+    ra.k_pages = k_pages;
+    ra.v_pages = v_pages;
+    ra.k_scales = k_scales;
+    ra.v_scales = v_scales;
+    ra.block_table = block_table;
+    ra.context_lens = context_lens;
+    ra.sink = sink;
+    ra.B = shape->batch;
+    ra.Hq = shape->num_q_heads;
+    ra.Hkv = shape->num_kv_heads;
+    ra.G = shape->num_q_heads / shape->num_kv_heads;
+    ra.HB = sd::head_blocks(ra.G);
+    ra.max_blocks = shape->max_blocks_per_seq;
+    ra.max_context_len = shape->max_context_len;
+    ra.ranges = sd::kWaves * rl.rblocks;
+    ra.min_tiles = std::max(1, shape->chunk_tokens / sd::kTileTokens);
+    ra.rows_stride = std::min(ra.G, sd::kMaxGroup);
+    const unsigned grid = (unsigned)rl.rblocks * (unsigned)(ra.Hkv * ra.HB);
+    const hipError_t e = sd::launch_range(ra, shape->head_dim, shape->kv_dtype, grid, true, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SD_OK : hip_fail(e);
 }
 

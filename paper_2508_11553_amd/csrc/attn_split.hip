@@ -31,68 +31,6 @@
 
 namespace sd {
 
-// Streams the tiles first, first+stride, ... of the chunk [t0, t1) through this
-// wave.  Loads for tile i+1 are issued before tile i is consumed, and the page
-// ids of tile i+2 are fetched (scalar loads) one step earlier still.
-// Everything inside the loop is unconditional so that the wait counters stay
-// exact; a tile's missing second page re-reads the first (its tokens are
-// masked by position).  `bt` points at the table entry of the chunk's first page.
-template <class P, bool STREAM>
-SD_DEV void stream_tiles(const SplitArgs &a, const int32_t *bt, int g, int t0, int t1, int first, int stride,
-                         const u32x4 (&qop)[P::kDim / 32], typename P::State &st, char *scratch, int lane)
-{
-    const int ntiles = (t1 - t0 + kTileTokens - 1) / kTileTokens;
-    const int nt = ntiles > first ? (ntiles - first + stride - 1) / stride : 0;
-    if (nt <= 0) return;
-    const int last_page = (t1 - t0 + kPage - 1) / kPage - 1;
-    const int64_t page_bytes = (int64_t)P::kTileBytes * a.Hkv;
-    const char *kbase = static_cast<const char *>(a.k_pages) + g * P::kTileBytes;
-    const char *vbase = static_cast<const char *>(a.v_pages) + g * P::kTileBytes;
-    auto page_ids = [&](int i, int &pa, int &pb) {
-        const int ti = first + stride * min(i, nt - 1);
-        pa = bt[2 * ti];
-        pb = bt[min(2 * ti + 1, last_page)];
-    };
-    auto issue = [&](typename P::Tile &r, int pa, int pb) {
-        P::template load_page<STREAM>(r, 0, kbase + pa * page_bytes, vbase + pa * page_bytes, a.k_scales, a.v_scales,
-                     (int64_t)pa * a.Hkv + g, lane);
-        P::template load_page<STREAM>(r, 1, kbase + pb * page_bytes, vbase + pb * page_bytes, a.k_scales, a.v_scales,
-                     (int64_t)pb * a.Hkv + g, lane);
-    };
-    // K takes a round trip through this wave's own LDS scratch; only the owning
-    // wave touches it, so wave-level fences suffice
-    auto consume = [&](typename P::Tile &r, int i) {
-        u32x4 ka[P::kDim / 32], kb[P::kDim / 32];
-        P::k_store(r, scratch, lane);
-        wave_lds_fence();
-        P::k_fetch(scratch, lane, ka, kb);
-        wave_lds_fence();
-        const int tok0 = t0 + (first + stride * i) * kTileTokens;
-        P::attend(ka, kb, r, qop, st, a.scale_log2e, tok0, t1, lane);
-    };
-    typename P::Tile ra, rb;
-    int pa, pb;
-    page_ids(0, pa, pb);
-    issue(ra, pa, pb);
-    page_ids(1, pa, pb);
-    int i = 0;
-    for (; i + 2 < nt; i += 2) {
-        issue(rb, pa, pb);
-        page_ids(i + 2, pa, pb);
-        consume(ra, i);
-        issue(ra, pa, pb);
-        page_ids(i + 3, pa, pb);
-        consume(rb, i + 1);
-    }
-    if (i + 1 < nt) {
-        issue(rb, pa, pb);
-        consume(ra, i);
-        consume(rb, i + 1);
-    } else {
-        consume(ra, i);
-    }
-}
-
 // Tokens of sequence b that its group shares: whole pages, never more than the
 // sequence has and never more than the host-side bound.
 SD_DEV int shared_tokens(const SplitArgs &a, int b)

@@ -211,6 +211,22 @@ struct Bf16Path {
                 r.v[pg][h][j] = kv_load<STREAM>(reinterpret_cast<const u32x2 *>(vl + j * (D * 2) + h * 128));
     }
 
+    // XOR of everything a tile's loads brought in (read probe)
+    SD_DEV static u32x4 fold(const Tile &r)
+    {
+        u32x4 f = {0, 0, 0, 0};
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg) {
+#pragma unroll
+            for (int j = 0; j < D / 32; ++j) f ^= r.k[pg][j];
+#pragma unroll
+            for (int h = 0; h < D / 64; ++h)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) f ^= u32x4{r.v[pg][h][j][0], r.v[pg][h][j][1], 0, 0};
+        }
+        return f;
+    }
+
     // K tiles go through LDS: written as they lie in memory, read back one row
     // per lane.  Piece c of row r sits at piece index c ^ r so that the writes
     // (16 lanes = one row) and the reads (16 lanes = one piece column over 16
@@ -418,6 +434,19 @@ struct Fp8Path {
         r.vs[pg] = vs[si];
     }
 
+    SD_DEV static u32x4 fold(const Tile &r)
+    {
+        u32x4 f = {__builtin_bit_cast(unsigned, r.ks[0]) ^ __builtin_bit_cast(unsigned, r.ks[1]),
+                   __builtin_bit_cast(unsigned, r.vs[0]) ^ __builtin_bit_cast(unsigned, r.vs[1]), 0, 0};
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg) {
+            f ^= r.k[pg][0] ^ r.k[pg][1];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) f ^= u32x4{r.v[pg][j][0], r.v[pg][j][1], 0, 0};
+        }
+        return f;
+    }
+
     // Rows are 128 bytes = 8 pieces; piece c of row r sits at c ^ (r >> 1), and
     // odd rows start half a bank cycle later, so 16 lanes never share a bank.
     SD_DEV static void k_store(const Tile &r, char *kslot, int lane)
@@ -596,5 +625,83 @@ struct Lds {
     static constexpr int kSharedBytes = kWaves * kSlotBytes;
     static constexpr int kBytes = kPlainBytes > kSharedBytes ? kPlainBytes : kSharedBytes;
 };
+
+// Walks the tiles first, first+stride, ... of the token range [t0, t1) of one
+// sequence: loads for tile i+1 are issued before tile i is handed to
+// `consume(tile, i)`, and the page ids of tile i+2 are fetched (scalar loads)
+// one step earlier still.  Everything inside the loop is unconditional so that
+// the wait counters stay exact; a tile's missing second page re-reads the first
+// (its tokens are masked by position).  `bt` points at the table entry of the
+// range's first page; t0 is a multiple of 32.  `a` supplies k_pages, v_pages,
+// k_scales, v_scales and Hkv.
+template <class P, bool STREAM, class Args, class Consume>
+SD_DEV void walk_tiles(const Args &a, const int32_t *bt, int g, int t0, int t1, int first, int stride, int lane,
+                       Consume consume)
+{
+    const int ntiles = (t1 - t0 + kTileTokens - 1) / kTileTokens;
+    const int nt = ntiles > first ? (ntiles - first + stride - 1) / stride : 0;
+    if (nt <= 0) return;
+    const int last_page = (t1 - t0 + kPage - 1) / kPage - 1;
+    const int64_t page_bytes = (int64_t)P::kTileBytes * a.Hkv;
+    const char *kbase = static_cast<const char *>(a.k_pages) + g * P::kTileBytes;
+    const char *vbase = static_cast<const char *>(a.v_pages) + g * P::kTileBytes;
+    auto page_ids = [&](int i, int &pa, int &pb) {
+        const int ti = first + stride * min(i, nt - 1);
+        pa = bt[2 * ti];
+        pb = bt[min(2 * ti + 1, last_page)];
+    };
+    auto issue = [&](typename P::Tile &r, int pa, int pb) {
+        P::template load_page<STREAM>(r, 0, kbase + pa * page_bytes, vbase + pa * page_bytes, a.k_scales, a.v_scales,
+                     (int64_t)pa * a.Hkv + g, lane);
+        P::template load_page<STREAM>(r, 1, kbase + pb * page_bytes, vbase + pb * page_bytes, a.k_scales, a.v_scales,
+                     (int64_t)pb * a.Hkv + g, lane);
+    };
+    typename P::Tile ra, rb;
+    int pa, pb;
+    page_ids(0, pa, pb);
+    issue(ra, pa, pb);
+    page_ids(1, pa, pb);
+    int i = 0;
+    for (; i + 2 < nt; i += 2) {
+        issue(rb, pa, pb);
+        page_ids(i + 2, pa, pb);
+        consume(ra, i);
+        issue(ra, pa, pb);
+        page_ids(i + 3, pa, pb);
+        consume(rb, i + 1);
+    }
+    if (i + 1 < nt) {
+        issue(rb, pa, pb);
+        consume(ra, i);
+        consume(rb, i + 1);
+    } else {
+        consume(ra, i);
+    }
+}
+
+// The attention walk: every tile goes through the wave's own tile step.  K takes
+// a round trip through this wave's LDS scratch; only the owning wave touches it,
+// so wave-level fences suffice.
+template <class P, bool STREAM, class Args>
+SD_DEV void stream_tiles(const Args &a, const int32_t *bt, int g, int t0, int t1, int first, int stride,
+                         const u32x4 (&qop)[P::kDim / 32], typename P::State &st, char *scratch, int lane)
+{
+    walk_tiles<P, STREAM>(a, bt, g, t0, t1, first, stride, lane, [&](typename P::Tile &r, int i) {
+        u32x4 ka[P::kDim / 32], kb[P::kDim / 32];
+        P::k_store(r, scratch, lane);
+        wave_lds_fence();
+        P::k_fetch(scratch, lane, ka, kb);
+        wave_lds_fence();
+        const int tok0 = t0 + (first + stride * i) * kTileTokens;
+        P::attend(ka, kb, r, qop, st, a.scale_log2e, tok0, t1, lane);
+    });
+}
+
+// The same walk with the same loads and no arithmetic beyond an XOR fold of what arrived.
+template <class P, class Args>
+SD_DEV void probe_tiles(const Args &a, const int32_t *bt, int g, int t0, int t1, u32x4 &fold, int lane)
+{
+    walk_tiles<P, true>(a, bt, g, t0, t1, 0, 1, lane, [&](typename P::Tile &r, int) { fold ^= P::fold(r); });
+}
 
 }  // namespace sd

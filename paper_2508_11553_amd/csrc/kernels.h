@@ -70,6 +70,37 @@ struct SplitArgs {
     int32_t grid_chunks;         // chunk slots the plain part of the grid spans (S, or S-1 without groups)
 };
 
+// Arguments of the range pass (batches without shared prefixes).  Per (virtual) KV head the batch is one line of 32-token tiles (sequence after
+// sequence); the line is cut into `ranges` equal ranges and each wave walks one of them.
+constexpr int kMaxRangeBatch = 4096;  // sequences whose tile offsets fit the workgroup's LDS
+struct RangeArgs {
+    const uint16_t *q;
+    const void *k_pages, *v_pages;
+    const float *k_scales, *v_scales;
+    const int32_t *block_table, *context_lens;
+    float *out;                  // [B][Hq][D]
+    int32_t *tile_off;           // [B + 1] written for the merge pass: tiles of the sequences before b
+    int4 *merge_rec;             // [ranges][Hv] written for the merge pass: {b, tile_off[b], tile_off[b+1], T} of the cut
+                                 // sequence whose first part the range holds, or b = -1
+    float *ws_m, *ws_l;          // [slots][16]   a wave's partial rows: running max (log2 domain), weight sum
+    float *ws_acc;               // [slots][rows_stride][D]   weighted V sums; slot = (range * Hv + head) * 2 + which
+    uint32_t *sink;              // probe launches only: one word per wave
+    float scale_log2e;           // scale * log2(e)
+    int32_t B, Hq, Hkv, G, HB, max_blocks, max_context_len;
+    int32_t ranges;              // ranges per virtual head: 4 x (grid / (Hkv * HB))
+    int32_t min_tiles;           // a range holds at least this many tiles (unless the batch has fewer)
+    int32_t rows_stride;         // rows per partial slot: min(G, 16)
+};
+
+struct RangeMergeArgs {
+    const int32_t *tile_off;
+    const int4 *merge_rec;
+    const float *ws_m, *ws_l, *ws_acc;
+    float *out;
+    int32_t B, Hq, Hkv, G, HB, ranges, min_tiles, rows_stride;
+    int32_t by_sequence;         // items are (sequence, head block) instead of (range, head block)
+};
+
 struct MergeArgs {
     const float *ws_m, *ws_l, *ws_acc;
     const int32_t *context_lens;
@@ -128,20 +159,16 @@ struct ValidateArgs {
     int32_t B, max_blocks, num_pages, max_context_len;
 };
 
-struct ProbeArgs {
-    const void *k_pages, *v_pages;
-    const int32_t *block_table, *context_lens;
-    uint32_t *sink;
-    int32_t B, Hkv, max_blocks, S, chunk_tokens, max_context_len;
-    int32_t tile_bytes;          // bytes of one (page, head) tile: 16 * D * elem
-};
-
 // Launchers: enqueue on `stream`, return the hipError_t of the launch.  When
 // `start`/`stop` are given they are bound to the kernel's own begin and end
 // timestamps (hipExtLaunchKernelGGL), so their elapsed time is the kernel's
 // duration without launch latency.
 hipError_t launch_split(const SplitArgs &a, int head_dim, int kv_dtype, hipStream_t stream,
                         hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
+hipError_t launch_range(const RangeArgs &a, int head_dim, int kv_dtype, unsigned grid, bool probe, hipStream_t stream,
+                        hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
+hipError_t launch_range_merge(const RangeMergeArgs &a, int head_dim, hipStream_t stream,
+                              hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
 hipError_t launch_merge(const MergeArgs &a, int head_dim, hipStream_t stream,
                         hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
 hipError_t launch_prefill(const PrefillArgs &a, int head_dim, int kv_dtype, hipStream_t stream,
@@ -150,6 +177,5 @@ hipError_t launch_append(const AppendArgs &a, int head_dim, hipStream_t stream);
 hipError_t launch_append_fp8(const AppendFp8Args &a, hipStream_t stream);
 hipError_t launch_copy_pages(const CopyPagesArgs &a, hipStream_t stream);
 hipError_t launch_validate(const ValidateArgs &a, hipStream_t stream);
-hipError_t launch_probe(const ProbeArgs &a, hipStream_t stream);
 
 }  // namespace sd

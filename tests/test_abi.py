@@ -57,10 +57,14 @@ def test_shape_struct_matches_header():
 def test_workspace_size_is_positive_and_monotone(lib):
     a = sd.workspace_bytes(good_shape())
     b = sd.workspace_bytes(good_shape(max_context_len=512, max_blocks_per_seq=64, batch=8))
-    assert 0 < a < b
+    assert 0 < a <= b   # the one-launch path's scratch depends on the machine's size, not on the batch
+    c = sd.workspace_bytes(good_shape(head_dim=128))
+    assert c > a
     # one chunk's worth of (m, l, acc) per row at least
     assert a >= 4 * 8 * (64 + 2) * 4
-    assert sd.workspace_bytes(good_shape(chunk_tokens=128)) > a
+    assert sd.workspace_bytes(good_shape(chunk_tokens=128)) >= a
+    # two partial slots per wave of the largest grid (512 workgroups), 4 query heads each
+    assert a >= 2 * 4 * 512 * 4 * (64 + 2) * 4
 
 
 @pytest.mark.parametrize("over,code", [
@@ -153,9 +157,9 @@ def test_empty_calls_are_noops(lib):
 
 def test_shapes_beyond_the_scratch_array_are_refused(lib):
     """Rejected on the host before any HIP call; nothing is enqueued."""
-    s = sd.Shape(batch=4096, num_q_heads=64, num_kv_heads=8, head_dim=128, page_size=16, num_pages=16,
+    s = sd.Shape(batch=8192, num_q_heads=64, num_kv_heads=8, head_dim=128, page_size=16, num_pages=16,
                  max_blocks_per_seq=512, kv_dtype=sd.SD_BF16, max_context_len=8192, chunk_tokens=1024)
-    assert sd.workspace_bytes(s) > 32 << 20
+    assert sd.workspace_bytes(s) > 48 << 20
     rc = sd.load().paged_decode_attention_static(ctypes.byref(s), 16, 16, 16, None, None, 16, 16, 1.0, 16, None)
     assert rc == -3
 

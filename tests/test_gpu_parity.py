@@ -97,34 +97,33 @@ def test_zero_length_sequences_give_zero_rows(sd):
 
 
 @pytest.mark.parametrize("kv_dtype,d", [("bf16", 64), ("bf16", 128), ("fp8", 128)])
-def test_single_chunk_batches_skip_the_merge_pass(sd, kv_dtype, d):
-    """A chunk that covers the longest sequence makes the split pass write `out` itself.  The result must be
-    bit-identical to the two-pass result of the same chunking (the merge of one slot is the identity), empty
-    sequences must still get their zero rows, and every element of `out` must be written."""
+@pytest.mark.parametrize("min_range", [0, 128, 640, 4096])
+def test_whole_and_cut_sequences_in_one_launch(sd, kv_dtype, d, min_range):
+    """Ranges of at least `min_range` tokens: from one tile per wave (every sequence cut into many partials
+    that the last wave combines) to one wave holding the whole batch (every sequence written by the wave that
+    walked it).  Empty sequences must get their zero rows and every element of `out` must be written."""
     import torch
-    lens = [0, 40, 1, 513, 0, 640, 639, 16, 17]
+    lens = [0, 40, 1, 513, 0, 640, 639, 16, 17, 0]
     wl = workloads.make_custom(lens, 8, 2, d, kv_dtype, seed=12, max_blocks_per_seq=41)
-    direct = device_workload(wl, chunk_tokens=640)            # 640 >= max length: one chunk per sequence
-    direct.out.fill_(float("nan"))
-    got = direct.attend().clone()
-    # the same chunking through the merge pass: a longer length bound keeps the second slot alive
-    two = device_workload(wl, chunk_tokens=640)
-    two.shape.max_context_len = 641
-    two.ws_bytes = sd.workspace_bytes(two.shape)
-    two.workspace = torch.empty(two.ws_bytes, dtype=torch.uint8, device=two.device)
-    want = two.attend().clone()
+    dw = device_workload(wl, chunk_tokens=min_range)
+    dw.out.fill_(float("nan"))
+    got = dw.attend().clone()
     torch.cuda.synchronize()
-    assert torch.equal(got, want)
     g = got.cpu().numpy()
-    assert not g[0].any() and not g[4].any()
+    assert not g[0].any() and not g[4].any() and not g[9].any()
     (check_fp8 if kv_dtype == "fp8" else check)(g, oracle_full(wl))
+    # a second call on the same workspace (now holding the first call's partials) gives the same bits
+    dw.out.fill_(float("nan"))
+    again = dw.attend()
+    torch.cuda.synchronize()
+    assert torch.equal(again, got)
 
 
 @pytest.mark.parametrize("kv_dtype", ["bf16", "fp8"])
 @pytest.mark.parametrize("chunk", [128, 512])
 def test_lengths_outside_the_bound_are_clamped(sd, chunk, kv_dtype):
     """context_lens above max_context_len count as max_context_len, negative ones as 0 (zero rows), in the
-    split + merge path (chunk 128) and in the single-chunk path (chunk 512 covers the bound)."""
+    path that cuts sequences across waves (ranges of 128 tokens) and with ranges that hold whole sequences."""
     import torch
     from paper_2508_11553_amd.device import _to_dev
     true_lens = np.int32([40, 700, 513, 16, 300, 1500, 512])
@@ -269,14 +268,20 @@ def test_runs_on_a_side_stream(sd):
     assert torch.equal(out2, ref)
 
 
-def test_kernel_timer_reports_both_kernels(sd):
-    wl = workloads.make_custom([700, 64], 8, 2, 128, seed=19)
+def test_kernel_timer_reports_the_kernels_of_a_call(sd):
+    """Both entry points run two kernels and report both durations."""
+    wl = workloads.make_custom([700, 650, 64], 8, 2, 128, seed=19, session_of=[0, 0, 1], prefix_len=[512, 512, 0])
     dw = device_workload(wl)
-    t = sd.KernelTimer(4)
+    t = sd.KernelTimer(8)
     for _ in range(3):
         dw.attend(timer=t)
+    first, second = t.read()
+    assert len(first) == 3 and all(x > 0 for x in first) and all(x > 0 for x in second)
+    t.reset()
+    for _ in range(2):
+        dw.attend_prefix(timer=t)
     split, merge = t.read()
-    assert len(split) == 3 and all(x > 0 for x in split) and all(x > 0 for x in merge)
+    assert len(split) == 2 and all(x > 0 for x in split) and all(x > 0 for x in merge)
     t.close()
 
 
@@ -400,11 +405,10 @@ def test_fp8_head_dim_64_is_reported_unsupported(sd):
 
 def test_full_size_fp8_large_batch(sd):
     """The step bench.py times at this workload: quantising append of one token per sequence, then attention
-    with one chunk per sequence (no merge pass)."""
+    in one launch."""
     import torch
     wl = workloads.make_config(4, append=True)
     dw = device_workload(wl, balance_for_batch=True)
-    assert dw.chunk_tokens() >= wl.max_context_len
     dw.append()
     got = dw.attend()
     torch.cuda.synchronize()
