@@ -1,9 +1,9 @@
 """Condenses rocprofv3 CSV output of a bench.py run into a short text summary.
 
-Usage (after the three profiler runs named in the summary's header):
-    python -m paper_2508_11553_amd.profile_summary --workload 'configs[1]' \
+Usage (after the profiler runs named in the summary's header):
+    python profile_summary.py --workload 'configs[1]' --kernel range_kernel --bench-args='--config 1 ...' \
         --kernel-trace gpurun_out/prof_kt --fetch gpurun_out/prof_fetch --write gpurun_out/prof_write \
-        > profiles/split_kernel_config1.md
+        > profiles/range_kernel_config1.md
 
 FETCH_SIZE and WRITE_SIZE are reported by rocprofv3 in KiB per dispatch.  Each
 is scaled by what the same counter reads for a device-to-device copy of known
@@ -19,15 +19,20 @@ import hashlib
 import os
 import statistics
 
-ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-KERNEL_SOURCES = [os.path.join(ROOT, "paper_2508_11553_amd", "csrc", f) for f in ("attn_split.hip", "attn_tile.h", "kernels.h")]
+ROOT = os.path.dirname(os.path.abspath(__file__))
 COPY_KIB = float(1 << 20)
+# the sources bench.py hashes for each main kernel
+KERNEL_SOURCES = {
+    "range_kernel": ("attn_range.hip", "attn_tile.h", "kernels.h"),
+    "split_kernel": ("attn_split.hip", "attn_tile.h", "kernels.h"),
+    "prefill_kernel": ("attn_prefill.hip", "attn_tile.h", "kernels.h"),
+}
 
 
-def source_hash():
+def source_hash(kernel):
     h = hashlib.sha256()
-    for s in KERNEL_SOURCES:
-        h.update(open(s, "rb").read())
+    for s in KERNEL_SOURCES[kernel]:
+        h.update(open(os.path.join(ROOT, "paper_2508_11553_amd", "csrc", s), "rb").read())
     return h.hexdigest()[:16]
 
 
@@ -59,13 +64,15 @@ def calibration(values_by_kernel):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", required=True)
+    ap.add_argument("--kernel", default="range_kernel", choices=sorted(KERNEL_SOURCES),
+                    help="the main kernel of this workload (its traffic line is what bench.py looks up)")
     ap.add_argument("--kernel-trace", required=True)
     ap.add_argument("--fetch", required=True)
     ap.add_argument("--write", required=True)
     ap.add_argument("--mfma", default=None, help="optional fourth run: --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CU_CYCLES")
-    ap.add_argument("--bench-args", default="--steps 100 --warmup 10 --no-cpu-baseline",
-                    help="arguments bench.py was given in the kernel-trace run (for the header)")
-    ap.add_argument("--pmc-bench-args", default="--steps 20 --warmup 2 --no-cpu-baseline --copy-calibration")
+    ap.add_argument("--bench-args", required=True,
+                    help="the arguments bench.py was given in the kernel-trace run, --config N included (for the header)")
+    ap.add_argument("--pmc-bench-args", required=True, help="the arguments of the counter runs")
     a = ap.parse_args()
 
     print(f"# rocprofv3 summary: bench.py, workload {a.workload}\n")
@@ -76,7 +83,8 @@ def main():
     if a.mfma:
         print(f"    rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CU_CYCLES --output-format csv -d {a.mfma} -o run -- "
               f"python3 bench.py {a.pmc_bench_args}")
-    print(f"    python -m paper_2508_11553_amd.profile_summary --workload '{a.workload}' --kernel-trace {a.kernel_trace} "
+    print(f"    python profile_summary.py --workload '{a.workload}' --kernel {a.kernel} --bench-args='{a.bench_args}' "
+          f"--pmc-bench-args='{a.pmc_bench_args}' --kernel-trace {a.kernel_trace} "
           f"--fetch {a.fetch} --write {a.write}" + (f" --mfma {a.mfma}" if a.mfma else "") + "\n")
 
     print("## Kernel durations (--kernel-trace --stats)\n")
@@ -114,15 +122,15 @@ def main():
         print("| kernel | SQ_VALU_MFMA_BUSY_CYCLES | SQ_BUSY_CU_CYCLES | MFMA busy, % of SIMD cycles |")
         print("|---|---|---|---|")
         for name in busy:
-            if name not in cu or "split_kernel" not in name and "prefill" not in name:
+            if name not in cu or a.kernel not in name:
                 continue
             bz, cz = statistics.mean(busy[name]), statistics.mean(cu[name])
             short = name if len(name) <= 70 else name[:67] + "..."
             print(f"| `{short}` | {bz:.3g} | {cz:.3g} | {100.0 * bz / (4.0 * cz):.1f} |")
     print()
-    tag = source_hash()
+    tag = source_hash(a.kernel)
     for name, t in total.items():
-        if "split_kernel" in name:
+        if a.kernel in name and "Lb1" not in name and ", true>" not in name:   # not the probe instantiation
             print(f"traffic_bytes_per_launch workload={a.workload} source_sha256={tag} kernel={name.split('(')[0].replace('void ', '').replace(' ', '')} value={t:.0f}")
 
 

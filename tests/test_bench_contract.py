@@ -15,26 +15,30 @@ def test_more_than_one_gpu_is_refused_with_a_message():
     assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
 
 
-def test_algorithmic_bytes_of_a_small_step_by_hand():
+def test_step_bytes_of_a_small_step_by_hand():
     sys.path.insert(0, ROOT)
     import bench
     wl = workloads.make_custom([40, 16, 0, 513], 8, 2, 64, seed=1, append=True)   # 3 staged rows (L > 0)
-    ab = bench.algorithmic_bytes(wl, chunk=256, include_append=True)
+    sb = bench.step_bytes(wl, include_append=True)
     kv = (40 + 16 + 513) * 2 * 64 * 2 * 2                   # tokens x kv heads x d x bf16 x (K and V)
     pages = 3 + 1 + 0 + 33
-    chunks = 1 + 1 + 0 + 3
-    partials = chunks * 8 * (64 + 2) * 4
     q, out = 4 * 8 * 64 * 2, 4 * 8 * 64 * 4
-    assert ab["kv"] == kv
-    assert ab["split"] == kv + q + pages * 4 + 4 * 4 + partials
-    assert ab["merge"] == partials + out + 4 * 4
-    assert ab["append"] == 2 * (3 * 2 * 64) * (2 + 2) + 3 * 12
-    assert ab["step"] == ab["split"] + ab["merge"] + ab["append"]
-    # one chunk per sequence: the split pass writes the output itself, nothing else moves
-    one = bench.algorithmic_bytes(wl, chunk=640, include_append=False, direct=True)
-    assert one["merge"] == 0 and one["split"] == kv + q + pages * 4 + 4 * 4 + out
+    assert sb["kv"] == kv
+    assert sb["attention"] == kv + q + pages * 4 + 4 * 4 + out      # no split-K scratch in the useful bytes
+    assert sb["append"] == 2 * (3 * 2 * 64) * (2 + 2) + 3 * 12
+    assert sb["step"] == sb["attention"] + sb["append"]
     # fp8 pools: one byte per element and two scales per (page, head)
     w8 = workloads.make_custom([40, 16], 8, 2, 128, "fp8", seed=2)
-    a8 = bench.algorithmic_bytes(w8, chunk=256, include_append=False)
+    a8 = bench.step_bytes(w8, include_append=False)
     assert a8["kv"] == 56 * 2 * 128 * 1 * 2
-    assert a8["split"] - a8["kv"] == 2 * 8 * 128 * 2 + 4 * 4 + 2 * 4 + 4 * 2 * 8 + 2 * 8 * (128 + 2) * 4
+    assert a8["attention"] - a8["kv"] == 2 * 8 * 128 * 2 + 4 * 4 + 2 * 4 + 4 * 2 * 8 + 2 * 8 * 128 * 4
+
+
+def test_partials_of_the_range_pass_by_hand():
+    """Two KV heads -> 1024 ranges per head; 5 + 1 + 17 = 23 tiles, one per range: sequences of 5 and 17 tiles are
+    cut into as many parts, the one-tile sequence is not cut."""
+    sys.path.insert(0, ROOT)
+    import bench
+    wl = workloads.make_custom([160, 20, 0, 513], 8, 2, 64, seed=1)
+    parts, nbytes = bench.range_partials(wl)
+    assert parts == (5 + 17) * 2 and nbytes == (5 + 17) * 8 * (64 + 2) * 4
