@@ -452,7 +452,7 @@ def test_prefix_entry_point_matches_oracle(sd, Hq, Hkv, d, chunk):
 def test_prefix_entry_point_fp8(sd):
     sizes = [4, 16, 1]
     session_of = np.repeat(np.arange(3), sizes)
-    prefix_len = np.repeat([1024, 2048 + 512, 512], sizes)  # multiples of 16: fp8 tails are not copied
+    prefix_len = np.repeat([1024 + 5, 2048 + 512, 512 - 9], sizes)  # two prefixes end inside a page
     lens = prefix_len + np.random.default_rng(5).integers(1, 700, size=len(session_of))
     wl = workloads.make_custom(lens, 16, 2, 128, "fp8", seed=410, session_of=session_of, prefix_len=prefix_len)
     check_fp8(gpu_attend_prefix(wl, chunk_tokens=512), oracle_full(wl))

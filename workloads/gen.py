@@ -185,7 +185,6 @@ def build_paged(
     if session_of is not None:
         session_of = np.asarray(session_of)
         prefix_len = np.asarray(prefix_len, dtype=np.int64)
-        assert kv_dtype == "bf16" or np.all(prefix_len % PAGE == 0)
         for b in range(B):
             s = int(session_of[b])
             ns = int(prefix_len[b] // PAGE)
@@ -235,15 +234,30 @@ def build_paged(
     k_pages, k_scales = _draw_pool(seed, _TAG_K, num_pages, Hkv, d, kv_dtype, stored, threads)
     v_pages, v_scales = _draw_pool(seed, _TAG_V, num_pages, Hkv, d, kv_dtype, stored, threads)
 
-    # prefix tails that do not fill a page: same bytes in every branch
+    # prefix tails that do not fill a page: same values in every branch.  bf16: the tail's bytes are
+    # copied from the session's first branch.  fp8: codes only mean something together with their
+    # page's scale, so every branch gets the codes AND scales of the whole page of the session's
+    # longest branch (its scale covers a superset of each branch's own tokens in that page; slots a
+    # shorter branch does not own are poisoned below like any other slot past a sequence's end).
     if session_of is not None:
         for b in range(B):
-            _, ns, p, b0 = shared_first[int(session_of[b])]
+            s_id = int(session_of[b])
+            _, ns, p, b0 = shared_first[s_id]
             tail = p % PAGE
-            if tail and b != b0:
-                src, dst = block_table[b0, ns], block_table[b, ns]
-                k_pages[dst, :, :tail] = k_pages[src, :, :tail]
-                v_pages[dst, :, :tail] = v_pages[src, :, :tail]
+            if not tail:
+                continue
+            if kv_dtype == "bf16":
+                if b != b0:
+                    src, dst = block_table[b0, ns], block_table[b, ns]
+                    k_pages[dst, :, :tail] = k_pages[src, :, :tail]
+                    v_pages[dst, :, :tail] = v_pages[src, :, :tail]
+            else:
+                members = np.nonzero(session_of == s_id)[0]
+                bsrc = int(members[np.argmax(lens[members])])
+                if b != bsrc:
+                    src, dst = block_table[bsrc, ns], block_table[b, ns]
+                    k_pages[dst], v_pages[dst] = k_pages[src], v_pages[src]
+                    k_scales[dst], v_scales[dst] = k_scales[src], v_scales[src]
 
     wl = Workload(
         name=name, batch=B, num_q_heads=Hq, num_kv_heads=Hkv, head_dim=d, kv_dtype=kv_dtype,
