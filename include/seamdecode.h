@@ -187,7 +187,9 @@ int kv_copy_pages(const sd_shape *shape, const int32_t *src_pages, const int32_t
  * with K_t, V_t the rows of KV head g at logical position t (fp8: code times
  * the page's scale).  L == 0 gives a zero row.  Products are accumulated in
  * fp32 from bf16 operands; softmax weights are rounded to bf16 before the
- * weighted sum and normalised by the sum of the rounded weights.
+ * weighted sum and normalised by the sum of the rounded weights (fp8 pools: the
+ * weight is rounded after the page's V scale has been folded in, and the sum
+ * runs over those rounded weights divided by the scale again).
  *
  * Runs two kernels (batches of up to 4096 sequences).  Range pass: per KV head
  * the batch's 32-token tiles form one line, sequence after sequence; the line
@@ -377,6 +379,26 @@ int32_t sd_tree_batch_groups(const sd_tree *t, const int32_t *trajs, int32_t B, 
  */
 int sd_validate_tables(const sd_shape *shape, const int32_t *block_table, const int32_t *context_lens,
                        int32_t *report, void *stream);
+
+/*
+ * sd_validate_groups -- optional check of the group arrays of
+ * paged_decode_attention_prefix, which trusts them: a group larger than
+ * max_group_size, members that disagree on shared_len, or members whose shared
+ * pages are not the first member's all give wrong output without any error.
+ * Two tiny launches on `stream` fill report[4] (i32, device, 16-byte aligned):
+ *   report[0]  groups that are empty, reach outside the batch or hold more than
+ *              max_group_size sequences
+ *   report[1]  sequences whose shared_len differs from their group's first
+ *              member's, is negative, exceeds their context_lens or
+ *              max_shared_len, or is non-zero although they are in no group
+ *   report[2]  members whose first shared_len / 16 block-table entries are not
+ *              those of the group's first member
+ *   report[3]  0
+ * All zero means the arrays are consistent.  Nothing else is read or written.
+ */
+int sd_validate_groups(const sd_shape *shape, const int32_t *block_table, const int32_t *context_lens,
+                       const int32_t *group_start, const int32_t *shared_len, int32_t num_groups,
+                       int32_t max_group_size, int32_t max_shared_len, int32_t *report, void *stream);
 
 /*
  * Measurement aids (not part of the decode step).

@@ -24,6 +24,7 @@ from .binding import (  # noqa: F401
     paged_prefill_attention,
     probe_read,
     strerror,
+    validate_groups,
     validate_tables,
     version,
     workspace_bytes,

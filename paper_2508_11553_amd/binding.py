@@ -82,6 +82,8 @@ def load():
     L.paged_prefill_attention.argtypes = [sp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp]
     L.sd_validate_tables.restype = ctypes.c_int
     L.sd_validate_tables.argtypes = [sp, vp, vp, vp, vp]
+    L.sd_validate_groups.restype = ctypes.c_int
+    L.sd_validate_groups.argtypes = [sp, vp, vp, vp, vp, i32, i32, i32, vp, vp]
     L.sd_timer_create.restype = vp
     L.sd_timer_create.argtypes = [i32]
     L.sd_timer_destroy.restype = None
@@ -252,6 +254,14 @@ def validate_tables(shape: Shape, block_table, context_lens, report, stream=None
     rc = load().sd_validate_tables(ctypes.byref(shape), _ptr(block_table), _ptr(context_lens), _ptr(report),
                                    _stream(stream))
     _check(rc, "sd_validate_tables")
+
+
+def validate_groups(shape: Shape, block_table, context_lens, group_start, shared_len, num_groups: int,
+                    max_group_size: int, max_shared_len: int, report, stream=None):
+    rc = load().sd_validate_groups(ctypes.byref(shape), _ptr(block_table), _ptr(context_lens), _ptr(group_start),
+                                   _ptr(shared_len), int(num_groups), int(max_group_size), int(max_shared_len),
+                                   _ptr(report), _stream(stream))
+    _check(rc, "sd_validate_groups")
 
 
 def probe_read(shape: Shape, k_pages, v_pages, k_scales, v_scales, block_table, context_lens, sink, stream=None):

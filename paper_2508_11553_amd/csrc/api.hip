@@ -24,6 +24,10 @@ int hip_fail(hipError_t e)
     return SD_EHIP;
 }
 
+// Workgroups of 4 waves at 2 waves per SIMD that the largest device this library targets runs at once
+// (256 compute units x 2).
+constexpr int kMaxRangeWorkgroups = 512;
+
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 bool bad_ptr(const void *p) { return p == nullptr || !aligned16(p); }
 
@@ -65,7 +69,9 @@ int chunk_for(const sd_shape *s, int64_t total_tokens)
     int lo = 512;
     while (lo * elem < 200 * G && lo < 4096) lo *= 2;
     const int64_t whole = std::max<int64_t>(128, ((int64_t)s->max_context_len + 127) / 128 * 128);
-    const int64_t share = total_tokens * s->num_kv_heads / 512;  // tokens per workgroup slot
+    // workgroup slots of the largest device this library targets (256 compute units x 2); the chunk is a host-only
+    // function of the shape so that callers can size buffers without a device, hence no device query here
+    const int64_t share = total_tokens * s->num_kv_heads / kMaxRangeWorkgroups;  // tokens per workgroup slot
     const double target = (double)std::max<int64_t>(share * 3 / 4, lo);
     int best = lo;
     for (int c = 512; c <= 8192; c += (c & (c - 1)) ? c / 3 : c / 2) {  // 512, 768, 1024, 1536, ... 8192
@@ -130,7 +136,6 @@ int static_scratch(void **ptr)
 
 // Workspace of the range pass (batches without shared prefixes): the sequences' tile offsets for
 // the merge pass, then the waves' partial slots.
-constexpr int kMaxRangeWorkgroups = 512;          // two per compute unit on a 256-CU device
 
 struct RangeLayout {
     int rblocks;                 // workgroups per virtual head
@@ -653,6 +658,33 @@ int sd_validate_tables(const sd_shape *shape, const int32_t *block_table, const 
     a.num_pages = shape->num_pages;
     a.max_context_len = shape->max_context_len;
     const hipError_t e = sd::launch_validate(a, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SD_OK : hip_fail(e);
+}
+
+int sd_validate_groups(const sd_shape *shape, const int32_t *block_table, const int32_t *context_lens,
+                       const int32_t *group_start, const int32_t *shared_len, int32_t num_groups,
+                       int32_t max_group_size, int32_t max_shared_len, int32_t *report, void *stream)
+{
+    const int rc = check_shape(shape);
+    if (rc) return rc;
+    if (num_groups < 0 || max_group_size < 0 || max_shared_len < 0 || max_shared_len > shape->max_context_len)
+        return SD_EINVAL;
+    if (bad_ptr(report)) return SD_EINVAL;
+    if (shape->batch > 0 && (bad_ptr(block_table) || bad_ptr(context_lens) || bad_ptr(shared_len))) return SD_EINVAL;
+    if (num_groups > 0 && bad_ptr(group_start)) return SD_EINVAL;
+    sd::ValidateGroupsArgs a;
+    a.block_table = block_table;
+    a.context_lens = context_lens;
+    a.group_start = group_start;
+    a.shared_len = shared_len;
+    a.report = report;
+    a.B = shape->batch;
+    a.max_blocks = shape->max_blocks_per_seq;
+    a.max_context_len = shape->max_context_len;
+    a.num_groups = num_groups;
+    a.max_group_size = max_group_size;
+    a.max_shared_len = max_shared_len;
+    const hipError_t e = sd::launch_validate_groups(a, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SD_OK : hip_fail(e);
 }
 

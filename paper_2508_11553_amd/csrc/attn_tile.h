@@ -519,13 +519,19 @@ struct Fp8Path {
             }
     }
 
-    // weights of one block -> P^T operand (times the page's V scale) and the
-    // unscaled weight sum
+    // Weights of one block -> P^T operand and weight sum.  The operand carries the page's V scale:
+    // w = bf16(p * v_scale) multiplies the raw codes.  The sum runs over the weights the product
+    // really uses, w / v_scale, so that the result is an exact convex combination of the dequantised
+    // values (a page whose scale is 0 holds zeros only; its weights count unrounded).
     SD_DEV static u32x4 weight_operand(const float (&p)[8], float va, float vb, float &l)
     {
-        l += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
-        return u32x4{cvt_pk_bf16(p[0] * va, p[1] * va), cvt_pk_bf16(p[2] * va, p[3] * va),
-                     cvt_pk_bf16(p[4] * vb, p[5] * vb), cvt_pk_bf16(p[6] * vb, p[7] * vb)};
+        const u32x4 w = {cvt_pk_bf16(p[0] * va, p[1] * va), cvt_pk_bf16(p[2] * va, p[3] * va),
+                         cvt_pk_bf16(p[4] * vb, p[5] * vb), cvt_pk_bf16(p[6] * vb, p[7] * vb)};
+        auto pair_sum = [](unsigned x) { return __builtin_bit_cast(float, x << 16) + __builtin_bit_cast(float, x & 0xffff0000u); };
+        const float sa = pair_sum(w[0]) + pair_sum(w[1]), sb = pair_sum(w[2]) + pair_sum(w[3]);
+        l += va != 0.f ? sa * __builtin_amdgcn_rcpf(va) : (p[0] + p[1]) + (p[2] + p[3]);
+        l += vb != 0.f ? sb * __builtin_amdgcn_rcpf(vb) : (p[4] + p[5]) + (p[6] + p[7]);
+        return w;
     }
 
     SD_DEV static void attend(const u32x4 (&ka)[4], const u32x4 (&kb)[4], Tile &r, const u32x4 (&qop)[4], State &st,

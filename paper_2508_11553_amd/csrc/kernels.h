@@ -159,6 +159,12 @@ struct ValidateArgs {
     int32_t B, max_blocks, num_pages, max_context_len;
 };
 
+struct ValidateGroupsArgs {
+    const int32_t *block_table, *context_lens, *group_start, *shared_len;
+    int32_t *report;             // [4]
+    int32_t B, max_blocks, max_context_len, num_groups, max_group_size, max_shared_len;
+};
+
 // Launchers: enqueue on `stream`, return the hipError_t of the launch.  When
 // `start`/`stop` are given they are bound to the kernel's own begin and end
 // timestamps (hipExtLaunchKernelGGL), so their elapsed time is the kernel's
@@ -177,5 +183,6 @@ hipError_t launch_append(const AppendArgs &a, int head_dim, hipStream_t stream);
 hipError_t launch_append_fp8(const AppendFp8Args &a, hipStream_t stream);
 hipError_t launch_copy_pages(const CopyPagesArgs &a, hipStream_t stream);
 hipError_t launch_validate(const ValidateArgs &a, hipStream_t stream);
+hipError_t launch_validate_groups(const ValidateGroupsArgs &a, hipStream_t stream);
 
 }  // namespace sd

@@ -161,6 +161,21 @@ def test_constant_v_returns_the_constant(sd):
     assert np.abs(got - workloads.bf16_bits_to_f32(np.uint16([c]))[0]).max() <= 1e-6
 
 
+@pytest.mark.parametrize("min_range", [0, 4096])
+def test_fp8_constant_v_returns_the_constant(sd, min_range):
+    """fp8 pools: pages with different (power-of-two) V scales whose codes all decode to 0.5.  The weight sum runs
+    over the rounded weights the product uses, so the constant comes back to fp32 rounding; both with sequences cut
+    across waves and with one workgroup per sequence."""
+    wl = workloads.make_custom([1, 5, 33, 200, 1300], 8, 2, 128, "fp8", seed=11, poison=False)
+    codes = {0.25: 0x40, 0.5: 0x38, 2.0: 0x28}      # 2.0, 1.0, 0.25 in e4m3fn: code value x scale = 0.5
+    for p in range(wl.num_pages):
+        s = (0.25, 0.5, 2.0)[p % 3]
+        wl.v_scales[p, :] = np.float32(s)
+        wl.v_pages[p] = codes[s]
+    got = gpu_attend(wl, chunk_tokens=min_range)
+    assert np.abs(got - 0.5).max() <= 1e-6
+
+
 def test_poisoned_slots_and_table_entries_are_never_read(sd):
     a = workloads.make_custom([3, 47, 130, 512, 529], 8, 2, 128, seed=12, poison=True)
     c = workloads.make_custom([3, 47, 130, 512, 529], 8, 2, 128, seed=12, poison=False)
@@ -632,6 +647,40 @@ def test_validate_tables_counts_what_a_launch_would_dereference(sd):
     want_bad = sum(int(((bt[b, :used[b]] < 0) | (bt[b, :used[b]] >= wl.num_pages)).sum()) for b in range(wl.batch))
     assert want_bad == 3
     assert report.cpu().tolist()[:2] == [want_bad, 2]
+
+
+def test_validate_groups_reports_inconsistent_group_arrays(sd):
+    """Deliberately inconsistent group arrays go to the check only, never to the attention kernel."""
+    import torch
+    from paper_2508_11553_amd.device import _to_dev
+    sizes = [3, 5, 2]
+    session_of = np.repeat(np.arange(3), sizes)
+    prefix_len = np.repeat([64, 160, 32], sizes)
+    lens = prefix_len + np.arange(1, 11) * 7
+    wl = workloads.make_custom(np.concatenate([lens, [50]]), 8, 2, 64, seed=71,
+                               session_of=np.concatenate([session_of, [3]]), prefix_len=np.concatenate([prefix_len, [0]]))
+    dw = device_workload(wl)
+    report = torch.full((4,), 77, dtype=torch.int32, device=dw.device)
+
+    def run(gs, sh, table=None, max_group=5, max_shared=160, ngroups=None):
+        gs = np.int32(gs)
+        sd.validate_groups(dw.shape, dw.block_table if table is None else _to_dev(table, dw.device), dw.context_lens,
+                           _to_dev(gs, dw.device), _to_dev(np.int32(sh), dw.device), len(gs) - 1 if ngroups is None else ngroups,
+                           max_group, max_shared, report)
+        torch.cuda.synchronize()
+        return report.cpu().tolist()
+
+    gs, sh = wl.group_start[:4], wl.shared_len           # the last sequence is in no group
+    assert run(gs, sh) == [0, 0, 0, 0]
+    assert run(gs, sh, max_group=4) == [1, 0, 0, 0]      # the group of five is too large
+    bad = sh.copy(); bad[4] = 144; bad[10] = 16          # a member disagrees; the ungrouped sequence claims a prefix
+    assert run(gs, bad) == [0, 2, 0, 0]
+    bad = sh.copy(); bad[8:10] = 112                     # a whole group claims more than its members hold (95, 102)
+    assert run(gs, bad)[1] == 2
+    tbl = wl.block_table.copy(); tbl[6, 3] = tbl[6, 4]   # a member's shared page is not the first member's
+    tbl[1, 7] = 0                                         # beyond the shared pages: not looked at
+    assert run(gs, sh, table=tbl) == [0, 0, 1, 0]
+    assert run([0, 3, 3, 20], sh)[0] == 2                # an empty group and one that leaves the batch
 
 
 # ---------------------------------------------------------------- HIP graph capture

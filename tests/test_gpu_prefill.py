@@ -85,9 +85,8 @@ def test_one_query_per_sequence_equals_the_decode_step(sd):
 
 @pytest.mark.parametrize("kv_dtype,d", [("bf16", 64), ("bf16", 128), ("fp8", 128)])
 def test_constant_v_returns_the_constant(sd, kv_dtype, d):
-    """Every row is a convex combination of V rows; for bf16 pools it is normalised by the sum of the very
-    weights the product uses, so with all V rows equal the result is that row up to fp32 rounding, however the
-    weights round."""
+    """Every row is a convex combination of V rows, normalised by the sum of the very weights the product uses,
+    so with all V rows equal the result is that row up to fp32 rounding, however the weights round."""
     lens, nq = [70, 300, 33], [70, 40, 33]
     wl, q, q_start = make(lens, nq, 8, 2, d, kv_dtype, seed=51)
     if kv_dtype == "bf16":
@@ -99,10 +98,7 @@ def test_constant_v_returns_the_constant(sd, kv_dtype, d):
         wl.v_scales[...] = np.float32(0.25)
         want = 0.25
     got = gpu(wl, q, q_start)
-    # fp8 pools: the product takes bf16(weight * page scale) while the sum takes the weights themselves, so the
-    # constant comes back to bf16 rounding only
-    tol = 2.0 ** -8 * want if kv_dtype == "fp8" else 2e-6 * abs(want) + 1e-7
-    assert np.abs(got - want).max() <= tol
+    assert np.abs(got - want).max() <= 2e-6 * abs(want) + 1e-7
 
 
 def test_sequences_without_queries_with_too_many_and_empty(sd):
