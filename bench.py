@@ -358,8 +358,14 @@ def run_config(cfg, args):
     sb_logical = step_bytes(wl, do_append, unique=False)
     stream = torch.cuda.current_stream()
 
+    # bf16 pools without shared prefixes: the newest token is appended and attended by ONE call
+    one_call = do_append and not prefix_aware and wl.kv_dtype == "bf16" and not args.separate_append
+
     def step(i, timer=None):
         dw.set_pool(*pools[i % npools])
+        if one_call:
+            dw.append_and_attend(stream, timer)
+            return
         if do_append:
             dw.append(stream)
         if prefix_aware:
@@ -456,8 +462,9 @@ def run_config(cfg, args):
             "workload": f"configs[{cfg}] {wl.name}", "batch": wl.batch, "q_heads": wl.num_q_heads,
             "kv_heads": wl.num_kv_heads, "head_dim": wl.head_dim, "page_size": 16, "kv_dtype": wl.kv_dtype,
             "attended_tokens": wl.attended_tokens, "unique_tokens": wl.unique_tokens,
-            "pools_rotated": npools, "entry_point": "paged_decode_attention_prefix" if prefix_aware else
-            "paged_decode_attention", "kernels": path, "chunk_tokens": chunk if (prefix_aware or single_pass) else None,
+            "pools_rotated": npools, "entry_point": "paged_decode_attention_append" if one_call else
+            ("kv_append_fp8 + " if wl.kv_dtype == "fp8" and do_append else "kv_append + " if do_append else "") +
+            ("paged_decode_attention_prefix" if prefix_aware else "paged_decode_attention"), "kernels": path, "chunk_tokens": chunk if (prefix_aware or single_pass) else None,
             "append_rows_per_step": int(wl.k_new.shape[0]) if do_append else 0, "seed": 0,
         },
         "attended_kv_tokens_per_s": wl.attended_tokens / (ms_per_step * 1e-3),
@@ -497,6 +504,8 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=5.0, help="host time given to the oracle per workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-append", action="store_true")
+    ap.add_argument("--separate-append", action="store_true",
+                    help="bf16 workloads: kv_append and paged_decode_attention as two calls instead of paged_decode_attention_append")
     ap.add_argument("--no-prefix", action="store_true",
                     help="branching workloads: use the plain entry point instead of the shared-prefix aware one")
     ap.add_argument("--copy-calibration", action="store_true",

@@ -55,6 +55,8 @@ extern "C" {
 #define SD_EWORKSPACE (-3)   /* workspace smaller than sd_workspace_bytes() */
 #define SD_EHIP (-4)         /* a HIP call failed; see sd_last_hip_error() */
 
+struct sd_timer; /* see the measurement aids at the end */
+
 #define SD_BF16 0
 #define SD_FP8_E4M3 1
 
@@ -215,6 +217,32 @@ int paged_decode_attention(const sd_shape *shape, const void *q,
                            void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * paged_decode_attention_append -- one decode step in one call: the newest
+ * token of every sequence is written into the cache AND attended.
+ *
+ * Advancing a rollout by one token (Data Plane: trajectories advance token by
+ * token between pauses) appends that token's K/V and attends over the sequence
+ * including it.  Row b of k_new / v_new (bf16 [batch][num_kv_heads][d], device)
+ * is the K/V of sequence b's newest token, whose position is
+ * context_lens[b] - 1 (the lengths passed already count it).  The result is
+ * that of kv_append(rows at those positions) followed by
+ * paged_decode_attention, bit for bit in the pool; where the range pass runs,
+ * the wave that walks a sequence's last tile takes the token from the rows and
+ * writes it into its slot, so no separate append kernel is launched.
+ * Sequences with context_lens <= 0 are left alone (zero rows in `out`).
+ * SD_BF16 pools only (SD_EUNSUPPORTED otherwise: fp8 pools take new tokens
+ * through kv_append_fp8).  Other arguments as for paged_decode_attention;
+ * `timer` may be NULL.
+ */
+int paged_decode_attention_append(const sd_shape *shape, const void *q,
+                                  const void *k_new, const void *v_new,
+                                  void *k_pages, void *v_pages,
+                                  const int32_t *block_table, const int32_t *context_lens,
+                                  float scale, float *out,
+                                  void *workspace, size_t workspace_bytes, void *stream,
+                                  struct sd_timer *timer);
+
+/*
  * paged_decode_attention_static -- paged_decode_attention without a workspace
  * argument, for callers that cannot allocate device memory: code running under
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
@@ -269,7 +297,6 @@ int paged_decode_attention_static(const sd_shape *shape, const void *q,
  * group for j < shared_len/16; the library reads the first member's row.
  * num_groups == 0 makes the call identical to paged_decode_attention.
  */
-struct sd_timer;
 int paged_decode_attention_prefix(const sd_shape *shape, const void *q,
                                   const void *k_pages, const void *v_pages,
                                   const float *k_scales, const float *v_scales,

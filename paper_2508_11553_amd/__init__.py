@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     lib_path,
     load,
     paged_decode_attention,
+    paged_decode_attention_append,
     paged_decode_attention_prefix,
     paged_decode_attention_static,
     paged_prefill_attention,

@@ -67,6 +67,8 @@ def load():
     L.kv_append.argtypes = [sp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
     L.paged_decode_attention.restype = ctypes.c_int
     L.paged_decode_attention.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, sz, vp]
+    L.paged_decode_attention_append.restype = ctypes.c_int
+    L.paged_decode_attention_append.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, sz, vp, vp]
     L.paged_decode_attention_static.restype = ctypes.c_int
     L.paged_decode_attention_static.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp]
     L.paged_decode_attention_timed.restype = ctypes.c_int
@@ -211,6 +213,16 @@ def paged_decode_attention(shape: Shape, q, k_pages, v_pages, k_scales, v_scales
                                             float(scale), _ptr(out), _ptr(workspace), int(workspace_nbytes),
                                             _stream(stream), timer._h)
     _check(rc, "paged_decode_attention")
+
+
+def paged_decode_attention_append(shape: Shape, q, k_new, v_new, k_pages, v_pages, block_table, context_lens,
+                                  scale: float, out, workspace, workspace_nbytes: int, stream=None,
+                                  timer: Optional[KernelTimer] = None):
+    rc = load().paged_decode_attention_append(ctypes.byref(shape), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_pages),
+                                              _ptr(v_pages), _ptr(block_table), _ptr(context_lens), float(scale),
+                                              _ptr(out), _ptr(workspace), int(workspace_nbytes), _stream(stream),
+                                              timer._h if timer is not None else None)
+    _check(rc, "paged_decode_attention_append")
 
 
 def paged_decode_attention_static(shape: Shape, q, k_pages, v_pages, k_scales, v_scales, block_table, context_lens,

@@ -253,9 +253,11 @@ int kv_append(const sd_shape *shape, const void *k_new, const void *v_new,
     a.k_pages = static_cast<uint4 *>(k_pages);
     a.v_pages = static_cast<uint4 *>(v_pages);
     a.block_table = block_table;
+    a.context_lens = nullptr;
     a.T = T;
     a.Hkv = shape->num_kv_heads;
     a.max_blocks = shape->max_blocks_per_seq;
+    a.max_context_len = shape->max_context_len;
     const hipError_t e = sd::launch_append(a, shape->head_dim, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SD_OK : hip_fail(e);
 }
@@ -333,10 +335,13 @@ int attend_impl(const sd_shape *shape, const void *q, const void *k_pages, const
                 const float *k_scales, const float *v_scales, const int32_t *block_table,
                 const int32_t *context_lens, const int32_t *group_start, const int32_t *shared_len,
                 int32_t num_groups, int32_t max_group_size, int32_t max_shared_len, float scale, float *out,
-                void *workspace, size_t workspace_bytes, void *stream, sd_timer *timer, bool own_scratch)
+                void *workspace, size_t workspace_bytes, void *stream, sd_timer *timer, bool own_scratch,
+                const void *k_new = nullptr, const void *v_new = nullptr)
 {
     const int rc = check_shape(shape);
     if (rc) return rc;
+    if ((k_new || v_new) && (shape->kv_dtype != SD_BF16 || bad_ptr(k_new) || bad_ptr(v_new)))
+        return shape->kv_dtype != SD_BF16 ? SD_EUNSUPPORTED : SD_EINVAL;
     if (num_groups < 0 || max_group_size < 0 || max_shared_len < 0 || max_shared_len > shape->max_context_len)
         return SD_EINVAL;
     if (shape->batch == 0) return SD_OK;
@@ -387,6 +392,10 @@ int attend_impl(const sd_shape *shape, const void *q, const void *k_pages, const
         ra.ws_l = reinterpret_cast<float *>(ws + rl.l_off);
         ra.ws_acc = reinterpret_cast<float *>(ws + rl.acc_off);
         ra.sink = nullptr;
+        ra.k_new = static_cast<const uint16_t *>(k_new);
+        ra.v_new = static_cast<const uint16_t *>(v_new);
+        ra.k_pages_out = k_new ? static_cast<uint16_t *>(const_cast<void *>(k_pages)) : nullptr;
+        ra.v_pages_out = k_new ? static_cast<uint16_t *>(const_cast<void *>(v_pages)) : nullptr;
         ra.scale_log2e = scale * 1.4426950408889634f;
         ra.B = shape->batch;
         ra.Hq = shape->num_q_heads;
@@ -422,6 +431,21 @@ int attend_impl(const sd_shape *shape, const void *q, const void *k_pages, const
         return SD_OK;
     }
 
+    if (k_new) {   // these passes read the newest token from the pool: put it there first
+        sd::AppendArgs ap;
+        ap.k_new = static_cast<const uint4 *>(k_new);
+        ap.v_new = static_cast<const uint4 *>(v_new);
+        ap.seq_ids = ap.positions = nullptr;
+        ap.k_pages = static_cast<uint4 *>(const_cast<void *>(k_pages));
+        ap.v_pages = static_cast<uint4 *>(const_cast<void *>(v_pages));
+        ap.block_table = block_table;
+        ap.context_lens = context_lens;
+        ap.T = shape->batch;
+        ap.Hkv = shape->num_kv_heads;
+        ap.max_blocks = shape->max_blocks_per_seq;
+        ap.max_context_len = shape->max_context_len;
+        if ((e = sd::launch_append(ap, shape->head_dim, st)) != hipSuccess) return hip_fail(e);
+    }
     if (own_scratch) {
         if (!direct && w.total > kStaticScratchBytes) return SD_EWORKSPACE;
         const int src = static_scratch(&workspace);
@@ -510,6 +534,16 @@ int paged_decode_attention_prefix(const sd_shape *shape, const void *q, const vo
     return attend_impl(shape, q, k_pages, v_pages, k_scales, v_scales, block_table, context_lens, group_start,
                        shared_len, num_groups, max_group_size, max_shared_len, scale, out, workspace,
                        workspace_bytes, stream, timer, false);
+}
+
+int paged_decode_attention_append(const sd_shape *shape, const void *q, const void *k_new, const void *v_new,
+                                  void *k_pages, void *v_pages, const int32_t *block_table,
+                                  const int32_t *context_lens, float scale, float *out, void *workspace,
+                                  size_t workspace_bytes, void *stream, sd_timer *timer)
+{
+    if (bad_ptr(k_new) || bad_ptr(v_new)) return check_shape(shape) ? check_shape(shape) : SD_EINVAL;
+    return attend_impl(shape, q, k_pages, v_pages, nullptr, nullptr, block_table, context_lens, nullptr, nullptr, 0, 0,
+                       0, scale, out, workspace, workspace_bytes, stream, timer, false, k_new, v_new);
 }
 
 int paged_decode_attention_static(const sd_shape *shape, const void *q, const void *k_pages, const void *v_pages,

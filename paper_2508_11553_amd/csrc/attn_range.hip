@@ -120,6 +120,9 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(2, 
     const int rblock = blockIdx.x / Hv;
     const HeadBlock hb = head_block(gv, a.G, a.HB);
 
+    // the newest token of every sequence comes as a row of k_new / v_new and goes into the pool from here
+    const int fused = P::kAppendInPlace && !PROBE && a.k_new != nullptr;
+
     // ---- tile offsets: exclusive prefix sums of ceil(L_b / 32), by the whole workgroup
     int nt[kSeqsPerThread];
     int local = 0;
@@ -128,8 +131,8 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(2, 
     for (int i = 0; i < kSeqsPerThread; ++i) {
         const int b = tid * per_thread + i;
         nt[i] = 0;
-        if (i < per_thread && b < a.B)
-            nt[i] = (max(0, min(a.context_lens[b], a.max_context_len)) + kTileTokens - 1) / kTileTokens;
+        if (i < per_thread && b < a.B)   // the pool's tokens: with an append in flight the newest one is not among them
+            nt[i] = (max(0, min(a.context_lens[b], a.max_context_len) - fused) + kTileTokens - 1) / kTileTokens;
         local += nt[i];
     }
     int incl = local;
@@ -159,13 +162,24 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(2, 
     if (!PROBE && blockIdx.x == 0)
         for (int i = tid; i <= a.B; i += kWaves * 64) a.tile_off[i] = tile_off[i];
 
-    // ---- empty sequences owe zero rows; the workgroups of this head share them out
+    // ---- sequences without tiles; the workgroups of this head share them out.  Empty ones owe zero
+    // rows; with an append in flight a sequence of one token is just that token: its V row is the
+    // result, and the row still has to go into the pool.
     if (!PROBE) {
         const int nrb = gridDim.x / Hv;
         for (int b = rblock; b < a.B; b += nrb)
-            if (tile_off[b + 1] == tile_off[b])
+            if (tile_off[b + 1] == tile_off[b]) {
+                const bool one = fused && min(a.context_lens[b], a.max_context_len) == 1;
+                const uint16_t *vrow = one ? a.v_new + ((int64_t)b * a.Hkv + hb.g) * D : nullptr;
                 for (int idx = tid; idx < hb.rows * D; idx += kWaves * 64)
-                    a.out[((int64_t)b * a.Hq + hb.head0) * D + idx] = 0.f;
+                    a.out[((int64_t)b * a.Hq + hb.head0) * D + idx] =
+                        one ? __builtin_bit_cast(float, (unsigned)vrow[idx % D] << 16) : 0.f;
+                if (one && gv % a.HB == 0 && tid < D) {
+                    const int64_t at = ((int64_t)a.block_table[(int64_t)b * a.max_blocks] * a.Hkv + hb.g) * (kPage * D) + tid;
+                    a.k_pages_out[at] = a.k_new[((int64_t)b * a.Hkv + hb.g) * D + tid];
+                    a.v_pages_out[at] = vrow[tid];
+                }
+            }
     }
     // no workgroup barrier below this line: from here on every wave is on its own
 
@@ -204,7 +218,7 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(2, 
         sg.o1 = __builtin_amdgcn_readfirstlane(tile_off[b + 1]);
         sg.lt0 = max(g0, sg.o0) - sg.o0;
         sg.lt1 = min(g1, sg.o1) - sg.o0;
-        sg.L = max(0, min(a.context_lens[b], a.max_context_len));
+        sg.L = max(0, min(a.context_lens[b], a.max_context_len) - fused);   // tokens in the pool
         sg.row = a.block_table + (int64_t)b * a.max_blocks;
         return sg;
     };
@@ -257,7 +271,27 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(2, 
         for (int s = 0; s < D / 32; ++s)
             qop[s] = n < hb.rows ? *reinterpret_cast<const u32x4 *>(a.q + row * D + P::q_offset(s, lane)) : u32x4{0, 0, 0, 0};
         reset(st);
+        // the segment that ends its sequence also takes the newest token, which is not in the pool yet; its
+        // rows are requested now so that they are there when the walk is over
+        const bool newest = fused && sg.lt1 == sg.o1 - sg.o0;   // wave-uniform
+        typename P::NewRow nr;
+        const int64_t new_at = ((int64_t)b * a.Hkv + hb.g) * D;
+        if (newest) nr = P::load_new_row(a.k_new + new_at, a.v_new + new_at, lane);
         stream_tiles<P, true>(a, bt, hb.g, t0, t1, 0, 1, qop, st, s_k, lane);
+        if (newest) {
+            typename P::Tile t;
+            P::new_row_tile(t, nr);
+            u32x4 ka[D / 32], kb[D / 32];
+            P::k_store(t, s_k, lane);
+            wave_lds_fence();
+            P::k_fetch(s_k, lane, ka, kb);
+            wave_lds_fence();
+            P::attend(ka, kb, t, qop, st, a.scale_log2e, sg.L, sg.L + 1, lane);   // one token, at position L - 1 of the sequence
+            if (gv % a.HB == 0) {   // one of the head blocks of this KV head puts the rows into the pool
+                const int64_t at = ((int64_t)sg.row[sg.L / kPage] * a.Hkv + hb.g) * (kPage * D) + (sg.L % kPage) * D;
+                P::store_new_row(nr, a.k_pages_out + at, a.v_pages_out + at, lane);
+            }
+        }
         finish(sg);
     }
     if (PROBE) {

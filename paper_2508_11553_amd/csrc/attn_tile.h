@@ -211,6 +211,46 @@ struct Bf16Path {
                 r.v[pg][h][j] = kv_load<STREAM>(reinterpret_cast<const u32x2 *>(vl + j * (D * 2) + h * 128));
     }
 
+    // The newest token of a sequence handed over as rows instead of pool bytes (the decode step that
+    // appends and attends in one go): row pieces in the lanes that would hold token 0 of a tile.
+    static constexpr bool kAppendInPlace = true;
+    struct NewRow {
+        u32x4 k;            // lanes < kPieces: 16 bytes of the K row
+        u32x2 v[D / 64];    // lanes < 16: V row, d = 64*half + 4*lane .. +4
+    };
+    SD_DEV static NewRow load_new_row(const uint16_t *k_row, const uint16_t *v_row, int lane)
+    {
+        NewRow x;
+        x.k = lane < kPieces ? *reinterpret_cast<const u32x4 *>(k_row + lane * 8) : u32x4{0, 0, 0, 0};
+#pragma unroll
+        for (int h = 0; h < D / 64; ++h)
+            x.v[h] = lane < 16 ? *reinterpret_cast<const u32x2 *>(v_row + 64 * h + 4 * lane) : u32x2{0, 0};
+        return x;
+    }
+    SD_DEV static void store_new_row(const NewRow &x, uint16_t *k_row, uint16_t *v_row, int lane)
+    {
+        if (lane < kPieces) *reinterpret_cast<u32x4 *>(k_row + lane * 8) = x.k;
+#pragma unroll
+        for (int h = 0; h < D / 64; ++h)
+            if (lane < 16) *reinterpret_cast<u32x2 *>(v_row + 64 * h + 4 * lane) = x.v[h];
+    }
+    // a tile whose token 0 is the new row and whose other 31 tokens are zeros (masked by position anyway)
+    SD_DEV static void new_row_tile(Tile &r, const NewRow &x)
+    {
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg) {
+#pragma unroll
+            for (int j = 0; j < D / 32; ++j) r.k[pg][j] = u32x4{0, 0, 0, 0};
+#pragma unroll
+            for (int h = 0; h < D / 64; ++h)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) r.v[pg][h][j] = u32x2{0, 0};
+        }
+        r.k[0][0] = x.k;
+#pragma unroll
+        for (int h = 0; h < D / 64; ++h) r.v[0][h][0] = x.v[h];
+    }
+
     // XOR of everything a tile's loads brought in (read probe)
     SD_DEV static u32x4 fold(const Tile &r)
     {
@@ -434,16 +474,25 @@ struct Fp8Path {
         r.vs[pg] = vs[si];
     }
 
+    // fp8 pools take new tokens through kv_append_fp8 (a page's scale may have to change)
+    static constexpr bool kAppendInPlace = false;
+    struct NewRow {};
+    SD_DEV static NewRow load_new_row(const uint16_t *, const uint16_t *, int) { return NewRow{}; }
+    SD_DEV static void store_new_row(const NewRow &, uint16_t *, uint16_t *, int) {}
+    SD_DEV static void new_row_tile(Tile &, const NewRow &) {}
+
     SD_DEV static u32x4 fold(const Tile &r)
     {
-        u32x4 f = {__builtin_bit_cast(unsigned, r.ks[0]) ^ __builtin_bit_cast(unsigned, r.ks[1]),
-                   __builtin_bit_cast(unsigned, r.vs[0]) ^ __builtin_bit_cast(unsigned, r.vs[1]), 0, 0};
+        u32x4 f = r.k[0][0] ^ r.k[0][1] ^ r.k[1][0] ^ r.k[1][1];
 #pragma unroll
-        for (int pg = 0; pg < 2; ++pg) {
-            f ^= r.k[pg][0] ^ r.k[pg][1];
+        for (int pg = 0; pg < 2; ++pg)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) f ^= u32x4{r.v[pg][j][0], r.v[pg][j][1], 0, 0};
-        }
+            for (int j = 0; j < 4; ++j) {
+                f[0] ^= r.v[pg][j][0];
+                f[1] ^= r.v[pg][j][1];
+            }
+        f[2] ^= __builtin_bit_cast(unsigned, r.ks[0]) ^ __builtin_bit_cast(unsigned, r.ks[1]);
+        f[3] ^= __builtin_bit_cast(unsigned, r.vs[0]) ^ __builtin_bit_cast(unsigned, r.vs[1]);
         return f;
     }
 

@@ -79,6 +79,11 @@ struct RangeArgs {
     const float *k_scales, *v_scales;
     const int32_t *block_table, *context_lens;
     float *out;                  // [B][Hq][D]
+    // append and attend in one go (bf16 pools; all null otherwise): row b of k_new / v_new [B][Hkv][D] is the
+    // newest token of sequence b, at position context_lens[b] - 1; it is attended from these rows and written
+    // into the pool
+    const uint16_t *k_new, *v_new;
+    uint16_t *k_pages_out, *v_pages_out;
     int32_t *tile_off;           // [B + 1] written for the merge pass: tiles of the sequences before b
     int4 *merge_rec;             // [ranges][Hv] written for the merge pass: {b, tile_off[b], tile_off[b+1], T} of the cut
                                  // sequence whose first part the range holds, or b = -1
@@ -128,10 +133,11 @@ struct PrefillArgs {
 
 struct AppendArgs {
     const uint4 *k_new, *v_new;  // [T][Hkv][D] bf16 viewed as 16-byte words
-    const int32_t *seq_ids, *positions;
+    const int32_t *seq_ids, *positions;   // [T], or both null: row j = sequence j's newest token (see context_lens)
     uint4 *k_pages, *v_pages;
     const int32_t *block_table;
-    int32_t T, Hkv, max_blocks;
+    const int32_t *context_lens;          // used only without index arrays
+    int32_t T, Hkv, max_blocks, max_context_len;
 };
 
 struct AppendFp8Args {

@@ -16,7 +16,10 @@ __global__ __launch_bounds__(256) void append_kernel(AppendArgs a)
     const int piece = (int)(gid % kPieces);
     const int g = (int)((gid / kPieces) % a.Hkv);
     const int j = (int)(gid / ((int64_t)kPieces * a.Hkv));
-    const int seq = a.seq_ids[j], pos = a.positions[j];
+    // without index arrays row j is the newest token of sequence j: position context_lens[j] - 1
+    const int seq = a.seq_ids ? a.seq_ids[j] : j;
+    const int pos = a.positions ? a.positions[j] : min(a.context_lens[j], a.max_context_len) - 1;
+    if (pos < 0) return;
     const int64_t page = a.block_table[(int64_t)seq * a.max_blocks + pos / kPage];
     const int64_t dst = ((page * a.Hkv + g) * kPage + pos % kPage) * kPieces + piece;
     a.k_pages[dst] = a.k_new[gid];

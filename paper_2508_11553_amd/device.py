@@ -48,6 +48,12 @@ class DeviceWorkload:
             self.T = int(wl.k_new.shape[0])
             # the same rows as ranges of one token each, for the fp8 append
             self.range_row0 = _to_dev(np.arange(self.T + 1, dtype=np.int32), self.device)
+            # and as one row per sequence in batch order (zeros where nothing is staged), for the call that appends and attends
+            if wl.k_new.dtype == np.uint16 and wl.kv_dtype == "bf16":
+                full_k = np.zeros((wl.batch,) + wl.k_new.shape[1:], np.uint16)
+                full_v = full_k.copy()
+                full_k[wl.seq_ids], full_v[wl.seq_ids] = wl.k_new, wl.v_new
+                self.k_new_rows, self.v_new_rows = _to_dev(full_k, self.device), _to_dev(full_v, self.device)
         self.group_start = self.shared_len = None
         self.num_groups = self.max_group_size = self.max_shared_len = 0
         if getattr(wl, "group_start", None) is not None:
@@ -82,6 +88,14 @@ class DeviceWorkload:
         sd.paged_decode_attention(self.shape, self.q, self.k_pages, self.v_pages, self.k_scales, self.v_scales,
                                   self.block_table, self.context_lens, self.scale, out, self.workspace,
                                   self.ws_bytes, stream, timer)
+        return out
+
+    def append_and_attend(self, stream=None, timer=None, out=None):
+        """One call: the staged newest tokens (one per sequence, in batch order) go into the pool and are attended."""
+        out = self.out if out is None else out
+        sd.paged_decode_attention_append(self.shape, self.q, self.k_new_rows, self.v_new_rows, self.k_pages, self.v_pages,
+                                         self.block_table, self.context_lens, self.scale, out, self.workspace,
+                                         self.ws_bytes, stream, timer)
         return out
 
     def attend_prefix(self, stream=None, timer=None, out=None):

@@ -232,6 +232,47 @@ def test_kv_append_is_bit_exact_and_append_then_attend_matches(sd):
     check(out.cpu().numpy(), oracle_full(wl, k_ref, v_ref))
 
 
+@pytest.mark.parametrize("Hq,Hkv,d", [(8, 2, 128), (28, 4, 128), (8, 1, 64), (32, 1, 128)])
+@pytest.mark.parametrize("min_range", [0, 256, 4096])
+def test_append_and_attend_in_one_call(sd, Hq, Hkv, d, min_range):
+    """paged_decode_attention_append = kv_append of every sequence's newest token + attention over it: pool bytes equal
+    the oracle's append bit for bit, the output matches the oracle run over the appended pool.  Lengths put the
+    newest token first in its page, last in its page, alone in the sequence, first of a new tile; one sequence is
+    empty.  Ranges of 4096 tokens cover every sequence, which takes the path that launches the append separately."""
+    import torch
+    lens = [1, 2, 16, 17, 32, 33, 34, 0, 64, 65, 513, 700, 1025, 1]
+    wl = workloads.make_custom(lens, Hq, Hkv, d, seed=500 + Hq + d, append=True)
+    dw = device_workload(wl, chunk_tokens=min_range)
+    dw.out.fill_(float("nan"))
+    out = dw.append_and_attend()
+    torch.cuda.synchronize()
+    k_ref, v_ref = wl.k_pages.copy(), wl.v_pages.copy()
+    oracle.kv_append(wl.k_new, wl.v_new, wl.seq_ids, wl.positions, k_ref, v_ref, wl.block_table)
+    k_gpu, v_gpu = dw.pools_to_host()
+    assert np.array_equal(k_gpu, k_ref) and np.array_equal(v_gpu, v_ref)
+    got = out.cpu().numpy()
+    check(got, oracle_full(wl, k_ref, v_ref))
+    assert not got[7].any()
+    # a sequence of one token returns that token's V row exactly
+    V = workloads.bf16_bits_to_f32(wl.v_new)
+    for b in (0, 13):
+        j = int(np.nonzero(wl.seq_ids == b)[0][0])
+        for h in range(Hq):
+            assert np.array_equal(got[b, h], V[j, h // (Hq // Hkv)])
+    # and the pool now serves the plain call with the same result up to rounding order
+    plain = dw.attend().cpu().numpy()
+    assert np.abs(got - plain).max() <= ALARM_ABS + ALARM_REL * np.abs(plain).max()
+
+
+def test_append_and_attend_rejects_fp8_pools(sd):
+    wl = workloads.make_custom([40, 17], 16, 2, 128, "fp8", seed=501)
+    dw = device_workload(wl)
+    with pytest.raises(sd.SeamDecodeError) as e:
+        sd.paged_decode_attention_append(dw.shape, dw.q, dw.q, dw.q, dw.k_pages, dw.v_pages, dw.block_table,
+                                         dw.context_lens, dw.scale, dw.out, dw.workspace, dw.ws_bytes)
+    assert e.value.code == -2
+
+
 def test_pool_built_token_by_token_with_kv_append(sd):
     """Resume: rebuild a paused sequence's cache from its stored rows, then attend."""
     import torch
@@ -316,9 +357,18 @@ def oracle_all_rows(wl, k_pages=None, v_pages=None, k_scales=None, v_scales=None
 
 @pytest.mark.parametrize("cfg", [1, 2])
 def test_full_size_config_every_row(sd, cfg):
-    wl = workloads.make_config(cfg)
-    got = gpu_attend(wl, balance_for_batch=True)  # the launch configuration bench.py times
-    check(got, oracle_all_rows(wl))
+    """The step bench.py times at these workloads: one call that appends every sequence's newest token and attends."""
+    import torch
+    wl = workloads.make_config(cfg, append=True)
+    dw = device_workload(wl)
+    out = dw.append_and_attend()
+    torch.cuda.synchronize()
+    oracle.kv_append(wl.k_new, wl.v_new, wl.seq_ids, wl.positions, wl.k_pages, wl.v_pages, wl.block_table)  # in place on the host copy
+    k_gpu, v_gpu = dw.pools_to_host()
+    assert np.array_equal(k_gpu, wl.k_pages) and np.array_equal(v_gpu, wl.v_pages)
+    ref = oracle_all_rows(wl)
+    check(out.cpu().numpy(), ref)
+    check(dw.attend().cpu().numpy(), ref)   # the plain call over the same pool
 
 
 def test_full_size_branching_mix_with_append(sd):
