@@ -115,9 +115,11 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(2, 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int Hv = a.Hkv * a.HB;
     // head fastest over the grid: neighbouring workgroups (they run on different dies) walk the same
-    // pages at the same pace, each reading its own head's tiles of them
-    const int gv = blockIdx.x % Hv;
-    const int rblock = blockIdx.x / Hv;
+    // pages at the same pace, each reading its own head's tiles of them; where the heads share lines
+    // (fp8 scales) one die takes all heads of a range block instead
+    const unsigned item = P::kDealByDie ? xcd_deal(blockIdx.x, gridDim.x, Hv) : blockIdx.x;
+    const int gv = item % Hv;
+    const int rblock = item / Hv;
     const HeadBlock hb = head_block(gv, a.G, a.HB);
 
     // the newest token of every sequence comes as a row of k_new / v_new and goes into the pool from here

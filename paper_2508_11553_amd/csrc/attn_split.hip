@@ -163,8 +163,8 @@ __global__ __launch_bounds__(kWaves * 64, 2) void split_kernel(SplitArgs a)
     // walks the chunks of every sequence from the front, aligned at the END: its last rows
     // hold every sequence's last chunk, which is the short one, so the workgroups that run
     // while the machine drains are the small ones.
-    const unsigned item = blockIdx.x - a.group_items;
     const int Hv = a.Hkv * a.HB;
+    const unsigned item = P::kDealByDie ? xcd_deal(blockIdx.x - a.group_items, gridDim.x - a.group_items, Hv) : blockIdx.x - a.group_items;
     const HeadBlock hb = head_block(item % Hv, a.G, a.HB);
     const int g = hb.g;
     const int b = (item / Hv) % a.B;

@@ -214,6 +214,7 @@ struct Bf16Path {
     // The newest token of a sequence handed over as rows instead of pool bytes (the decode step that
     // appends and attends in one go): row pieces in the lanes that would hold token 0 of a tile.
     static constexpr bool kAppendInPlace = true;
+    static constexpr bool kDealByDie = false;   // the heads of a sequence share no lines worth keeping together
     struct NewRow {
         u32x4 k;            // lanes < kPieces: 16 bytes of the K row
         u32x2 v[D / 64];    // lanes < 16: V row, d = 64*half + 4*lane .. +4
@@ -476,6 +477,7 @@ struct Fp8Path {
 
     // fp8 pools take new tokens through kv_append_fp8 (a page's scale may have to change)
     static constexpr bool kAppendInPlace = false;
+    static constexpr bool kDealByDie = true;    // the scales of a page's heads lie in one line: one die takes all heads of a sequence
     struct NewRow {};
     SD_DEV static NewRow load_new_row(const uint16_t *, const uint16_t *, int) { return NewRow{}; }
     SD_DEV static void store_new_row(const NewRow &, uint16_t *, uint16_t *, int) {}

@@ -31,6 +31,18 @@ __host__ __device__ inline HeadBlock head_block(int gv, int G, int HB)
 // Sequences (decode) or query tokens (causal pass) that share one 16-row column block.
 __host__ __device__ inline int units_per_block(int G) { return G <= kMaxGroup / 2 ? kMaxGroup / G : 1; }
 constexpr int kXcds = 8;            // accelerator dies, each with its own L2; workgroup i runs on die i % 8
+// Deal of a grid's items to the dies.  Items i and i + 1 differ in the head (head fastest, `Hv` of
+// them) and would run on different dies; lines that the heads of one sequence have in common (the
+// scales of a page's heads lie in one line, so do its block-table entries) would then be fetched
+// once per die.  Within every run of 8 * Hv items this hands the Hv items of one sequence to one
+// die, one after the other; a ragged last run stays as it is.  A bijection of [0, n).
+__device__ inline unsigned xcd_deal(unsigned i, unsigned n, unsigned Hv)
+{
+    const unsigned run = kXcds * Hv;
+    const unsigned k = i / run, j = i - k * run;
+    if ((k + 1) * run > n) return i;
+    return k * run + (j % kXcds) * Hv + j / kXcds;
+}
 constexpr int kPrefillBlocks = 2;   // 16-row column blocks one wave of the causal pass carries
 
 // Chunk slots of one output row.  Without a shared prefix, chunk c covers tokens
