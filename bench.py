@@ -168,7 +168,7 @@ def prefill_main(args):
 
     import paper_2508_11553_amd as sd
     import workloads
-    from paper_2508_11553_amd.device import DeviceWorkload, _to_dev
+    from device_workload import DeviceWorkload, _to_dev
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     sd.load()
@@ -247,7 +247,7 @@ def bulk_append_main(args):
     import paper_2508_11553_amd as sd
     import workloads
     from paper_2508_11553_amd import binding
-    from paper_2508_11553_amd.device import DeviceWorkload, _to_dev
+    from device_workload import DeviceWorkload, _to_dev
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     sd.load()
@@ -332,7 +332,7 @@ def run_config(cfg, args):
     import paper_2508_11553_amd as sd
     import workloads
     from paper_2508_11553_amd.binding import probe_read, probe_sink_words
-    from paper_2508_11553_amd.device import DeviceWorkload
+    from device_workload import DeviceWorkload
     from workloads.gen import draw_extra_pool
 
     t_gen = time.perf_counter()

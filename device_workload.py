@@ -7,7 +7,7 @@ from __future__ import annotations
 import numpy as np
 import torch
 
-from . import binding as sd
+import paper_2508_11553_amd as sd
 
 
 def _to_dev(a: np.ndarray, device) -> torch.Tensor:

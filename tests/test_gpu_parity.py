@@ -30,7 +30,7 @@ def sd():
 
 
 def device_workload(wl, **kw):
-    from paper_2508_11553_amd.device import DeviceWorkload
+    from device_workload import DeviceWorkload
     return DeviceWorkload(wl, **kw)
 
 
@@ -125,7 +125,7 @@ def test_lengths_outside_the_bound_are_clamped(sd, chunk, kv_dtype):
     """context_lens above max_context_len count as max_context_len, negative ones as 0 (zero rows), in the
     path that cuts sequences across waves (ranges of 128 tokens) and with ranges that hold whole sequences."""
     import torch
-    from paper_2508_11553_amd.device import _to_dev
+    from device_workload import _to_dev
     true_lens = np.int32([40, 700, 513, 16, 300, 1500, 512])
     wl = workloads.make_custom(true_lens, 8, 2, 128, kv_dtype, seed=21)
     dw = device_workload(wl, chunk_tokens=chunk)
@@ -286,7 +286,7 @@ def test_pool_built_token_by_token_with_kv_append(sd):
         for t in range(L):
             p, s = wl.block_table[b, t // 16], t % 16
             rows_k.append(wl.k_pages[p, :, s]); rows_v.append(wl.v_pages[p, :, s]); seqs.append(b); poss.append(t)
-    from paper_2508_11553_amd.device import _to_dev
+    from device_workload import _to_dev
     kn, vn = _to_dev(np.stack(rows_k), dw.device), _to_dev(np.stack(rows_v), dw.device)
     si, po = _to_dev(np.int32(seqs), dw.device), _to_dev(np.int32(poss), dw.device)
     dw.k_pages.zero_(); dw.v_pages.zero_()
@@ -555,7 +555,7 @@ def _fp8_append_case(sd, ranges, Hkv=2, num_pages=12, seed=0, scales=(1.0,), pre
     """Run the same range append on the device and in the oracle; both start from the same pool."""
     import torch
     from paper_2508_11553_amd import binding
-    from paper_2508_11553_amd.device import _to_dev
+    from device_workload import _to_dev
     rng = np.random.default_rng(seed)
     d = 128
     nseq = max(r[0] for r in ranges) + 1
@@ -603,7 +603,7 @@ def test_fp8_append_encoder_matches_the_oracle_on_every_bf16_magnitude(sd):
     across every binade the format covers, including exact ties between neighbouring codes."""
     import torch
     from paper_2508_11553_amd import binding
-    from paper_2508_11553_amd.device import _to_dev
+    from device_workload import _to_dev
     d, Hkv = 128, 1
     vals = []
     for e in range(-12, 9):
@@ -634,7 +634,7 @@ def test_fp8_resume_then_attend(sd):
     the oracle run over the oracle-built pool."""
     import torch
     from paper_2508_11553_amd import binding
-    from paper_2508_11553_amd.device import _to_dev
+    from device_workload import _to_dev
     src = workloads.make_custom([700, 33, 1500], 16, 2, 128, "bf16", seed=30, poison=False)
     rows_k, rows_v = [], []
     for b, L in enumerate(src.context_lens):
@@ -675,7 +675,7 @@ def test_fp8_decode_step_append_then_attend(sd):
 # ---------------------------------------------------------------- table check
 def test_validate_tables_counts_what_a_launch_would_dereference(sd):
     import torch
-    from paper_2508_11553_amd.device import _to_dev
+    from device_workload import _to_dev
     wl = workloads.make_custom([40, 0, 513, 16, 700], 8, 2, 64, seed=70)
     dw = device_workload(wl)
     report = torch.full((4,), 77, dtype=torch.int32, device=dw.device)
@@ -702,7 +702,7 @@ def test_validate_tables_counts_what_a_launch_would_dereference(sd):
 def test_validate_groups_reports_inconsistent_group_arrays(sd):
     """Deliberately inconsistent group arrays go to the check only, never to the attention kernel."""
     import torch
-    from paper_2508_11553_amd.device import _to_dev
+    from device_workload import _to_dev
     sizes = [3, 5, 2]
     session_of = np.repeat(np.arange(3), sizes)
     prefix_len = np.repeat([64, 160, 32], sizes)
@@ -749,7 +749,7 @@ def test_decode_step_replays_from_a_hip_graph(sd):
         with torch.cuda.graph(graph, stream=stream):
             dw.append(); dw.attend()
     rng = np.random.default_rng(0)
-    from paper_2508_11553_amd.device import _to_dev
+    from device_workload import _to_dev
     for it in range(4):
         q = workloads.f32_to_bf16_bits(rng.standard_normal(wl.q.shape).astype(np.float32))
         kn = workloads.f32_to_bf16_bits(rng.standard_normal(wl.k_new.shape).astype(np.float32))

@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 def test_tree_tables_and_groups_feed_the_prefix_entry_point(sd):
     import torch
     from paper_2508_11553_amd import binding
-    from paper_2508_11553_amd.device import _to_dev
+    from device_workload import _to_dev
     from paper_2508_11553_amd.prefix_tree import PrefixTree
 
     rng = np.random.default_rng(0)
@@ -77,7 +77,7 @@ def test_tree_tables_and_groups_feed_the_prefix_entry_point(sd):
 def test_copy_pages_matches_the_oracle_bit_for_bit(sd, kv_dtype):
     import torch
     from paper_2508_11553_amd import binding
-    from paper_2508_11553_amd.device import DeviceWorkload, _to_dev
+    from device_workload import DeviceWorkload, _to_dev
 
     wl = workloads.make_custom([40, 70, 5, 130], 8, 4, 128, kv_dtype, seed=21, spare_pages=12)
     dw = DeviceWorkload(wl)
@@ -103,7 +103,7 @@ def test_a_session_branches_inside_a_page_and_decodes_on(sd):
     prefix-aware attention; every step is checked against the oracle run on the host copy of the pool."""
     import torch
     from paper_2508_11553_amd import binding
-    from paper_2508_11553_amd.device import _to_dev
+    from device_workload import _to_dev
     from paper_2508_11553_amd.prefix_tree import PrefixTree
 
     rng = np.random.default_rng(7)

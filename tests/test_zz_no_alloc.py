@@ -29,7 +29,7 @@ def sd():
 def both_entry_points(sd, wl, chunk):
     """-> (out of paged_decode_attention, out of paged_decode_attention_static), numpy."""
     import torch
-    from paper_2508_11553_amd.device import DeviceWorkload
+    from device_workload import DeviceWorkload
     dw = DeviceWorkload(wl, chunk_tokens=chunk)
     assert sd.workspace_bytes(dw.shape) <= 48 << 20
     want = dw.attend().clone()
