@@ -17,9 +17,12 @@
 //   - otherwise: leaves (max, sum, weighted sum) in a partial slot.  A piece has
 //     at most two such segments, its first and its last, so two slots per wave
 //     suffice.
-// range_merge_kernel then combines the partials of every sequence that was cut,
-// in range order, and writes those rows of `out`; it finds the cuts from the
-// tile offsets the range pass leaves in the workspace.
+// The four waves of a workgroup walk neighbouring pieces; parts of one sequence
+// that lie in neighbouring pieces of one workgroup are first added up through
+// LDS (see handed_over), so a sequence leaves at most one part per workgroup.
+// range_merge_kernel then combines the partials of every sequence that is still
+// cut, in range order, and writes those rows of `out`; it finds the cuts from
+// the tile offsets the range pass leaves in the workspace.
 //
 // Where the pieces fall depends on the lengths only (never on page placement),
 // which keeps results independent of the physical layout.
@@ -33,9 +36,40 @@ namespace sd {
 
 constexpr int kSeqsPerThread = kMaxRangeBatch / (kWaves * 64);
 
-// LDS scratch of one wave: the K image of a tile, or a whole partial ([16][D] floats) on its way out
+// LDS scratch of one wave: the K image of a tile, or a whole partial ([16][D] floats, then the rows'
+// maxima and weight sums) on its way out or on its way to a neighbouring wave
 template <class P>
-constexpr int wave_lds_bytes() { return P::kScratchBytes > kMaxGroup * P::kDim * 4 ? P::kScratchBytes : kMaxGroup * P::kDim * 4; }
+constexpr int wave_lds_bytes()
+{
+    return (P::kScratchBytes > kMaxGroup * P::kDim * 4 ? P::kScratchBytes : kMaxGroup * P::kDim * 4) + 2 * kMaxGroup * 4;
+}
+
+// Hand-over inside a workgroup.  The four waves of a workgroup walk neighbouring pieces (ranges 4i ..
+// 4i + 3).  When the LAST segment of a wave's piece began before the piece (then it is the piece's only
+// segment and continues the last segment of the wave before), and the wave is not the workgroup's first,
+// its result does not go to memory: it is handed through LDS to the wave before, which adds it to its own.
+// Such a run of waves leaves one partial (in the slot of its first wave) or, when it holds the whole
+// sequence, the finished rows.  Whether range r handed over its part of the sequence whose tiles are
+// [o0, o1) of a line of T tiles follows from the geometry alone, so the merge pass needs no marker.
+SD_DEV bool handed_over(int r, int o0, int o1, int T, int per)
+{
+    return r % kWaves != 0 && o0 < r * per && o1 >= min(T, (r + 1) * per);
+}
+// The ranges that still hold a part of a sequence spread over ranges r_first .. r_last: r_first, every
+// workgroup's first range in between, and r_last unless it handed over.
+struct LiveParts {
+    int r_first, r_last, first_lead, leads, count;
+    SD_DEV int range(int i) const { return i == 0 ? r_first : i <= leads ? first_lead + kWaves * (i - 1) : r_last; }
+};
+SD_DEV LiveParts live_parts(int o0, int o1, int T, int per)
+{
+    LiveParts p;
+    p.r_first = o0 / per, p.r_last = (o1 - 1) / per;
+    p.first_lead = (p.r_first / kWaves + 1) * kWaves;
+    p.leads = p.r_last > p.first_lead ? (p.r_last - 1 - p.first_lead) / kWaves + 1 : 0;   // multiples of 4 inside (r_first, r_last)
+    p.count = 1 + p.leads + (p.r_last > p.r_first && !handed_over(p.r_last, o0, o1, T, per) ? 1 : 0);
+    return p;
+}
 
 // Slot of the partial that range r holds for a sequence whose tiles start at line position o0:
 // the first segment of a range uses slot 0, a later one (it starts inside the range) slot 1.
@@ -44,15 +78,15 @@ SD_DEV int64_t partial_slot(int r, int gv, int Hv, int o0, int per)
     return ((int64_t)r * Hv + gv) * 2 + (o0 > r * per ? 1 : 0);
 }
 
-// Combines the partials that ranges r_first .. r_last hold for the `rows` query heads of one
+// Combines the partials that the ranges of `parts` hold for the `rows` query heads of one
 // (sequence, head block) and writes columns [col0, col0 + DW) of the rows of `out` starting at
 // row0.  One wave: the 64 lanes share the rows out (a row goes to 64 / R2 neighbouring lanes, R2 the
 // power of two >= rows, each lane a run of DW * R2 / 64 >= 4 floats) and PB partials are fetched at
 // a time, all loads in flight together, so up to PB partials cost one trip to memory.  Partials
 // are folded in range order with a running maximum.
 template <int PB, int NL_MAX>
-SD_DEV void combine_parts(const RangeMergeArgs &a, int r_first, int r_last, int gv, int Hv, int o0, int per, int rows,
-                          int64_t row0, int D, int col0, int DW, int lane)
+SD_DEV void combine_parts(const RangeMergeArgs &a, const LiveParts &parts, int gv, int Hv, int o0, int per,
+                          int rows, int64_t row0, int D, int col0, int DW, int lane)
 {
     const int R2 = rows > 8 ? 16 : rows > 4 ? 8 : rows > 2 ? 4 : rows > 1 ? 2 : 1;
     const int lpr = min(64 / R2, DW / 4);   // lanes per row
@@ -64,13 +98,13 @@ SD_DEV void combine_parts(const RangeMergeArgs &a, int r_first, int r_last, int 
     f32x4 num[NL_MAX];
 #pragma unroll
     for (int j = 0; j < NL_MAX; ++j) num[j] = f32x4{0, 0, 0, 0};
-    for (int base = r_first; base <= r_last; base += PB) {
+    for (int base = 0; base < parts.count; base += PB) {
         float m[PB], l[PB];
         f32x4 v[PB][NL_MAX];
 #pragma unroll
         for (int p = 0; p < PB; ++p) {
-            const bool valid = base + p <= r_last;   // wave-uniform
-            const int64_t ps = partial_slot(valid ? base + p : r_last, gv, Hv, o0, per);
+            const bool valid = base + p < parts.count;   // wave-uniform
+            const int64_t ps = partial_slot(parts.range(valid ? base + p : 0), gv, Hv, o0, per);
             m[p] = valid ? a.ws_m[ps * kMaxGroup + mr] : -INFINITY;
             l[p] = valid ? a.ws_l[ps * kMaxGroup + mr] : 0.f;
             const f32x4 *src = reinterpret_cast<const f32x4 *>(a.ws_acc + (ps * a.rows_stride + mr) * D + col0 + c * F);
@@ -190,14 +224,10 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(2, 
     const int r = rblock * kWaves + wave;
     const int g0 = r * per;
     const int g1 = min(T, g0 + per);
-    // which sequence the merge pass combines on behalf of this range: the one whose FIRST part lies here
-    int4 merge_rec = {-1, 0, 0, 0};
-    if (g0 >= g1) {
-        if (!PROBE && lane == 0) a.merge_rec[(int64_t)r * Hv + gv] = int4{-1, 0, 0, 0};
-        return;
-    }
-    int b_first;
-    {   // the sequence that holds tile g0: the last b with tile_off[b] <= g0
+    const bool has = g0 < g1;   // a wave past the end of the line only takes part in the hand-over's barrier
+    if (PROBE && !has) return;
+    int b_first = 0;
+    if (has) {   // the sequence that holds tile g0: the last b with tile_off[b] <= g0
         int lo = 0, hi = a.B;  // tile_off[hi] = T > g0
         while (lo < hi) {
             const int mid = (lo + hi) >> 1;
@@ -228,8 +258,9 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(2, 
     u32x4 qop[D / 32];
     typename P::State st;
     // a finished segment: the whole sequence -> `out`; a part of one -> this wave's partial slot
-    auto finish = [&](const Segment &sg) {
-        const float l = head_sum(st.l);  // the four lanes of a head hold disjoint shares of the weight sum
+    // (l: the rows' weight sums; the four lanes of a head hold disjoint shares of st.l)
+    auto finish = [&](const auto &sg, float l, int lane) {
+        const int n = lane & 15, qd = lane >> 4;
         if (sg.lt0 == 0 && sg.lt1 == sg.o1 - sg.o0) {
             if (n < hb.rows) {
 #pragma unroll
@@ -244,20 +275,21 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(2, 
         P::store_acc(st, reinterpret_cast<float *>(s_k) + n * D, qd);
         wave_lds_fence();
         char *dst = reinterpret_cast<char *>(a.ws_acc + slot * a.rows_stride * D);
+        const int image_bytes = __builtin_amdgcn_readfirstlane(hb.rows * D * 4);
 #pragma unroll
         for (int j = 0; j < kMaxGroup * D * 4 / 1024; ++j)
-            if (j * 1024 + lane * 16 < hb.rows * D * 4)
+            if (j * 1024 + lane * 16 < image_bytes)
                 *reinterpret_cast<u32x4 *>(dst + j * 1024 + lane * 16) = *reinterpret_cast<const u32x4 *>(s_k + j * 1024 + lane * 16);
         wave_lds_fence();
         if (lane < hb.rows) {   // lane n < 16 holds row n's max and weight sum (qd == 0)
             a.ws_m[slot * kMaxGroup + lane] = st.m;
             a.ws_l[slot * kMaxGroup + lane] = l;
         }
-        // a sequence that is cut gets merged where its first part lies
-        if (sg.lt0 == 0) merge_rec = int4{sg.b, sg.o0, sg.o1, T};
     };
 
-    for (int b = b_first; b < a.B; ++b) {
+    struct { int b, lt0, lt1, o0, o1; } last = {0, 0, 0, 0, 0};   // the piece's last segment is finished after the loop
+    bool open = false;                                            // ... if there is one
+    for (int b = b_first; has && b < a.B; ++b) {
         if (__builtin_amdgcn_readfirstlane(tile_off[b]) >= g1) break;
         if (__builtin_amdgcn_readfirstlane(tile_off[b + 1]) == __builtin_amdgcn_readfirstlane(tile_off[b])) continue;
         const Segment sg = open_segment(b);
@@ -273,14 +305,23 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(2, 
         for (int s = 0; s < D / 32; ++s)
             qop[s] = n < hb.rows ? *reinterpret_cast<const u32x4 *>(a.q + row * D + P::q_offset(s, lane)) : u32x4{0, 0, 0, 0};
         reset(st);
-        // the segment that ends its sequence also takes the newest token, which is not in the pool yet; its
-        // rows are requested now so that they are there when the walk is over
+        // the segment that ends its sequence also takes the newest token, which is not in the pool yet.  Its
+        // rows are fetched after the walk (eight registers less to carry through it); four lanes touch their
+        // lines now, so that the fetch finds them in the cache
         const bool newest = fused && sg.lt1 == sg.o1 - sg.o0;   // wave-uniform
-        typename P::NewRow nr;
         const int64_t new_at = ((int64_t)b * a.Hkv + hb.g) * D;
-        if (newest) nr = P::load_new_row(a.k_new + new_at, a.v_new + new_at, lane);
+        unsigned touched = 0;
+        if (newest && lane < 4 && (lane & 1) * 64 < D)
+            touched = *reinterpret_cast<const unsigned *>((lane < 2 ? a.k_new : a.v_new) + new_at + (lane & 1) * 64);
         stream_tiles<P, true>(a, bt, hb.g, t0, t1, 0, 1, qop, st, s_k, lane);
+        // What follows the walk forms its addresses from this copy of the lane number, i.e. here and not
+        // ahead of the walk, where they would only occupy registers.  (Not volatile and no memory clobber:
+        // either would make the block-table reads of the next segment vector loads; the dependence on the
+        // walk's result keeps it in place.)
+        int lane_after = lane;
+        asm("" : "+v"(lane_after) : "v"(touched), "v"(st.m));
         if (newest) {
+            const typename P::NewRow nr = P::load_new_row(a.k_new + new_at, a.v_new + new_at, lane_after);
             typename P::Tile t;
             P::new_row_tile(t, nr);
             u32x4 ka[D / 32], kb[D / 32];
@@ -291,10 +332,15 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(2, 
             P::attend(ka, kb, t, qop, st, a.scale_log2e, sg.L, sg.L + 1, lane);   // one token, at position L - 1 of the sequence
             if (gv % a.HB == 0) {   // one of the head blocks of this KV head puts the rows into the pool
                 const int64_t at = ((int64_t)sg.row[sg.L / kPage] * a.Hkv + hb.g) * (kPage * D) + (sg.L % kPage) * D;
-                P::store_new_row(nr, a.k_pages_out + at, a.v_pages_out + at, lane);
+                P::store_new_row(nr, a.k_pages_out + at, a.v_pages_out + at, lane_after);
             }
         }
-        finish(sg);
+        if (sg.o0 + sg.lt1 == g1) {
+            last = {sg.b, sg.lt0, sg.lt1, sg.o0, sg.o1};
+            open = true;
+            break;
+        }
+        finish(sg, head_sum(st.l), lane_after);
     }
     if (PROBE) {
         unsigned f = fold[0] ^ fold[1] ^ fold[2] ^ fold[3];
@@ -303,7 +349,50 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(2, 
         if (lane == 0) a.sink[(int64_t)r * Hv + gv] = f;
         return;
     }
-    if (lane == 0) a.merge_rec[(int64_t)r * Hv + gv] = merge_rec;
+    // ---- hand-over inside the workgroup (see handed_over), then the last segment's result leaves.
+    // (The lane number passes through an empty asm so that the addresses below are formed here and not
+    // ahead of the walk, where they would only occupy registers.)
+    __shared__ int s_link[kWaves][2];   // lt0 (< 0: the wave has no tiles) and lt1 of each wave's last segment
+    int lane_now;   // the lane number once more, produced here so that nothing has to be kept for it
+    asm("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(lane_now) : "v"(open ? st.m : 0.f));
+    const int n_now = lane_now & 15, qd_now = lane_now >> 4;
+    float *image = reinterpret_cast<float *>(s_k);
+    float l = open ? head_sum(st.l) : 0.f;
+    const bool hands_over = open && wave > 0 && last.lt0 > 0;
+    if (lane_now == 0) {
+        s_link[wave][0] = open ? last.lt0 : -1;
+        s_link[wave][1] = last.lt1;
+    }
+    if (hands_over) {
+        P::store_acc(st, image + n_now * D, qd_now);
+        if (qd_now == 0) {
+            image[kMaxGroup * D + n_now] = st.m;
+            image[kMaxGroup * D + kMaxGroup + n_now] = l;
+        }
+    }
+    __syncthreads();
+    if (open && !hands_over) {
+        for (int w = wave + 1; w < kWaves && __builtin_amdgcn_readfirstlane(s_link[w][0]) > 0; ++w) {   // in range order
+            const float *theirs = reinterpret_cast<const float *>(lds + w * wave_lds_bytes<P>());
+            const float m2 = theirs[kMaxGroup * D + n_now], l2 = theirs[kMaxGroup * D + kMaxGroup + n_now];
+            const float m_new = fmaxf(st.m, m2);
+            const float c1 = __builtin_amdgcn_exp2f(st.m - m_new), c2 = __builtin_amdgcn_exp2f(m2 - m_new);
+            f32x4 acc2[D / 16];
+            P::load_acc(acc2, theirs + n_now * D, qd_now);
+#pragma unroll
+            for (int k = 0; k < D / 16; ++k) st.acc[k] = st.acc[k] * c1 + acc2[k] * c2;
+            l = l * c1 + l2 * c2;
+            st.m = m_new;
+            last.lt1 = __builtin_amdgcn_readfirstlane(s_link[w][1]);
+        }
+        finish(last, l, lane_now);
+    }
+    // Which sequence the merge pass combines on behalf of this range: the one whose FIRST part lies here and
+    // that does not end here.  Only a piece's last segment can be that (an earlier one that starts inside the
+    // piece also ends inside it).
+    const bool first_part = open && !hands_over && last.lt0 == 0 && last.lt1 < last.o1 - last.o0;
+    if (lane_now == 0)
+        a.merge_rec[(int64_t)r * Hv + gv] = first_part ? int4{last.b, last.o0, last.o1, T} : int4{-1, 0, 0, 0};
 }
 
 // Merge pass of the range design.  A sequence that one range held whole was written by the wave
@@ -328,14 +417,16 @@ __global__ __launch_bounds__(128) void range_merge_kernel(RangeMergeArgs a)
         if (b < 0) return;
     }
     const int per = max((T + a.ranges - 1) / a.ranges, a.min_tiles);
-    const int r_first = o0 / per, r_last = (o1 - 1) / per;
-    if (r_first == r_last) return;
+    // parts that were handed over inside a workgroup are in their neighbour's; a sequence with a single part
+    // left was written by the wave that held it
+    const LiveParts parts = live_parts(o0, o1, T, per);
+    if (parts.count == 1) return;
     const HeadBlock hb = head_block(gv, a.G, a.HB);
     const int64_t row0 = (int64_t)b * a.Hq + hb.head0;
     if (hb.rows > kMaxGroup / 2)
-        combine_parts<8, D / 32>(a, r_first, r_last, gv, Hv, o0, per, hb.rows, row0, D, half * (D / 2), D / 2, lane);
+        combine_parts<8, D / 32>(a, parts, gv, Hv, o0, per, hb.rows, row0, D, half * (D / 2), D / 2, lane);
     else
-        combine_parts<16, (D / 64 > 0 ? D / 64 : 1)>(a, r_first, r_last, gv, Hv, o0, per, hb.rows, row0, D, half * (D / 2), D / 2, lane);
+        combine_parts<16, (D / 64 > 0 ? D / 64 : 1)>(a, parts, gv, Hv, o0, per, hb.rows, row0, D, half * (D / 2), D / 2, lane);
 }
 
 hipError_t launch_range_merge(const RangeMergeArgs &a, int head_dim, hipStream_t stream, hipEvent_t start, hipEvent_t stop)

@@ -74,19 +74,29 @@ SD_DEV T kv_load(const T *p)
 // v_permlane16_swap exchanges rows 1<->0' and 3<->2' of its two operands and
 // v_permlane32_swap the upper half of one with the lower half of the other;
 // fed the same value twice they return (x, x from the partner row/half).
+// (The two results are copied out of the pair before they are reinterpreted: a bit cast applied
+// directly to an element of the pair reads element 0 whichever element is named.)
 SD_DEV float head_max(float x)
 {
     const unsigned u = __builtin_bit_cast(unsigned, x);
     const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
-    const float y = fmaxf(__builtin_bit_cast(float, a[0]), __builtin_bit_cast(float, a[1]));
+    const unsigned a0 = a[0], a1 = a[1];
+    const float y = fmaxf(__builtin_bit_cast(float, a0), __builtin_bit_cast(float, a1));
     const unsigned w = __builtin_bit_cast(unsigned, y);
     const auto b = __builtin_amdgcn_permlane32_swap(w, w, false, false);
-    return fmaxf(__builtin_bit_cast(float, b[0]), __builtin_bit_cast(float, b[1]));
+    const unsigned b0 = b[0], b1 = b[1];
+    return fmaxf(__builtin_bit_cast(float, b0), __builtin_bit_cast(float, b1));
 }
 SD_DEV float head_sum(float x)
 {
-    x += __shfl_xor(x, 16, 64);
-    return x + __shfl_xor(x, 32, 64);
+    const unsigned u = __builtin_bit_cast(unsigned, x);
+    const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    const unsigned a0 = a[0], a1 = a[1];
+    const float y = __builtin_bit_cast(float, a0) + __builtin_bit_cast(float, a1);
+    const unsigned w = __builtin_bit_cast(unsigned, y);
+    const auto b = __builtin_amdgcn_permlane32_swap(w, w, false, false);
+    const unsigned b0 = b[0], b1 = b[1];
+    return __builtin_bit_cast(float, b0) + __builtin_bit_cast(float, b1);
 }
 
 // Keeps the compiler from moving this wave's LDS reads above its LDS writes
@@ -436,6 +446,18 @@ struct Bf16Path {
                 *reinterpret_cast<f32x4 *>(dst + 64 * h + 16 * qd + 4 * r) = o;
             }
     }
+    // the inverse: row `src` as this lane's accumulators would hold it
+    SD_DEV static void load_acc(f32x4 (&acc)[D / 16], const float *src, int qd)
+    {
+#pragma unroll
+        for (int h = 0; h < D / 64; ++h)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const f32x4 o = *reinterpret_cast<const f32x4 *>(src + 64 * h + 16 * qd + 4 * r);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc[4 * h + i][r] = o[i];
+            }
+    }
 };
 
 // ---------------------------------------------------------------------------
@@ -669,6 +691,19 @@ struct Fp8Path {
             *reinterpret_cast<f32x4 *>(dst + 32 * qd + 8 * r + 4) = hi;
         }
     }
+    SD_DEV static void load_acc(f32x4 (&acc)[8], const float *src, int qd)
+    {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const f32x4 lo = *reinterpret_cast<const f32x4 *>(src + 32 * qd + 8 * r);
+            const f32x4 hi = *reinterpret_cast<const f32x4 *>(src + 32 * qd + 8 * r + 4);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                acc[i][r] = lo[i];
+                acc[4 + i][r] = hi[i];
+            }
+        }
+    }
 };
 
 // LDS of one workgroup of the split pass.  Plain items: per-wave K scratch plus
@@ -702,10 +737,16 @@ SD_DEV void walk_tiles(const Args &a, const int32_t *bt, int g, int t0, int t1, 
     const int64_t page_bytes = (int64_t)P::kTileBytes * a.Hkv;
     const char *kbase = static_cast<const char *>(a.k_pages) + g * P::kTileBytes;
     const char *vbase = static_cast<const char *>(a.v_pages) + g * P::kTileBytes;
+    // The block table is never written while a kernel that walks it runs: it is read through the
+    // constant address space, which makes these reads scalar loads whatever else the kernel stores
+    // (as vector loads they would queue behind the tile loads and every wait for a page id would
+    // drain the tiles in flight).
+    typedef const __attribute__((address_space(4))) int32_t *ConstTable;
+    const ConstTable btc = (ConstTable)bt;
     auto page_ids = [&](int i, int &pa, int &pb) {
         const int ti = first + stride * min(i, nt - 1);
-        pa = bt[2 * ti];
-        pb = bt[min(2 * ti + 1, last_page)];
+        pa = btc[2 * ti];
+        pb = btc[min(2 * ti + 1, last_page)];
     };
     auto issue = [&](typename P::Tile &r, int pa, int pb) {
         P::template load_page<STREAM>(r, 0, kbase + pa * page_bytes, vbase + pa * page_bytes, a.k_scales, a.v_scales,

@@ -119,6 +119,41 @@ def test_whole_and_cut_sequences_in_one_launch(sd, kv_dtype, d, min_range):
     assert torch.equal(again, got)
 
 
+@pytest.mark.parametrize("Hq,Hkv,d,kv_dtype", [(8, 2, 128, "bf16"), (16, 1, 64, "bf16"), (8, 2, 128, "fp8"), (40, 2, 128, "bf16")])
+@pytest.mark.parametrize("min_range", [0, 128, 256, 384, 640])
+def test_parts_handed_over_inside_a_workgroup(sd, Hq, Hkv, d, kv_dtype, min_range):
+    """The four waves of a workgroup walk neighbouring ranges and hand their parts of one sequence to the first of
+    them through LDS.  Sequences of 1 .. 64 tiles against ranges of 1, 4, 8, 12 and 20 tiles put the sequence borders
+    at every position of a workgroup's four ranges: runs that hold a whole sequence (written directly), runs that leave one
+    part, runs that end because the next range holds a border, sequences spread over several workgroups."""
+    import torch
+    lens = [32 * k - (k % 3) for k in (1, 2, 3, 4, 5, 7, 8, 9, 12, 13, 16, 17, 23, 29, 31, 40, 47, 64)] + [1, 33, 0, 449, 97, 225, 31, 161]
+    wl = workloads.make_custom(lens, Hq, Hkv, d, kv_dtype, seed=77 + min_range + d)
+    dw = device_workload(wl, chunk_tokens=min_range)
+    dw.out.fill_(float("nan"))
+    got = dw.attend().clone()
+    torch.cuda.synchronize()
+    (check_fp8 if kv_dtype == "fp8" else check)(got.cpu().numpy(), oracle_full(wl))
+    dw.out.fill_(float("nan"))
+    assert torch.equal(dw.attend(), got)
+
+
+def test_more_sequences_than_ranges(sd):
+    """1300 short sequences: more than the grid has ranges per head, so the merge pass works from the records the
+    range pass leaves per range; ranges of twelve tiles cut many of the sequences, inside workgroups and between them."""
+    import torch
+    rng = np.random.default_rng(5)
+    lens = [int(x) for x in rng.integers(0, 600, size=1300)]
+    wl = workloads.make_custom(lens, 4, 2, 64, seed=78)
+    dw = device_workload(wl, chunk_tokens=128)
+    dw.out.fill_(float("nan"))
+    got = dw.attend().clone()
+    torch.cuda.synchronize()
+    check(got.cpu().numpy(), oracle_full(wl))
+    dw.out.fill_(float("nan"))
+    assert torch.equal(dw.attend(), got)
+
+
 @pytest.mark.parametrize("kv_dtype", ["bf16", "fp8"])
 @pytest.mark.parametrize("chunk", [128, 512])
 def test_lengths_outside_the_bound_are_clamped(sd, chunk, kv_dtype):
