@@ -70,6 +70,13 @@ SD_DEV T kv_load(const T *p)
     return *p;
 }
 
+// What a decode or prefill kernel only reads and nothing running beside it writes (the block table,
+// the fp8 scales) is read through the constant address space: that pins wave-uniform reads to scalar
+// loads whatever else the kernel stores.  As vector loads they would queue behind the tile loads,
+// and every wait for a page id or a scale would drain the tiles in flight.
+typedef const __attribute__((address_space(4))) int32_t *ConstTable;
+typedef const __attribute__((address_space(4))) float *ConstScales;
+
 // Reductions over the four lanes {n, n+16, n+32, n+48} that share a row.
 // v_permlane16_swap exchanges rows 1<->0' and 3<->2' of its two operands and
 // v_permlane32_swap the upper half of one with the lower half of the other;
@@ -493,8 +500,8 @@ struct Fp8Path {
         const char *vl = vp + (lane >> 4) * 4 * D + (lane & 15) * 8;
 #pragma unroll
         for (int j = 0; j < 4; ++j) r.v[pg][j] = kv_load<STREAM>(reinterpret_cast<const u32x2 *>(vl + j * D));
-        r.ks[pg] = ks[si];
-        r.vs[pg] = vs[si];
+        r.ks[pg] = ((ConstScales)ks)[si];
+        r.vs[pg] = ((ConstScales)vs)[si];
     }
 
     // fp8 pools take new tokens through kv_append_fp8 (a page's scale may have to change)
@@ -737,11 +744,6 @@ SD_DEV void walk_tiles(const Args &a, const int32_t *bt, int g, int t0, int t1, 
     const int64_t page_bytes = (int64_t)P::kTileBytes * a.Hkv;
     const char *kbase = static_cast<const char *>(a.k_pages) + g * P::kTileBytes;
     const char *vbase = static_cast<const char *>(a.v_pages) + g * P::kTileBytes;
-    // The block table is never written while a kernel that walks it runs: it is read through the
-    // constant address space, which makes these reads scalar loads whatever else the kernel stores
-    // (as vector loads they would queue behind the tile loads and every wait for a page id would
-    // drain the tiles in flight).
-    typedef const __attribute__((address_space(4))) int32_t *ConstTable;
     const ConstTable btc = (ConstTable)bt;
     auto page_ids = [&](int i, int &pa, int &pb) {
         const int ti = first + stride * min(i, nt - 1);
