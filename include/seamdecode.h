@@ -453,6 +453,22 @@ int paged_decode_attention_timed(const sd_shape *shape, const void *q,
                                  sd_timer *timer);
 
 /*
+ * sd_range_parts -- where the range pass of paged_decode_attention leaves the
+ * parts of one sequence (host only, no device access; for tests and for reading
+ * a profile).  Per KV head the batch's 32-token tiles form one line of
+ * `line_tiles` tiles, cut into ranges of `tiles_per_range` tiles (range r =
+ * tiles [r * tiles_per_range, (r + 1) * tiles_per_range)); the four ranges 4i ..
+ * 4i + 3 belong to one workgroup, whose waves add up neighbouring parts of one
+ * sequence before anything is stored.  For the sequence that occupies tiles
+ * [first_tile, end_tile) of the line, writes the ranges that still hold a part,
+ * ascending, to `ranges` (host, at most max_ranges entries) and returns their
+ * number; 1 means the range pass finished the sequence itself and the merge
+ * pass skips it.  SD_EINVAL for an empty or out-of-line sequence, a range size
+ * below 1, or a null `ranges` with max_ranges > 0.
+ */
+int sd_range_parts(int first_tile, int end_tile, int line_tiles, int tiles_per_range, int *ranges, int max_ranges);
+
+/*
  * sd_probe_read -- the kernel of paged_decode_attention with the arithmetic
  * taken out: same grid, same ranges, same loads of every K and V byte (and fp8
  * scale) the decode step must read, folded with XOR; one word per wave goes to

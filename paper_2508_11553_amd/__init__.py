@@ -24,6 +24,7 @@ from .binding import (  # noqa: F401
     paged_decode_attention_static,
     paged_prefill_attention,
     probe_read,
+    range_parts,
     strerror,
     validate_groups,
     validate_tables,

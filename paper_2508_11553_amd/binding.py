@@ -94,6 +94,8 @@ def load():
     L.sd_timer_reset.argtypes = [vp]
     L.sd_timer_read.restype = ctypes.c_int
     L.sd_timer_read.argtypes = [vp, vp, vp, i32]
+    L.sd_range_parts.restype = ctypes.c_int
+    L.sd_range_parts.argtypes = [i32, i32, i32, i32, vp, i32]
     L.sd_probe_sink_words.restype = sz
     L.sd_probe_sink_words.argtypes = [sp]
     L.sd_probe_read.restype = ctypes.c_int
@@ -280,6 +282,15 @@ def probe_read(shape: Shape, k_pages, v_pages, k_scales, v_scales, block_table, 
     rc = load().sd_probe_read(ctypes.byref(shape), _ptr(k_pages), _ptr(v_pages), _ptr(k_scales), _ptr(v_scales),
                               _ptr(block_table), _ptr(context_lens), _ptr(sink), _stream(stream))
     _check(rc, "sd_probe_read")
+
+
+def range_parts(first_tile: int, end_tile: int, line_tiles: int, tiles_per_range: int):
+    """sd_range_parts: the ranges that still hold a part of the sequence occupying tiles [first_tile, end_tile)."""
+    cap = max(1, (line_tiles + tiles_per_range - 1) // max(1, tiles_per_range))
+    buf = (ctypes.c_int * cap)()
+    n = load().sd_range_parts(first_tile, end_tile, line_tiles, tiles_per_range, buf, cap)
+    _check(min(n, 0), "sd_range_parts")
+    return list(buf[:n])
 
 
 def probe_sink_words(shape: Shape) -> int:

@@ -722,6 +722,16 @@ int sd_validate_groups(const sd_shape *shape, const int32_t *block_table, const 
     return e == hipSuccess ? SD_OK : hip_fail(e);
 }
 
+int sd_range_parts(int first_tile, int end_tile, int line_tiles, int tiles_per_range, int *ranges, int max_ranges)
+{
+    if (first_tile < 0 || end_tile <= first_tile || end_tile > line_tiles || tiles_per_range <= 0 || max_ranges < 0 ||
+        (max_ranges > 0 && !ranges))
+        return SD_EINVAL;
+    const sd::LiveParts parts = sd::live_parts(first_tile, end_tile, line_tiles, tiles_per_range);
+    for (int i = 0; i < parts.count && i < max_ranges; ++i) ranges[i] = parts.range(i);
+    return parts.count;
+}
+
 size_t sd_probe_sink_words(const sd_shape *shape)
 {
     if (check_shape(shape) || !range_pass_fits(shape)) return 0;

@@ -44,33 +44,6 @@ constexpr int wave_lds_bytes()
     return (P::kScratchBytes > kMaxGroup * P::kDim * 4 ? P::kScratchBytes : kMaxGroup * P::kDim * 4) + 2 * kMaxGroup * 4;
 }
 
-// Hand-over inside a workgroup.  The four waves of a workgroup walk neighbouring pieces (ranges 4i ..
-// 4i + 3).  When the LAST segment of a wave's piece began before the piece (then it is the piece's only
-// segment and continues the last segment of the wave before), and the wave is not the workgroup's first,
-// its result does not go to memory: it is handed through LDS to the wave before, which adds it to its own.
-// Such a run of waves leaves one partial (in the slot of its first wave) or, when it holds the whole
-// sequence, the finished rows.  Whether range r handed over its part of the sequence whose tiles are
-// [o0, o1) of a line of T tiles follows from the geometry alone, so the merge pass needs no marker.
-SD_DEV bool handed_over(int r, int o0, int o1, int T, int per)
-{
-    return r % kWaves != 0 && o0 < r * per && o1 >= min(T, (r + 1) * per);
-}
-// The ranges that still hold a part of a sequence spread over ranges r_first .. r_last: r_first, every
-// workgroup's first range in between, and r_last unless it handed over.
-struct LiveParts {
-    int r_first, r_last, first_lead, leads, count;
-    SD_DEV int range(int i) const { return i == 0 ? r_first : i <= leads ? first_lead + kWaves * (i - 1) : r_last; }
-};
-SD_DEV LiveParts live_parts(int o0, int o1, int T, int per)
-{
-    LiveParts p;
-    p.r_first = o0 / per, p.r_last = (o1 - 1) / per;
-    p.first_lead = (p.r_first / kWaves + 1) * kWaves;
-    p.leads = p.r_last > p.first_lead ? (p.r_last - 1 - p.first_lead) / kWaves + 1 : 0;   // multiples of 4 inside (r_first, r_last)
-    p.count = 1 + p.leads + (p.r_last > p.r_first && !handed_over(p.r_last, o0, o1, T, per) ? 1 : 0);
-    return p;
-}
-
 // Slot of the partial that range r holds for a sequence whose tiles start at line position o0:
 // the first segment of a range uses slot 0, a later one (it starts inside the range) slot 1.
 SD_DEV int64_t partial_slot(int r, int gv, int Hv, int o0, int per)

@@ -82,6 +82,34 @@ struct SplitArgs {
     int32_t grid_chunks;         // chunk slots the plain part of the grid spans (S, or S-1 without groups)
 };
 
+// Hand-over inside a workgroup.  The four waves of a workgroup walk neighbouring pieces (ranges 4i ..
+// 4i + 3).  When the LAST segment of a wave's piece began before the piece (then it is the piece's only
+// segment and continues the last segment of the wave before), and the wave is not the workgroup's first,
+// its result does not go to memory: it is handed through LDS to the wave before, which adds it to its own.
+// Such a run of waves leaves one partial (in the slot of its first wave) or, when it holds the whole
+// sequence, the finished rows.  Whether range r handed over its part of the sequence whose tiles are
+// [o0, o1) of a line of T tiles follows from the geometry alone, so the merge pass needs no marker.
+__host__ __device__ inline bool handed_over(int r, int o0, int o1, int T, int per)
+{
+    const int end = (r + 1) * per < T ? (r + 1) * per : T;
+    return r % kWaves != 0 && o0 < r * per && o1 >= end;
+}
+// The ranges that still hold a part of a sequence spread over ranges r_first .. r_last: r_first, every
+// workgroup's first range in between, and r_last unless it handed over.
+struct LiveParts {
+    int r_first, r_last, first_lead, leads, count;
+    __host__ __device__ int range(int i) const { return i == 0 ? r_first : i <= leads ? first_lead + kWaves * (i - 1) : r_last; }
+};
+__host__ __device__ inline LiveParts live_parts(int o0, int o1, int T, int per)
+{
+    LiveParts p;
+    p.r_first = o0 / per, p.r_last = (o1 - 1) / per;
+    p.first_lead = (p.r_first / kWaves + 1) * kWaves;
+    p.leads = p.r_last > p.first_lead ? (p.r_last - 1 - p.first_lead) / kWaves + 1 : 0;   // multiples of 4 inside (r_first, r_last)
+    p.count = 1 + p.leads + (p.r_last > p.r_first && !handed_over(p.r_last, o0, o1, T, per) ? 1 : 0);
+    return p;
+}
+
 // Arguments of the range pass (batches without shared prefixes).  Per (virtual) KV head the batch is one line of 32-token tiles (sequence after
 // sequence); the line is cut into `ranges` equal ranges and each wave walks one of them.
 constexpr int kMaxRangeBatch = 4096;  // sequences whose tile offsets fit the workgroup's LDS
