@@ -154,6 +154,23 @@ def test_more_sequences_than_ranges(sd):
     assert torch.equal(dw.attend(), got)
 
 
+@pytest.mark.parametrize("batch", [4096, 4097])
+def test_batches_at_the_limit_of_the_range_pass(sd, batch):
+    """4096 sequences is the most the range pass lays out in one workgroup's LDS; one more takes the chunked
+    passes.  Both sides of the limit against the oracle, with empty sequences and a few long ones among them."""
+    import torch
+    rng = np.random.default_rng(9)
+    lens = [int(x) for x in rng.integers(0, 90, size=batch)]
+    for i in (0, 17, batch - 1):
+        lens[i] = 700
+    wl = workloads.make_custom(lens, 4, 2, 64, seed=90)
+    dw = device_workload(wl, chunk_tokens=128)
+    dw.out.fill_(float("nan"))
+    got = dw.attend().clone()
+    torch.cuda.synchronize()
+    check(got.cpu().numpy(), oracle_full(wl))
+
+
 @pytest.mark.parametrize("kv_dtype", ["bf16", "fp8"])
 @pytest.mark.parametrize("chunk", [128, 512])
 def test_lengths_outside_the_bound_are_clamped(sd, chunk, kv_dtype):
