@@ -817,3 +817,38 @@ def test_decode_step_replays_from_a_hip_graph(sd):
     oracle.kv_append(kn, wl.v_new, wl.seq_ids, wl.positions, k, v, wl.block_table)
     wl.q = q
     check(got.cpu().numpy(), oracle_full(wl, k, v))
+
+
+def test_one_call_decode_step_replays_from_a_hip_graph(sd):
+    """The same for the decode step as ONE call (range pass that appends, then the merge pass): captured once,
+    replayed with new queries and new rows, compared with the eager call bit for bit and with the oracle."""
+    import torch
+    from device_workload import _to_dev
+    lens = [700, 33, 1500, 64, 1, 257]
+    wl = workloads.make_custom(lens, 8, 2, 128, seed=41, append=True)
+    dw = device_workload(wl, chunk_tokens=128)
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        dw.append_and_attend(stream)  # warm-up on the capture stream
+        stream.synchronize()
+        with torch.cuda.graph(graph, stream=stream):
+            dw.append_and_attend()
+    rng = np.random.default_rng(1)
+    for it in range(3):
+        q = workloads.f32_to_bf16_bits(rng.standard_normal(wl.q.shape).astype(np.float32))
+        kn = workloads.f32_to_bf16_bits(rng.standard_normal(wl.k_new.shape).astype(np.float32))
+        rows = np.zeros((wl.batch,) + kn.shape[1:], np.uint16)
+        rows[wl.seq_ids] = kn
+        dw.q.copy_(_to_dev(q, dw.device)); dw.k_new_rows.copy_(_to_dev(rows, dw.device))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = dw.out.clone()
+        dw.out.zero_()                      # eager work between replays
+        eager = dw.append_and_attend().clone()
+        torch.cuda.synchronize()
+        assert torch.equal(got, eager), f"replay {it} differs from the eager step"
+    k, v = wl.k_pages.copy(), wl.v_pages.copy()
+    oracle.kv_append(kn, wl.v_new, wl.seq_ids, wl.positions, k, v, wl.block_table)
+    wl.q = q
+    check(got.cpu().numpy(), oracle_full(wl, k, v))
