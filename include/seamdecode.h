@@ -65,7 +65,7 @@ typedef struct {
     int32_t num_q_heads;        /* Hq */
     int32_t num_kv_heads;       /* Hkv; Hq % Hkv == 0 and Hq / Hkv <= 64 (above 16 the K/V of a head
                                    is read once per block of 16 query heads, mostly from cache) */
-    int32_t head_dim;           /* 64 or 128 (fp8 pools: 128 only) */
+    int32_t head_dim;           /* 64 or 128 */
     int32_t page_size;          /* must be 16 */
     int32_t num_pages;          /* extent of the pools */
     int32_t max_blocks_per_seq; /* row stride of block_table */
@@ -126,7 +126,7 @@ int kv_append(const sd_shape *shape, const void *k_new, const void *v_new,
               void *k_pages, void *v_pages, const int32_t *block_table, void *stream);
 
 /*
- * kv_append_fp8 -- quantising append into SD_FP8_E4M3 pools (head_dim 128).
+ * kv_append_fp8 -- quantising append into SD_FP8_E4M3 pools (head_dim 64 or 128).
  *
  * Resuming a paused trajectory from its stored tokens (Data Plane: partial
  * rollout) rewrites whole stretches of a sequence's cache, and a decode step

@@ -46,7 +46,6 @@ int check_shape(const sd_shape *s)
         (s->chunk_tokens < 128 || s->chunk_tokens > 65536 || s->chunk_tokens % 128 != 0))
         return SD_EINVAL;
     if (s->head_dim != 64 && s->head_dim != 128) return SD_EUNSUPPORTED;
-    if (s->kv_dtype == SD_FP8_E4M3 && s->head_dim != 128) return SD_EUNSUPPORTED;
     if (s->num_q_heads / s->num_kv_heads > sd::kMaxGroup * sd::kMaxHeadBlocks) return SD_EUNSUPPORTED;
     return SD_OK;
 }
@@ -294,7 +293,7 @@ int kv_append_fp8(const sd_shape *shape, const void *k_new, const void *v_new, c
     if (tiles > 0x7fffffffull) return SD_EUNSUPPORTED;
     a.num_tiles = (uint32_t)tiles;
     a.single_rows = max_range_len == 1;
-    const hipError_t e = sd::launch_append_fp8(a, static_cast<hipStream_t>(stream));
+    const hipError_t e = sd::launch_append_fp8(a, shape->head_dim, static_cast<hipStream_t>(stream));
     if (e == hipErrorNotSupported) return SD_EUNSUPPORTED;
     return e == hipSuccess ? SD_OK : hip_fail(e);
 }

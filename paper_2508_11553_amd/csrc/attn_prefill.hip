@@ -163,6 +163,8 @@ hipError_t launch_prefill(const PrefillArgs &a, int head_dim, int kv_dtype, hipS
         go(prefill_kernel<Bf16Path<64>>);
     else if (kv_dtype == 1 && head_dim == 128)
         go(prefill_kernel<Fp8Path>);
+    else if (kv_dtype == 1 && head_dim == 64)
+        go(prefill_kernel<Fp8Path64>);
     else
         return hipErrorNotSupported;
     return hipGetLastError();

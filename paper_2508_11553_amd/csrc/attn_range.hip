@@ -209,7 +209,7 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(2, 
         b_first = lo - 1;
     }
     char *s_k = lds + wave * wave_lds_bytes<P>();
-    const int n = lane & 15, qd = lane >> 4;
+    const int n = lane & 15;
 
     // A segment: the tiles [lt0, lt1) of sequence b that lie in this wave's piece (all wave-uniform).
     struct Segment {
@@ -445,6 +445,9 @@ hipError_t launch_range(const RangeArgs &a, int head_dim, int kv_dtype, unsigned
     else if (kv_dtype == 1 && head_dim == 128)
         probe ? launch_range_one<Fp8Path, true>(a, grid, stream, start, stop)
               : launch_range_one<Fp8Path, false>(a, grid, stream, start, stop);
+    else if (kv_dtype == 1 && head_dim == 64)
+        probe ? launch_range_one<Fp8Path64, true>(a, grid, stream, start, stop)
+              : launch_range_one<Fp8Path64, false>(a, grid, stream, start, stop);
     else
         return hipErrorNotSupported;
     return hipGetLastError();

@@ -262,6 +262,8 @@ hipError_t launch_split(const SplitArgs &a, int head_dim, int kv_dtype, hipStrea
         launch_one<Bf16Path<64>>(a, g, b, stream, start, stop);
     else if (kv_dtype == 1 && head_dim == 128)
         launch_one<Fp8Path>(a, g, b, stream, start, stop);
+    else if (kv_dtype == 1 && head_dim == 64)
+        launch_one<Fp8Path64>(a, g, b, stream, start, stop);
     else
         return hipErrorNotSupported;
     return hipGetLastError();

@@ -713,6 +713,170 @@ struct Fp8Path {
     }
 };
 
+// ---------------------------------------------------------------------------
+// fp8 e4m3fn pools, head_dim 64: rows of 64 bytes, tiles of 1 KB.  The codes
+// are converted (exactly) into the register and LDS images the bf16 path of
+// head_dim 64 works with, and that path's operand code does the rest; the page
+// scales enter as in the 128-wide fp8 path (K scale on the scores, V scale on
+// the weights, weight sum over the rounded weights divided by the scale).
+// ---------------------------------------------------------------------------
+struct Fp8Path64 {
+    typedef Bf16Path<64> B;
+    static constexpr int D = 64;
+    static constexpr int kDim = D;
+    static constexpr int kTileBytes = kPage * D;             // one (page, head) tile of codes
+    static constexpr int kScratchBytes = B::kScratchBytes;   // K of one 32-token tile in LDS, as bf16
+    static constexpr int kOpsBytes = B::kOpsBytes + 16;      // four bf16 V^T operands and the four page scales
+    typedef WaveState<D> State;
+    typedef WaveState<D> ParkedState;
+
+    struct Tile {
+        u32x4 k[2];        // [page]: 16 codes at byte offset 16*lane of the K tile: row lane>>2, d = 16*(lane&3) .. +16
+        unsigned v[2][4];  // [page][j]: V row 4*(lane>>4)+j, d = 4*(lane&15) .. +4
+        float ks[2], vs[2];
+    };
+
+    SD_DEV static int q_offset(int s, int lane) { return B::q_offset(s, lane); }
+
+    template <bool STREAM>
+    SD_DEV static void load_page(Tile &r, int pg, const char *kp, const char *vp, const float *ks, const float *vs, int64_t si, int lane)
+    {
+        r.k[pg] = kv_load<STREAM>(reinterpret_cast<const u32x4 *>(kp + lane * 16));
+        const char *vl = vp + (lane >> 4) * 4 * D + (lane & 15) * 4;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) r.v[pg][j] = kv_load<STREAM>(reinterpret_cast<const unsigned *>(vl + j * D));
+        r.ks[pg] = ((ConstScales)ks)[si];
+        r.vs[pg] = ((ConstScales)vs)[si];
+    }
+
+    static constexpr bool kAppendInPlace = false;
+    static constexpr bool kDealByDie = true;
+    struct NewRow {};
+    SD_DEV static NewRow load_new_row(const uint16_t *, const uint16_t *, int) { return NewRow{}; }
+    SD_DEV static void store_new_row(const NewRow &, uint16_t *, uint16_t *, int) {}
+    SD_DEV static void new_row_tile(Tile &, const NewRow &) {}
+
+    SD_DEV static u32x4 fold(const Tile &r)
+    {
+        u32x4 f = r.k[0] ^ r.k[1];
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) f[j] ^= r.v[pg][j];
+        f[2] ^= __builtin_bit_cast(unsigned, r.ks[0]) ^ __builtin_bit_cast(unsigned, r.ks[1]);
+        f[3] ^= __builtin_bit_cast(unsigned, r.vs[0]) ^ __builtin_bit_cast(unsigned, r.vs[1]);
+        return f;
+    }
+
+    // four codes -> four bf16
+    SD_DEV static u32x2 cvt4(unsigned w) { return u32x2{cvt_pk_bf16_fp8<false>(w), cvt_pk_bf16_fp8<true>(w)}; }
+
+    // The lane's 16 codes are two 16-byte pieces of the bf16 row; they go where the bf16 path's k_store
+    // would have put them, so that its k_fetch reads them back.
+    SD_DEV static void k_store(const Tile &r, char *kslot, int lane)
+    {
+        const int row = lane >> 2;
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+                const u32x2 lo = cvt4(r.k[pg][2 * hh]), hi = cvt4(r.k[pg][2 * hh + 1]);
+                const int piece = (2 * (lane & 3) + hh) ^ (row % B::kPieces);
+                *reinterpret_cast<u32x4 *>(kslot + pg * B::kTileBytes + row * (D * 2) + piece * 16) = u32x4{lo[0], lo[1], hi[0], hi[1]};
+            }
+    }
+    SD_DEV static void k_fetch(const char *kslot, int lane, u32x4 (&ka)[2], u32x4 (&kb)[2]) { B::k_fetch(kslot, lane, ka, kb); }
+
+    // the V registers of the bf16 path (its K registers are not used)
+    SD_DEV static void v_to_bf16(const Tile &r, typename B::Tile &t)
+    {
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) t.v[pg][0][j] = cvt4(r.v[pg][j]);
+    }
+
+    SD_DEV static void attend(const u32x4 (&ka)[2], const u32x4 (&kb)[2], Tile &r, const u32x4 (&qop)[2], State &st,
+                              float scale_log2e, int tok0, int t_end, int lane)
+    {
+        const int qd = lane >> 4;
+        f32x4 sa = {0, 0, 0, 0}, sb = {0, 0, 0, 0};
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            sa = mfma_bf16_k32(ka[s], qop[s], sa);
+            sb = mfma_bf16_k32(kb[s], qop[s], sb);
+        }
+        const float ca = scale_log2e * r.ks[0], cb = scale_log2e * r.ks[1];
+        float x[8], p[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            x[e] = sa[e] * ca;
+            x[4 + e] = sb[e] * cb;
+        }
+        if (tok0 + kTileTokens > t_end) mask_scores(x, tok0, t_end, qd);  // wave-uniform
+        online_softmax(x, p, st);
+        const u32x4 pop = Fp8Path::weight_operand(p, r.vs[0], r.vs[1], st.l);
+        typename B::Tile t;
+        v_to_bf16(r, t);
+        B::v_sanitise(t, tok0, t_end, qd);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) st.acc[i] = mfma_bf16_k32(B::v_operand(t, 0, i), pop, st.acc[i]);
+    }
+
+    SD_DEV static void v_park(Tile &r, char *vslot, int lane, int tok0, int t_end)
+    {
+        typename B::Tile t;
+        v_to_bf16(r, t);
+        B::v_park(t, vslot, lane, tok0, t_end);
+        if (lane == 0) *reinterpret_cast<f32x4 *>(vslot + B::kOpsBytes) = f32x4{r.ks[0], r.ks[1], r.vs[0], r.vs[1]};
+    }
+
+    // as Fp8Path::attend_parked, with the four operands of head_dim 64
+    template <int NB>
+    SD_DEV static void attend_parked(const u32x4 (&ka)[2], const u32x4 (&kb)[2], const char *vslot,
+                                     const u32x4 (&qop)[NB][2], ParkedState (&st)[NB], float c, int tok0, int lane,
+                                     const int (&row_end)[NB], bool mask)
+    {
+        const int qd = lane >> 4;
+        const f32x4 sc = *reinterpret_cast<const f32x4 *>(vslot + B::kOpsBytes);  // k scales, v scales of the two pages
+        f32x4 sa[NB], sb[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) sa[b] = sb[b] = f32x4{0, 0, 0, 0};
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                sa[b] = mfma_bf16_k32(ka[s], qop[b][s], sa[b]);
+                sb[b] = mfma_bf16_k32(kb[s], qop[b][s], sb[b]);
+            }
+        const float ca = c * sc[0], cb = c * sc[1];
+        u32x4 pop[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            float x[8], p[8];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                x[e] = sa[b][e] * ca;
+                x[4 + e] = sb[b][e] * cb;
+            }
+            if (mask) mask_scores(x, tok0, row_end[b], qd);
+            online_softmax(x, p, st[b]);
+            pop[b] = Fp8Path::weight_operand(p, sc[2], sc[3], st[b].l);
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const u32x4 a = *reinterpret_cast<const u32x4 *>(vslot + k * 1024 + lane * 16);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) st[b].acc[k] = mfma_bf16_k32(a, pop[b], st[b].acc[k]);
+        }
+    }
+    SD_DEV static float weight_sum(const ParkedState &st) { return head_sum(st.l); }
+
+    template <class S>
+    SD_DEV static void store_acc(const S &st, float *dst, int qd) { B::store_acc(st, dst, qd); }
+    SD_DEV static void load_acc(f32x4 (&acc)[4], const float *src, int qd) { B::load_acc(acc, src, qd); }
+};
+
 // LDS of one workgroup of the split pass.  Plain items: per-wave K scratch plus
 // the merge buffers.  Shared items (and the causal pass): four tile slots (K
 // image + V^T operands), one filled by each wave and read by all.

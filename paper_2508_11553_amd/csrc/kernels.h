@@ -181,7 +181,7 @@ struct AppendArgs {
 };
 
 struct AppendFp8Args {
-    const uint4 *k_new, *v_new;  // [T][Hkv][128] bf16 viewed as 16-byte words
+    const uint4 *k_new, *v_new;  // [T][Hkv][d] bf16 viewed as 16-byte words
     const int32_t *range_seq, *range_start, *range_row0;  // [R], [R], [R+1]
     uint8_t *k_pages, *v_pages;
     float *k_scales, *v_scales;
@@ -226,7 +226,7 @@ hipError_t launch_merge(const MergeArgs &a, int head_dim, hipStream_t stream,
 hipError_t launch_prefill(const PrefillArgs &a, int head_dim, int kv_dtype, hipStream_t stream,
                           hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
 hipError_t launch_append(const AppendArgs &a, int head_dim, hipStream_t stream);
-hipError_t launch_append_fp8(const AppendFp8Args &a, hipStream_t stream);
+hipError_t launch_append_fp8(const AppendFp8Args &a, int head_dim, hipStream_t stream);
 hipError_t launch_copy_pages(const CopyPagesArgs &a, hipStream_t stream);
 hipError_t launch_validate(const ValidateArgs &a, hipStream_t stream);
 hipError_t launch_validate_groups(const ValidateGroupsArgs &a, hipStream_t stream);

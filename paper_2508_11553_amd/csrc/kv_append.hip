@@ -43,11 +43,11 @@ hipError_t launch_append(const AppendArgs &a, int head_dim, hipStream_t stream)
 }  // namespace sd
 
 // ---------------------------------------------------------------------------
-// Quantising append into fp8 e4m3fn pools (head_dim 128).
+// Quantising append into fp8 e4m3fn pools (head_dim 128 or 64).
 //
 // Rows arrive as ranges of consecutive positions of one sequence.  One
 // wave (four to a workgroup) owns one (range, page touched by the range, KV head, K or V) tile:
-// lane l handles 32 elements, slot l/4, d = 32*(l%4)..+32.
+// lane l handles a quarter of a row, slot l/4, d = (D/4)*(l%4)..+D/4.
 //   amax_new over the rows written into the tile        (wave max, exact)
 //   the tile's scale stays if the range starts inside the page and
 //   amax_new <= old_scale*448; otherwise scale = amax_new/448 (1 if 0) and the
@@ -73,9 +73,12 @@ __device__ __forceinline__ unsigned enc4(float a, float b, float c, float d)
     return w;
 }
 
+template <int D>
 __global__ __launch_bounds__(256) void append_fp8_kernel(AppendFp8Args a)
 {
-    constexpr int D = 128;
+    constexpr int E = D / 4;    // elements one lane handles: a quarter of a row
+    constexpr int NW = E / 8;   // 16-byte words of bf16 that is
+    constexpr int NC = E / 16;  // and 16-byte words of codes
     const int lane = threadIdx.x & 63;
     // four independent waves per workgroup (no barrier below), one tile each
     const unsigned tile_id = blockIdx.x * 4u + (threadIdx.x >> 6);
@@ -97,17 +100,17 @@ __global__ __launch_bounds__(256) void append_fp8_kernel(AppendFp8Args a)
     float *scale_p = (which ? a.v_scales : a.k_scales) + tile_index;
     const uint4 *src = which ? a.v_new : a.k_new;
 
-    // one wave per tile: lane -> slot lane/4, d = 32*(lane%4) .. +32
+    // one wave per tile: lane -> slot lane/4, d = (D/4)*(lane%4) .. +D/4
     const int slot = lane >> 2, quarter = lane & 3;
     const bool is_new = slot >= s0 && slot < s1;
-    float x[32];
+    float x[E];
 #pragma unroll
-    for (int i = 0; i < 32; ++i) x[i] = 0.f;
+    for (int i = 0; i < E; ++i) x[i] = 0.f;
     if (is_new) {
         const int64_t row = row0 + (p0 + slot - start);
-        const uint4 *p = src + (row * a.Hkv + g) * (D / 8) + quarter * 4;
+        const uint4 *p = src + (row * a.Hkv + g) * (D / 8) + quarter * NW;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < NW; ++j) {
             const uint4 w = p[j];
             x[8 * j + 0] = bf16_lo(w.x); x[8 * j + 1] = bf16_hi(w.x); x[8 * j + 2] = bf16_lo(w.y); x[8 * j + 3] = bf16_hi(w.y);
             x[8 * j + 4] = bf16_lo(w.z); x[8 * j + 5] = bf16_hi(w.z); x[8 * j + 6] = bf16_lo(w.w); x[8 * j + 7] = bf16_hi(w.w);
@@ -115,7 +118,7 @@ __global__ __launch_bounds__(256) void append_fp8_kernel(AppendFp8Args a)
     }
     float amax_new = 0.f;
 #pragma unroll
-    for (int i = 0; i < 32; ++i) amax_new = fmaxf(amax_new, fabsf(x[i]));
+    for (int i = 0; i < E; ++i) amax_new = fmaxf(amax_new, fabsf(x[i]));
     for (int off = 32; off > 0; off >>= 1) amax_new = fmaxf(amax_new, __shfl_xor(amax_new, off, 64));
 
     const float old_scale = s0 > 0 ? *scale_p : 0.f;
@@ -126,8 +129,8 @@ __global__ __launch_bounds__(256) void append_fp8_kernel(AppendFp8Args a)
     if (!keep) {
         if (slot < s0) {  // re-encode what the page already held
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const uint4 c = tile[slot * (D / 16) + quarter * 2 + j];
+            for (int j = 0; j < NC; ++j) {
+                const uint4 c = tile[slot * (D / 16) + quarter * NC + j];
                 const unsigned in[4] = {c.x, c.y, c.z, c.w};
                 unsigned o[4];
 #pragma unroll
@@ -135,32 +138,35 @@ __global__ __launch_bounds__(256) void append_fp8_kernel(AppendFp8Args a)
                     const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(in[w], false), hi = __builtin_amdgcn_cvt_pk_f32_fp8(in[w], true);
                     o[w] = enc4(lo[0] * ratio, lo[1] * ratio, hi[0] * ratio, hi[1] * ratio);
                 }
-                tile[slot * (D / 16) + quarter * 2 + j] = uint4{o[0], o[1], o[2], o[3]};
+                tile[slot * (D / 16) + quarter * NC + j] = uint4{o[0], o[1], o[2], o[3]};
             }
         }
         if (lane == 0) *scale_p = scale;  // every lane has read the old scale: one wave runs in lockstep
     }
     if (is_new) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
+        for (int j = 0; j < NC; ++j) {
             unsigned o[4];
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
                 const int e = 16 * j + 4 * w;
                 o[w] = enc4(x[e] / scale, x[e + 1] / scale, x[e + 2] / scale, x[e + 3] / scale);
             }
-            tile[slot * (D / 16) + quarter * 2 + j] = uint4{o[0], o[1], o[2], o[3]};
+            tile[slot * (D / 16) + quarter * NC + j] = uint4{o[0], o[1], o[2], o[3]};
         }
     }
 }
 
 // The decode step's form of the same operation: every range is a single row, so
-// a tile is touched in one slot only and 4 lanes (32 elements each) are enough
+// a tile is touched in one slot only and 4 lanes (a quarter of the row each) are enough
 // for it.  Lane group u = (range, KV head, K or V); 16 groups per wave.  Same
 // arithmetic, in the same order, as append_fp8_kernel.
+template <int D>
 __global__ __launch_bounds__(256) void append_fp8_row_kernel(AppendFp8Args a)
 {
-    constexpr int D = 128;
+    constexpr int E = D / 4;    // elements one lane handles: a quarter of a row
+    constexpr int NW = E / 8;   // 16-byte words of bf16 that is
+    constexpr int NC = E / 16;  // and 16-byte words of codes
     const unsigned gid = blockIdx.x * 256u + threadIdx.x;
     const unsigned unit = gid >> 2;
     const int quarter = gid & 3;
@@ -176,17 +182,17 @@ __global__ __launch_bounds__(256) void append_fp8_row_kernel(AppendFp8Args a)
     const int64_t tile_index = page * a.Hkv + g;
     uint4 *tile = reinterpret_cast<uint4 *>((which ? a.v_pages : a.k_pages) + tile_index * (kPage * D));
     float *scale_p = (which ? a.v_scales : a.k_scales) + tile_index;
-    const uint4 *p = (which ? a.v_new : a.k_new) + ((int64_t)row0 * a.Hkv + g) * (D / 8) + quarter * 4;
-    float x[32];
+    const uint4 *p = (which ? a.v_new : a.k_new) + ((int64_t)row0 * a.Hkv + g) * (D / 8) + quarter * NW;
+    float x[E];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < NW; ++j) {
         const uint4 w = p[j];
         x[8 * j + 0] = bf16_lo(w.x); x[8 * j + 1] = bf16_hi(w.x); x[8 * j + 2] = bf16_lo(w.y); x[8 * j + 3] = bf16_hi(w.y);
         x[8 * j + 4] = bf16_lo(w.z); x[8 * j + 5] = bf16_hi(w.z); x[8 * j + 6] = bf16_lo(w.w); x[8 * j + 7] = bf16_hi(w.w);
     }
     float amax_new = 0.f;
 #pragma unroll
-    for (int i = 0; i < 32; ++i) amax_new = fmaxf(amax_new, fabsf(x[i]));
+    for (int i = 0; i < E; ++i) amax_new = fmaxf(amax_new, fabsf(x[i]));
     amax_new = fmaxf(amax_new, __shfl_xor(amax_new, 1, 64));
     amax_new = fmaxf(amax_new, __shfl_xor(amax_new, 2, 64));
 
@@ -198,16 +204,16 @@ __global__ __launch_bounds__(256) void append_fp8_row_kernel(AppendFp8Args a)
     if (!keep) {
         // re-encode what the page already held: eight slots' loads in flight at a time
         for (int base = 0; base < s0; base += 8) {
-            uint4 c[8][2];
+            uint4 c[8][NC];
 #pragma unroll
             for (int i = 0; i < 8; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    if (base + i < s0) c[i][j] = tile[(base + i) * (D / 16) + quarter * 2 + j];
+                for (int j = 0; j < NC; ++j)
+                    if (base + i < s0) c[i][j] = tile[(base + i) * (D / 16) + quarter * NC + j];
 #pragma unroll
             for (int i = 0; i < 8; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
+                for (int j = 0; j < NC; ++j) {
                     if (base + i >= s0) continue;
                     const unsigned in[4] = {c[i][j].x, c[i][j].y, c[i][j].z, c[i][j].w};
                     unsigned o[4];
@@ -216,30 +222,37 @@ __global__ __launch_bounds__(256) void append_fp8_row_kernel(AppendFp8Args a)
                         const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(in[w], false), hi = __builtin_amdgcn_cvt_pk_f32_fp8(in[w], true);
                         o[w] = enc4(lo[0] * ratio, lo[1] * ratio, hi[0] * ratio, hi[1] * ratio);
                     }
-                    tile[(base + i) * (D / 16) + quarter * 2 + j] = uint4{o[0], o[1], o[2], o[3]};
+                    tile[(base + i) * (D / 16) + quarter * NC + j] = uint4{o[0], o[1], o[2], o[3]};
                 }
         }
         if (quarter == 0) *scale_p = scale;  // the group's four lanes read the old scale in the same instruction
     }
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+    for (int j = 0; j < NC; ++j) {
         unsigned o[4];
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
             const int e = 16 * j + 4 * w;
             o[w] = enc4(x[e] / scale, x[e + 1] / scale, x[e + 2] / scale, x[e + 3] / scale);
         }
-        tile[s0 * (D / 16) + quarter * 2 + j] = uint4{o[0], o[1], o[2], o[3]};
+        tile[s0 * (D / 16) + quarter * NC + j] = uint4{o[0], o[1], o[2], o[3]};
     }
 }
 
-hipError_t launch_append_fp8(const AppendFp8Args &a, hipStream_t stream)
+hipError_t launch_append_fp8(const AppendFp8Args &a, int head_dim, hipStream_t stream)
 {
     if (a.num_tiles == 0) return hipSuccess;
-    if (a.pages_per_range == 1 && a.single_rows)
-        hipLaunchKernelGGL(append_fp8_row_kernel, dim3((a.num_tiles + 63) / 64), dim3(256), 0, stream, a);
-    else
-        hipLaunchKernelGGL(append_fp8_kernel, dim3((a.num_tiles + 3) / 4), dim3(256), 0, stream, a);
+    const bool rows = a.pages_per_range == 1 && a.single_rows;
+    const dim3 grid(rows ? (a.num_tiles + 63) / 64 : (a.num_tiles + 3) / 4);
+    if (head_dim == 128) {
+        if (rows) hipLaunchKernelGGL(append_fp8_row_kernel<128>, grid, dim3(256), 0, stream, a);
+        else hipLaunchKernelGGL(append_fp8_kernel<128>, grid, dim3(256), 0, stream, a);
+    } else if (head_dim == 64) {
+        if (rows) hipLaunchKernelGGL(append_fp8_row_kernel<64>, grid, dim3(256), 0, stream, a);
+        else hipLaunchKernelGGL(append_fp8_kernel<64>, grid, dim3(256), 0, stream, a);
+    } else {
+        return hipErrorNotSupported;
+    }
     return hipGetLastError();
 }
 

@@ -99,7 +99,7 @@ def test_null_and_misaligned_pointers_are_rejected_before_any_launch(lib):
     s8 = good_shape(kv_dtype=sd.SD_FP8_E4M3, head_dim=128)
     args8 = list(args); args8[10] = sd.workspace_bytes(s8)
     assert lib.paged_decode_attention(ctypes.byref(s8), *args8) == -1  # fp8 needs scales
-    assert lib.sd_chunk_tokens(ctypes.byref(good_shape(kv_dtype=sd.SD_FP8_E4M3))) == -2  # fp8 with d=64
+    assert lib.sd_chunk_tokens(ctypes.byref(good_shape(kv_dtype=sd.SD_FP8_E4M3))) > 0    # fp8 with d=64
     assert lib.kv_append(ctypes.byref(s), None, 16, 16, 16, 3, 16, 16, 16, None) == -1
     assert lib.kv_append(ctypes.byref(s), 16, 16, 16, 16, -1, 16, 16, 16, None) == -1
     assert lib.kv_append(ctypes.byref(s8), 16, 16, 16, 16, 3, 16, 16, 16, None) == -2

@@ -96,7 +96,7 @@ def test_zero_length_sequences_give_zero_rows(sd):
     check(got, oracle_full(wl))
 
 
-@pytest.mark.parametrize("kv_dtype,d", [("bf16", 64), ("bf16", 128), ("fp8", 128)])
+@pytest.mark.parametrize("kv_dtype,d", [("bf16", 64), ("bf16", 128), ("fp8", 128), ("fp8", 64)])
 @pytest.mark.parametrize("min_range", [0, 128, 640, 4096])
 def test_whole_and_cut_sequences_in_one_launch(sd, kv_dtype, d, min_range):
     """Ranges of at least `min_range` tokens: from one tile per wave (every sequence cut into many partials
@@ -119,7 +119,7 @@ def test_whole_and_cut_sequences_in_one_launch(sd, kv_dtype, d, min_range):
     assert torch.equal(again, got)
 
 
-@pytest.mark.parametrize("Hq,Hkv,d,kv_dtype", [(8, 2, 128, "bf16"), (16, 1, 64, "bf16"), (8, 2, 128, "fp8"), (40, 2, 128, "bf16")])
+@pytest.mark.parametrize("Hq,Hkv,d,kv_dtype", [(8, 2, 128, "bf16"), (16, 1, 64, "bf16"), (8, 2, 128, "fp8"), (40, 2, 128, "bf16"), (8, 2, 64, "fp8")])
 @pytest.mark.parametrize("min_range", [0, 128, 256, 384, 640])
 def test_parts_handed_over_inside_a_workgroup(sd, Hq, Hkv, d, kv_dtype, min_range):
     """The four waves of a workgroup walk neighbouring ranges and hand their parts of one sequence to the first of
@@ -513,11 +513,53 @@ def test_fp8_poison_is_never_read(sd):
     assert not np.isnan(ga).any() and np.array_equal(ga, gc)
 
 
-def test_fp8_head_dim_64_is_reported_unsupported(sd):
-    import ctypes
-    s = sd.Shape(batch=1, num_q_heads=2, num_kv_heads=1, head_dim=64, page_size=16, num_pages=4,
-                 max_blocks_per_seq=2, kv_dtype=sd.SD_FP8_E4M3, max_context_len=32, chunk_tokens=0)
-    assert sd.load().sd_chunk_tokens(ctypes.byref(s)) == -2
+@pytest.mark.parametrize("Hq,Hkv", [(8, 1), (8, 2), (64, 8), (28, 4), (16, 1), (40, 2), (1, 1)])
+@pytest.mark.parametrize("min_range", [0, 128, 4096])
+def test_fp8_head_dim_64(sd, Hq, Hkv, min_range):
+    """fp8 pools with 64-wide heads: the range pass (ranges of one tile and of 128 tokens) and the
+    workgroup-per-sequence kernel (ranges that cover every sequence), on lengths around page and tile edges."""
+    lens = [1, 2, 15, 16, 17, 31, 32, 33, 64, 65, 127, 129, 300, 511, 512, 513, 1025, 2049, 0]
+    wl = workloads.make_custom(lens, Hq, Hkv, 64, "fp8", seed=340 + Hq)
+    check_fp8(gpu_attend(wl, chunk_tokens=min_range), oracle_full(wl))
+
+
+def test_fp8_head_dim_64_every_code_decodes_exactly_on_the_device(sd):
+    """As for 128-wide heads: length-1 sequences with power-of-two scales return code * scale bit for bit,
+    all 254 finite codes, spread over four rows of 64."""
+    wl = workloads.make_custom([1, 1, 1, 1], 1, 1, 64, "fp8", seed=341, poison=False)
+    codes = np.arange(256, dtype=np.uint8)
+    codes[0x7F] = 0; codes[0xFF] = 0x80  # the two NaN codes
+    for b in range(4):
+        wl.v_pages[wl.block_table[b, 0], 0, 0, :] = codes[64 * b:64 * b + 64]
+    wl.v_scales[:] = np.float32(2.0 ** -5); wl.k_scales[:] = np.float32(0.25)
+    got = gpu_attend(wl)
+    table = np.array([oracle.e4m3fn_to_float(int(c)) for c in codes], dtype=np.float32) * np.float32(2.0 ** -5)
+    for b in range(4):
+        assert np.array_equal(got[b, 0], table[64 * b:64 * b + 64])
+
+
+def test_fp8_head_dim_64_k_codes_decode_like_the_oracle(sd):
+    """One-hot queries at every d in turn: the two-token weights are a logistic of the difference of two
+    decoded K codes, so a K element that lands at the wrong d, or a wrong code, shows."""
+    B = 128
+    wl = workloads.make_custom([2] * B, 1, 1, 64, "fp8", seed=342, poison=False)
+    q = np.zeros((B, 1, 64), np.float32)
+    for b in range(B):
+        q[b, 0, b % 64] = 1.0
+    wl.q = workloads.f32_to_bf16_bits(q)
+    wl.scale = 1.0
+    for b in range(B):
+        p = wl.block_table[b, 0]
+        wl.k_pages[p, 0, 0, b % 64] = (3 * b) % 127; wl.k_pages[p, 0, 1, b % 64] = (3 * b + 5) % 127
+        wl.k_scales[p, 0] = np.float32(2.0 ** -4)
+    check_fp8(gpu_attend(wl), oracle_full(wl))
+
+
+def test_fp8_head_dim_64_poison_is_never_read(sd):
+    a = workloads.make_custom([3, 47, 130, 512, 529], 16, 2, 64, "fp8", seed=343, poison=True)
+    c = workloads.make_custom([3, 47, 130, 512, 529], 16, 2, 64, "fp8", seed=343, poison=False)
+    ga, gc = gpu_attend(a), gpu_attend(c)
+    assert not np.isnan(ga).any() and np.array_equal(ga, gc)
 
 
 def test_full_size_fp8_large_batch(sd):
@@ -566,12 +608,13 @@ def test_prefix_entry_point_matches_oracle(sd, Hq, Hkv, d, chunk):
     assert np.abs(got - plain).max() <= ALARM_ABS + ALARM_REL * np.abs(plain).max()
 
 
-def test_prefix_entry_point_fp8(sd):
+@pytest.mark.parametrize("d", [128, 64])
+def test_prefix_entry_point_fp8(sd, d):
     sizes = [4, 16, 1]
     session_of = np.repeat(np.arange(3), sizes)
     prefix_len = np.repeat([1024 + 5, 2048 + 512, 512 - 9], sizes)  # two prefixes end inside a page
     lens = prefix_len + np.random.default_rng(5).integers(1, 700, size=len(session_of))
-    wl = workloads.make_custom(lens, 16, 2, 128, "fp8", seed=410, session_of=session_of, prefix_len=prefix_len)
+    wl = workloads.make_custom(lens, 16, 2, d, "fp8", seed=410, session_of=session_of, prefix_len=prefix_len)
     check_fp8(gpu_attend_prefix(wl, chunk_tokens=512), oracle_full(wl))
 
 
@@ -603,13 +646,12 @@ def test_prefix_entry_point_without_groups_is_the_plain_call(sd):
 
 
 # ---------------------------------------------------------------- fp8 quantising append
-def _fp8_append_case(sd, ranges, Hkv=2, num_pages=12, seed=0, scales=(1.0,), prefill=None):
+def _fp8_append_case(sd, ranges, Hkv=2, num_pages=12, seed=0, scales=(1.0,), prefill=None, d=128):
     """Run the same range append on the device and in the oracle; both start from the same pool."""
     import torch
     from paper_2508_11553_amd import binding
     from device_workload import _to_dev
     rng = np.random.default_rng(seed)
-    d = 128
     nseq = max(r[0] for r in ranges) + 1
     maxnb = 6
     bt = rng.permutation(num_pages)[:nseq * maxnb].reshape(nseq, maxnb).astype(np.int32)
@@ -638,28 +680,31 @@ def _fp8_append_case(sd, ranges, Hkv=2, num_pages=12, seed=0, scales=(1.0,), pre
     assert np.array_equal(dvs.cpu().numpy().view(np.uint32), vs.view(np.uint32))
 
 
-def test_fp8_append_fresh_ranges_bit_exact(sd):
-    _fp8_append_case(sd, [(0, 0, 96), (1, 0, 1), (2, 0, 17)], num_pages=20, seed=1, scales=(1.0, 0.01, 30.0))
+@pytest.mark.parametrize("d", [128, 64])
+def test_fp8_append_fresh_ranges_bit_exact(sd, d):
+    _fp8_append_case(sd, [(0, 0, 96), (1, 0, 1), (2, 0, 17)], num_pages=20, seed=1, scales=(1.0, 0.01, 30.0), d=d)
 
 
-def test_fp8_append_into_partly_filled_pages_bit_exact(sd):
+@pytest.mark.parametrize("d", [128, 64])
+def test_fp8_append_into_partly_filled_pages_bit_exact(sd, d):
     # sequence 0 holds 5 tokens, 1 holds 21, 2 holds 16 (next append opens a page)
     pre = [(0, 0, 5), (1, 0, 21), (2, 0, 16)]
-    _fp8_append_case(sd, [(0, 5, 3), (1, 21, 40), (2, 16, 1)], num_pages=20, seed=2, scales=(0.05, 1.0, 8.0), prefill=pre)
-    _fp8_append_case(sd, [(0, 5, 1), (1, 21, 1), (2, 16, 1)], num_pages=20, seed=3, scales=(0.05,), prefill=pre)   # no growth
-    _fp8_append_case(sd, [(0, 5, 1), (1, 21, 1), (2, 16, 1)], num_pages=20, seed=4, scales=(40.0,), prefill=pre)   # growth
+    _fp8_append_case(sd, [(0, 5, 3), (1, 21, 40), (2, 16, 1)], num_pages=20, seed=2, scales=(0.05, 1.0, 8.0), prefill=pre, d=d)
+    _fp8_append_case(sd, [(0, 5, 1), (1, 21, 1), (2, 16, 1)], num_pages=20, seed=3, scales=(0.05,), prefill=pre, d=d)   # no growth
+    _fp8_append_case(sd, [(0, 5, 1), (1, 21, 1), (2, 16, 1)], num_pages=20, seed=4, scales=(40.0,), prefill=pre, d=d)   # growth
 
 
-def test_fp8_append_encoder_matches_the_oracle_on_every_bf16_magnitude(sd):
+@pytest.mark.parametrize("d", [128, 64])
+def test_fp8_append_encoder_matches_the_oracle_on_every_bf16_magnitude(sd, d):
     """One page whose first row pins the scale to 1 (a 448 in it); the other rows sweep bf16 values
     across every binade the format covers, including exact ties between neighbouring codes."""
     import torch
     from paper_2508_11553_amd import binding
     from device_workload import _to_dev
-    d, Hkv = 128, 1
+    Hkv = 1
     vals = []
     for e in range(-12, 9):
-        for m in range(0, 128, 1):
+        for m in range(0, 128, 128 // d):   # every bf16 mantissa at d = 128, every other one at d = 64: both hold all ties
             vals.append((1 + m / 128.0) * 2.0 ** e)
     vals = np.float32(vals)[:15 * d]
     x = np.zeros((16, Hkv, d), np.float32)
@@ -681,20 +726,21 @@ def test_fp8_append_encoder_matches_the_oracle_on_every_bf16_magnitude(sd):
     assert np.array_equal(dk.cpu().numpy(), k) and np.array_equal(dv.cpu().numpy(), v)
 
 
-def test_fp8_resume_then_attend(sd):
+@pytest.mark.parametrize("d", [128, 64])
+def test_fp8_resume_then_attend(sd, d):
     """Rebuild an fp8 cache from bf16 rows in one bulk call per sequence, then attend: the result must match
     the oracle run over the oracle-built pool."""
     import torch
     from paper_2508_11553_amd import binding
     from device_workload import _to_dev
-    src = workloads.make_custom([700, 33, 1500], 16, 2, 128, "bf16", seed=30, poison=False)
+    src = workloads.make_custom([700, 33, 1500], 16, 2, d, "bf16", seed=30, poison=False)
     rows_k, rows_v = [], []
     for b, L in enumerate(src.context_lens):
         t = np.arange(L)
         rows_k.append(src.k_pages[src.block_table[b, t // 16], :, t % 16]); rows_v.append(src.v_pages[src.block_table[b, t // 16], :, t % 16])
     kn, vn = np.concatenate(rows_k), np.concatenate(rows_v)
     r0 = np.int32(np.concatenate([[0], np.cumsum(src.context_lens)]))
-    wl = workloads.make_custom(src.context_lens, 16, 2, 128, "fp8", seed=31)  # same table shape; pools get overwritten
+    wl = workloads.make_custom(src.context_lens, 16, 2, d, "fp8", seed=31)  # same table shape; pools get overwritten
     wl.q, wl.block_table = src.q, src.block_table
     wl.k_pages[:] = 0x7F; wl.v_pages[:] = 0x7F; wl.k_scales[:] = np.nan; wl.v_scales[:] = np.nan
     dw = device_workload(wl)
@@ -708,10 +754,11 @@ def test_fp8_resume_then_attend(sd):
     check_fp8(out.cpu().numpy(), oracle_full(wl))
 
 
-def test_fp8_decode_step_append_then_attend(sd):
+@pytest.mark.parametrize("d", [128, 64])
+def test_fp8_decode_step_append_then_attend(sd, d):
     """One decode step on an fp8 cache: quantising append of one token per sequence, then attention."""
     import torch
-    wl = workloads.make_custom([17, 33, 5, 16, 700, 1025], 16, 2, 128, "fp8", seed=33, append=True)
+    wl = workloads.make_custom([17, 33, 5, 16, 700, 1025], 16, 2, d, "fp8", seed=33, append=True)
     dw = device_workload(wl)
     dw.append()
     out = dw.attend()

@@ -44,7 +44,7 @@ def gpu(wl, q, q_start):
     return out.cpu().numpy()
 
 
-@pytest.mark.parametrize("kv_dtype,d", [("bf16", 64), ("bf16", 128), ("fp8", 128)])
+@pytest.mark.parametrize("kv_dtype,d", [("bf16", 64), ("bf16", 128), ("fp8", 128), ("fp8", 64)])
 @pytest.mark.parametrize("Hq,Hkv", [(1, 1), (4, 2), (8, 1), (28, 4), (6, 2), (16, 1), (32, 4), (17, 1), (40, 2), (64, 1)])
 def test_ragged_query_counts_over_several_tiles(sd, Hq, Hkv, d, kv_dtype):
     # query counts below, at and above a workgroup's block, context lengths across page, tile and round edges
@@ -83,7 +83,7 @@ def test_one_query_per_sequence_equals_the_decode_step(sd):
     assert (diff <= 2 * (3e-4 + 2.0 ** -8 * np.abs(ref_).max(axis=-1, keepdims=True))).all()
 
 
-@pytest.mark.parametrize("kv_dtype,d", [("bf16", 64), ("bf16", 128), ("fp8", 128)])
+@pytest.mark.parametrize("kv_dtype,d", [("bf16", 64), ("bf16", 128), ("fp8", 128), ("fp8", 64)])
 def test_constant_v_returns_the_constant(sd, kv_dtype, d):
     """Every row is a convex combination of V rows, normalised by the sum of the very weights the product uses,
     so with all V rows equal the result is that row up to fp32 rounding, however the weights round."""

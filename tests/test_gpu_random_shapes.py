@@ -29,7 +29,7 @@ def test_decode_random_shapes(sd, seed):
     rng = np.random.default_rng(1000 + seed)
     Hq, Hkv = HEADS[int(rng.integers(len(HEADS)))]
     kv_dtype = "fp8" if rng.random() < 0.35 else "bf16"
-    d = 128 if kv_dtype == "fp8" or rng.random() < 0.6 else 64
+    d = 128 if rng.random() < 0.6 else 64
     lens = draw_lens(rng, int(rng.integers(1, 24)), int(rng.choice([40, 300, 1500, 4000])))
     chunk = int(rng.choice([0, 128, 256, 384, 512, 1024, 4096]))
     wl = workloads.make_custom(lens, Hq, Hkv, d, kv_dtype, seed=2000 + seed)
@@ -42,7 +42,7 @@ def test_prefix_random_groups(sd, seed):
     rng = np.random.default_rng(3000 + seed)
     Hq, Hkv = HEADS[int(rng.integers(len(HEADS)))]
     kv_dtype = "fp8" if rng.random() < 0.3 else "bf16"
-    d = 128 if kv_dtype == "fp8" or rng.random() < 0.6 else 64
+    d = 128 if rng.random() < 0.6 else 64
     chunk = int(rng.choice([128, 256, 512, 1024]))
     sizes = rng.integers(1, 20, size=int(rng.integers(1, 6)))
     prefix = rng.integers(0, 6 * chunk, size=len(sizes))
@@ -63,7 +63,7 @@ def test_prefill_random_stretches(sd, seed):
     rng = np.random.default_rng(5000 + seed)
     Hq, Hkv = HEADS[int(rng.integers(len(HEADS)))]
     kv_dtype = "fp8" if rng.random() < 0.35 else "bf16"
-    d = 128 if kv_dtype == "fp8" or rng.random() < 0.6 else 64
+    d = 128 if rng.random() < 0.6 else 64
     lens = draw_lens(rng, int(rng.integers(1, 10)), int(rng.choice([40, 300, 900])))
     nq = np.array([int(rng.integers(0, L + 3)) for L in lens])       # none .. more queries than tokens
     wl = workloads.make_custom(lens, Hq, Hkv, d, kv_dtype, seed=6000 + seed)
