@@ -695,6 +695,18 @@ def test_fp8_append_into_partly_filled_pages_bit_exact(sd, d):
 
 
 @pytest.mark.parametrize("d", [128, 64])
+def test_fp8_append_quotients_over_many_scales_bit_exact(sd, d):
+    """The kernels divide by a tile's scale through a reciprocal refined once per tile; the codes must be those of
+    the plain division the oracle uses.  Magnitudes from 2^-70 to 2^70 (beyond the range in which the kernels use the shortcut), mixed within
+    a tile and one per tile, rows of random values."""
+    rng = np.random.default_rng(77)
+    mags = tuple(float(2.0 ** k * (1 + rng.random())) for k in range(-70, 71, 2))
+    _fp8_append_case(sd, [(b, 0, 16) for b in range(40)], num_pages=260, seed=100, scales=mags, d=d)   # mixed within a tile
+    for i, m in enumerate(mags[::3]):   # and one magnitude per call: every element of a tile within its range
+        _fp8_append_case(sd, [(b, 0, 16) for b in range(8)], num_pages=60, seed=200 + i, scales=(m,), d=d)
+
+
+@pytest.mark.parametrize("d", [128, 64])
 def test_fp8_append_encoder_matches_the_oracle_on_every_bf16_magnitude(sd, d):
     """One page whose first row pins the scale to 1 (a 448 in it); the other rows sweep bf16 values
     across every binade the format covers, including exact ties between neighbouring codes."""
