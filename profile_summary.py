@@ -2,7 +2,7 @@
 
 Usage (after the profiler runs named in the summary's header):
     python profile_summary.py --workload 'configs[1]' --kernel range_kernel --bench-args='--config 1 ...' \
-        --kernel-trace gpurun_out/prof_kt --fetch gpurun_out/prof_fetch --write gpurun_out/prof_write \
+        --kernel-trace out/prof_kt --fetch out/prof_fetch --write out/prof_write \
         > profiles/range_kernel_config1.md
 
 FETCH_SIZE and WRITE_SIZE are reported by rocprofv3 in KiB per dispatch.  Each
