@@ -17,6 +17,8 @@
 //
 // The causal limit is a per-lane token bound in the score mask; a wave stops
 // once a tile starts at or past the last position any of its rows may see.
+#include <type_traits>
+
 #include "attn_tile.h"
 
 namespace sd {
@@ -107,24 +109,38 @@ __global__ __launch_bounds__(kWaves * 64, 2) void prefill_kernel(PrefillArgs a)
         typename P::Tile r;
         // tiles past the end re-read the last page; nobody attends them
         issue(r, bt[min(2 * wave, last_page)], bt[min(2 * wave + 1, last_page)]);
+        // page ids are read two rounds ahead of their tile: the read is waited for at this round's
+        // barrier (with the LDS writes) and its result is used in the next round
+        const int t1 = kWaves * min(1, rounds - 1) + wave;
+        int na = bt[min(2 * t1, last_page)], nb = bt[min(2 * t1 + 1, last_page)];
         for (int rd = 0; rd < rounds; ++rd) {
-            const int tn = kWaves * min(rd + 1, rounds - 1) + wave;
-            const int na = bt[min(2 * tn, last_page)], nb = bt[min(2 * tn + 1, last_page)];
+            const int t2 = kWaves * min(rd + 2, rounds - 1) + wave;
+            const int fa = bt[min(2 * t2, last_page)], fb = bt[min(2 * t2 + 1, last_page)];
             P::k_store(r, mine, lane);
             P::v_park(r, mine + P::kScratchBytes, lane, (kWaves * rd + wave) * kTileTokens, L);
             if (rd + 1 < rounds) issue(r, na, nb);
+            na = fa;
+            nb = fb;
             __syncthreads();
             if (active) {
-#pragma unroll 2
-                for (int j = 0; j < kWaves; ++j) {
+                // the round's tiles below the diagonal of every row of the wave, then those on it
+                auto step = [&](int j, auto masked) {
                     const int tok0 = (kWaves * rd + j) * kTileTokens;
-                    if (tok0 >= wave_max_end) break;  // wave-uniform
                     const char *slot = lds + j * kSlot;
                     u32x4 ka[D / 32], kb[D / 32];
                     P::k_fetch(slot, lane, ka, kb);
-                    P::template attend_parked<NB>(ka, kb, slot + P::kScratchBytes, qop, st, a.scale_log2e, tok0, lane,
-                                                  row_end, tok0 + kTileTokens > wave_min_end);
-                }
+                    P::template attend_parked<NB, decltype(masked)::value>(ka, kb, slot + P::kScratchBytes, qop, st, a.scale_log2e,
+                                                                          tok0, lane, row_end);
+                };
+                const int t0 = kWaves * rd * kTileTokens;
+                // tiles [0, j_plain) end at or before the first visible row's limit; tiles [j_plain, j_end) start before the last row's
+                const int j_end = min(kWaves, (wave_max_end - t0 + kTileTokens - 1) / kTileTokens);
+                const int j_plain = max(0, min(j_end, (wave_min_end - t0) / kTileTokens));
+                int j = 0;
+#pragma unroll 1
+                for (; j < j_plain; ++j) step(j, std::false_type{});
+#pragma unroll 1
+                for (; j < j_end; ++j) step(j, std::true_type{});
             }
             __syncthreads();
         }

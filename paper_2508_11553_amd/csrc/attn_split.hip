@@ -116,9 +116,10 @@ SD_DEV void shared_item(const SplitArgs &a, char *lds, int lane, int wave)
                 const char *slot = lds + j * kSlot;
                 u32x4 ka[D / 32], kb[D / 32];
                 P::k_fetch(slot, lane, ka, kb);
-                P::template attend_parked<1>(ka, kb, slot + P::kScratchBytes, reinterpret_cast<const u32x4 (&)[1][D / 32]>(qop),
-                                             reinterpret_cast<typename P::ParkedState (&)[1]>(st), a.abs_scale_log2e, tok0,
-                                             lane, ends, tok0 + kTileTokens > t1);
+                auto &q1 = reinterpret_cast<const u32x4 (&)[1][D / 32]>(qop);
+                auto &st1 = reinterpret_cast<typename P::ParkedState (&)[1]>(st);
+                P::template attend_parked<1, true>(ka, kb, slot + P::kScratchBytes, q1, st1, a.abs_scale_log2e, tok0, lane, ends,
+                                                   tok0 + kTileTokens > t1);  // the shared stretch ends inside the tile
             }
         }
         __syncthreads();

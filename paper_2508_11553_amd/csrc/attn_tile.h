@@ -77,6 +77,13 @@ SD_DEV T kv_load(const T *p)
 typedef const __attribute__((address_space(4))) int32_t *ConstTable;
 typedef const __attribute__((address_space(4))) float *ConstScales;
 
+// The larger of two scores.  Scores are never NaN (a masked one is -inf), so the
+// NaN-propagating maximum is the same value as fmaxf, and it is one v_maximum3_f32
+// for up to three operands, where fmaxf first re-quiets every operand the compiler
+// cannot prove canonical (an MFMA result, a permuted lane): a second instruction each.
+SD_DEV float max_of(float a, float b) { return __builtin_elementwise_maximum(a, b); }
+SD_DEV float max_of(float a, float b, float c) { return max_of(max_of(a, b), c); }
+
 // Reductions over the four lanes {n, n+16, n+32, n+48} that share a row.
 // v_permlane16_swap exchanges rows 1<->0' and 3<->2' of its two operands and
 // v_permlane32_swap the upper half of one with the lower half of the other;
@@ -88,11 +95,11 @@ SD_DEV float head_max(float x)
     const unsigned u = __builtin_bit_cast(unsigned, x);
     const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
     const unsigned a0 = a[0], a1 = a[1];
-    const float y = fmaxf(__builtin_bit_cast(float, a0), __builtin_bit_cast(float, a1));
+    const float y = max_of(__builtin_bit_cast(float, a0), __builtin_bit_cast(float, a1));
     const unsigned w = __builtin_bit_cast(unsigned, y);
     const auto b = __builtin_amdgcn_permlane32_swap(w, w, false, false);
     const unsigned b0 = b[0], b1 = b[1];
-    return fmaxf(__builtin_bit_cast(float, b0), __builtin_bit_cast(float, b1));
+    return max_of(__builtin_bit_cast(float, b0), __builtin_bit_cast(float, b1));
 }
 SD_DEV float head_sum(float x)
 {
@@ -141,27 +148,32 @@ SD_DEV void reset(State &st)
 // never by content.
 SD_DEV void mask_scores(float (&x)[8], int tok0, int row_end, int qd)
 {
+    const int visible = row_end - tok0 - 4 * qd;  // of this lane's tokens, counted from its first
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-        if (tok0 + 4 * qd + e >= row_end) x[e] = -INFINITY;
-        if (tok0 + 16 + 4 * qd + e >= row_end) x[4 + e] = -INFINITY;
+        if (e >= visible) x[e] = -INFINITY;
+        if (16 + e >= visible) x[4 + e] = -INFINITY;
     }
 }
 
 SD_DEV float max8(const float (&x)[8])
 {
-    return fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+    return max_of(max_of(x[0], x[1], x[2]), max_of(x[3], x[4], x[5]), max_of(x[6], x[7]));
 }
 
-// The running max moved by m_old -> m_new: everything accumulated so far shrinks
-// by alpha = exp2(m_old - m_new).  Skipped when no row of the wave moved.
+// The running max goes m_old -> m_new: everything accumulated so far shrinks by
+// alpha = exp2(m_old - m_new).  When no row of the wave moved (the usual case once
+// a few tiles are in) alpha is 1 in every lane, and neither the exponential nor the
+// products are issued.
 template <class State>
-SD_DEV void rescale(State &st, float alpha)
+SD_DEV void advance_max(State &st, float m_new)
 {
-    st.l *= alpha;
-    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f)) {
+    if (__builtin_expect(__builtin_amdgcn_ballot_w64(m_new != st.m) != 0, 0)) {
+        const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
+        st.l *= alpha;
 #pragma unroll
         for (int i = 0; i < State::kAcc; ++i) st.acc[i] *= alpha;
+        st.m = m_new;
     }
 }
 
@@ -170,12 +182,9 @@ SD_DEV void rescale(State &st, float alpha)
 template <class State>
 SD_DEV void online_softmax(const float (&x)[8], float (&p)[8], State &st)
 {
-    const float m_new = fmaxf(st.m, head_max(max8(x)));
-    const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
-    st.m = m_new;
+    advance_max(st, max_of(st.m, head_max(max8(x))));
 #pragma unroll
-    for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(x[e] - m_new);
-    rescale(st, alpha);
+    for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(x[e] - st.m);
 }
 
 // The same for raw scores and a positive scale c (log2 domain) folded into the
@@ -184,12 +193,9 @@ SD_DEV void online_softmax(const float (&x)[8], float (&p)[8], State &st)
 template <class State>
 SD_DEV void online_softmax_folded(const float (&s)[8], float c, float (&p)[8], State &st)
 {
-    const float m_new = fmaxf(st.m, head_max(max8(s)) * c);
-    const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
-    st.m = m_new;
+    advance_max(st, max_of(st.m, head_max(max8(s)) * c));
 #pragma unroll
-    for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], c, -m_new));
-    rescale(st, alpha);
+    for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], c, -st.m));
 }
 
 // ---------------------------------------------------------------------------
@@ -391,33 +397,67 @@ struct Bf16Path {
     }
 
     // The tile step for NB column blocks of 16 rows over a parked tile.  The row
-    // of block b in this lane ends at row_end[b]; `mask` (wave-uniform) says some
-    // row ends inside the tile.  c = |scale| * log2(e) > 0 is folded into the
+    // of block b in this lane ends at row_end[b]; MASK says some row may end
+    // inside the tile, and `tile_has_end` (wave-uniform) whether one does.  c = |scale| * log2(e) > 0 is folded into the
     // exponent.  The weight sum is one more accumulator fed an all-ones operand,
-    // i.e. the sum of the rounded weights exactly.  The V^T operands are
-    // requested before the softmax arithmetic so that the LDS latency passes
-    // behind it.
-    template <int NB>
+    // i.e. the sum of the rounded weights exactly.
+    //
+    // Order of issue.  A wave issues in program order, and a matrix instruction
+    // holds the matrix pipe for 16 cycles of which its issue takes 4.  With several
+    // blocks and no mask (the tiles below the diagonal: nearly all) the vector
+    // arithmetic of block b's softmax is therefore written between the matrix
+    // instructions of the group after it (the first product of block b + 1, or the
+    // second product of block 0 after the last block), a few vector instructions per
+    // matrix instruction, so that both pipes work at once within one wave.  Tiles
+    // with a mask take the plain order (products, softmax, products).
+    template <int NB, bool MASK>
     SD_DEV static void attend_parked(const u32x4 (&ka)[D / 32], const u32x4 (&kb)[D / 32], const char *vslot,
                                      const u32x4 (&qop)[NB][D / 32], ParkedState (&st)[NB], float c, int tok0,
-                                     int lane, const int (&row_end)[NB], bool mask)
+                                     int lane, const int (&row_end)[NB], bool tile_has_end = true)
     {
+        constexpr int S = D / 32, K = D / 16;
+        constexpr bool kBeside = NB > 1 && !MASK;
+        constexpr float kSlack = 8.0f;  // log2 domain
         const int qd = lane >> 4;
+        const u32x4 ones = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};  // bf16 1.0 pairs
         f32x4 sa[NB], sb[NB];
+        u32x4 va[K], pop[NB];
 #pragma unroll
         for (int b = 0; b < NB; ++b) sa[b] = sb[b] = f32x4{0, 0, 0, 0};
+        auto first_product = [&](int b, int s) {
+            sa[b] = mfma_bf16_k32(ka[s], qop[b][s], sa[b]);
+            sb[b] = mfma_bf16_k32(kb[s], qop[b][s], sb[b]);
+        };
+        // step k of block b's second product; step K feeds the weight sum
+        auto second_product = [&](int b, int k) {
+            st[b].acc[k] = mfma_bf16_k32(k == K ? ones : va[k], pop[b], st[b].acc[k]);
+        };
+        // matrix instructions [i0, i1) of the group that runs beside block b's softmax
+        auto beside = [&](int b, int i0, int i1) {
+            if (!kBeside) return;
 #pragma unroll
-        for (int s = 0; s < D / 32; ++s)
-#pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                sa[b] = mfma_bf16_k32(ka[s], qop[b][s], sa[b]);
-                sb[b] = mfma_bf16_k32(kb[s], qop[b][s], sb[b]);
+            for (int i = i0; i < i1; ++i) {
+                if (b + 1 < NB) {
+                    if (i < S) first_product(b + 1, i);
+                } else {
+                    if (i <= K) second_product(0, i == 0 ? K : i - 1);
+                }
             }
-        u32x4 va[D / 16];
+        };
+        constexpr int kBesideAll = K + 1;  // covers either kind of group
+        auto fetch_v = [&]() {
 #pragma unroll
-        for (int k = 0; k < D / 16; ++k) va[k] = *reinterpret_cast<const u32x4 *>(vslot + k * 1024 + lane * 16);
+            for (int k = 0; k < K; ++k) va[k] = *reinterpret_cast<const u32x4 *>(vslot + k * 1024 + lane * 16);
+        };
+#pragma unroll
+        for (int b = 0; b < (kBeside ? 1 : NB); ++b)
+#pragma unroll
+            for (int s = 0; s < S; ++s) first_product(b, s);
+        // plain order: the V^T operands are requested before the softmax arithmetic so that the LDS
+        // latency passes behind it.  Beside-order: once the K operands are no longer needed (their
+        // registers are reused), which still leaves a softmax between the request and the first use.
+        if (!kBeside) fetch_v();
         __builtin_amdgcn_sched_barrier(0);
-        u32x4 pop[NB];
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
             float x[8], p[8];
@@ -426,18 +466,56 @@ struct Bf16Path {
                 x[e] = sa[b][e];
                 x[4 + e] = sb[b][e];
             }
-            if (mask) mask_scores(x, tok0, row_end[b], qd);
-            online_softmax_folded(x, c, p, st[b]);
+            if (MASK && tile_has_end) mask_scores(x, tok0, row_end[b], qd);
+            beside(b, 0, 1);
+            if (kBeside) {
+                // The reference of the exponent only has to stay within kSlack of the row's largest
+                // score (weights up to 2^kSlack lose nothing in fp32 or as bf16): the row-wide
+                // maximum, a chain of a dozen dependent instructions with two lane exchanges, is
+                // taken only when some lane's score has outgrown the reference.
+                const float hi = max8(x) * c;
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one matrix instruction
+                __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);  // three vector instructions
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+                if (__builtin_expect(__builtin_amdgcn_ballot_w64(hi > st[b].m + kSlack) != 0, 0))
+                    advance_max(st[b], max_of(st[b].m, head_max(hi)));
+            } else {
+                advance_max(st[b], max_of(st[b].m, head_max(max8(x)) * c));
+            }
+            // the weights: independent instructions, three per matrix instruction
+            beside(b, 1, kBesideAll);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(x[e], c, -st[b].m));
 #pragma unroll
             for (int e = 0; e < 8; e += 2) pop[b][e >> 1] = cvt_pk_bf16(p[e], p[e + 1]);
+            if (kBeside) {
+#pragma unroll
+                for (int i = 0; i < 7; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+                }
+                if (b == NB - 2) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    fetch_v();
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
         }
-        const u32x4 ones = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};  // bf16 1.0 pairs
+        if (kBeside) {
+            // what ran beside nothing: the second product of every block but the first
 #pragma unroll
-        for (int b = 0; b < NB; ++b) st[b].acc[D / 16] = mfma_bf16_k32(ones, pop[b], st[b].acc[D / 16]);
+            for (int b = 1; b < NB; ++b)
 #pragma unroll
-        for (int k = 0; k < D / 16; ++k)
+                for (int k = 0; k <= K; ++k) second_product(b, k == 0 ? K : k - 1);
+        } else {
 #pragma unroll
-            for (int b = 0; b < NB; ++b) st[b].acc[k] = mfma_bf16_k32(va[k], pop[b], st[b].acc[k]);
+            for (int b = 0; b < NB; ++b) second_product(b, K);
+#pragma unroll
+            for (int k = 0; k < K; ++k)
+#pragma unroll
+                for (int b = 0; b < NB; ++b) second_product(b, k);
+        }
     }
     SD_DEV static float weight_sum(const ParkedState &st) { return st.acc[D / 16][0]; }
 
@@ -647,10 +725,10 @@ struct Fp8Path {
 
     // as Bf16Path::attend_parked; the scores are scaled per page before the mask
     // (a page of zeros has scale 0), so nothing is folded here
-    template <int NB>
+    template <int NB, bool MASK>
     SD_DEV static void attend_parked(const u32x4 (&ka)[4], const u32x4 (&kb)[4], const char *vslot,
                                      const u32x4 (&qop)[NB][4], ParkedState (&st)[NB], float c, int tok0, int lane,
-                                     const int (&row_end)[NB], bool mask)
+                                     const int (&row_end)[NB], bool tile_has_end = true)
     {
         const int qd = lane >> 4;
         const f32x4 sc = *reinterpret_cast<const f32x4 *>(vslot + 8 * 1024);  // k scales, v scales of the two pages
@@ -674,7 +752,7 @@ struct Fp8Path {
                 x[e] = sa[b][e] * ca;
                 x[4 + e] = sb[b][e] * cb;
             }
-            if (mask) mask_scores(x, tok0, row_end[b], qd);
+            if (MASK && tile_has_end) mask_scores(x, tok0, row_end[b], qd);
             online_softmax(x, p, st[b]);
             pop[b] = weight_operand(p, sc[2], sc[3], st[b].l);
         }
@@ -832,10 +910,10 @@ struct Fp8Path64 {
     }
 
     // as Fp8Path::attend_parked, with the four operands of head_dim 64
-    template <int NB>
+    template <int NB, bool MASK>
     SD_DEV static void attend_parked(const u32x4 (&ka)[2], const u32x4 (&kb)[2], const char *vslot,
                                      const u32x4 (&qop)[NB][2], ParkedState (&st)[NB], float c, int tok0, int lane,
-                                     const int (&row_end)[NB], bool mask)
+                                     const int (&row_end)[NB], bool tile_has_end = true)
     {
         const int qd = lane >> 4;
         const f32x4 sc = *reinterpret_cast<const f32x4 *>(vslot + B::kOpsBytes);  // k scales, v scales of the two pages
@@ -859,7 +937,7 @@ struct Fp8Path64 {
                 x[e] = sa[b][e] * ca;
                 x[4 + e] = sb[b][e] * cb;
             }
-            if (mask) mask_scores(x, tok0, row_end[b], qd);
+            if (MASK && tile_has_end) mask_scores(x, tok0, row_end[b], qd);
             online_softmax(x, p, st[b]);
             pop[b] = Fp8Path::weight_operand(p, sc[2], sc[3], st[b].l);
         }
