@@ -160,13 +160,188 @@ __global__ __launch_bounds__(kWaves * 64, 2) void prefill_kernel(PrefillArgs a)
     }
 }
 
+// bf16 pools: one workgroup of 8 waves per compute unit.  A round is four 32-token tiles, held in
+// one of two LDS buffers; wave w brings page w & 1 of tile w >> 1 (half the registers of a whole
+// tile), and because the next round's buffer is the one nobody reads, a wave parks what it loaded
+// and asks for the page after that without waiting for anybody: one barrier per round, none
+// between a write and the reads of the same round.  Twice the query tokens per workgroup also
+// halve what travels from L2 to LDS per row.  The rest (rows of a wave, causal limits, tile step)
+// is as above.
+template <int D>
+__global__ __launch_bounds__(kPrefillWideWaves * 64) void prefill_wide_kernel(PrefillArgs a)
+{
+    typedef Bf16Path<D> P;
+    constexpr int NB = kPrefillBlocks;
+    constexpr int kW = kPrefillWideWaves;
+    constexpr int kTiles = 4;  // tiles per round
+    constexpr int kSlot = Lds<P>::kSlotBytes;
+    constexpr int kBuf = kTiles * kSlot;
+    static_assert(kW == 2 * kTiles, "one page of one tile per wave");
+    __shared__ __attribute__((aligned(16))) char lds[2 * kBuf];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const unsigned per_xcd = gridDim.x / kXcds;  // the grid is padded to a multiple of kXcds
+    const unsigned item = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+    const int Hv = a.Hkv * a.HB;
+    if (item >= (unsigned)a.q_blocks * (unsigned)a.B * (unsigned)Hv) return;
+    const int jb = a.q_blocks - 1 - (int)(item % a.q_blocks);
+    const HeadBlock hb = head_block((item / a.q_blocks) % Hv, a.G, a.HB);
+    const int g = hb.g;
+    const int b = item / ((unsigned)a.q_blocks * Hv);
+    const int tpb = units_per_block(a.G);  // query tokens per column block
+    const int tpw = NB * tpb;              // and per wave
+
+    // everything below up to the loop is workgroup-uniform
+    const int qs = a.q_start[b];
+    const int nq = min(a.q_start[b + 1] - qs, a.max_q_len);
+    const int i0 = jb * kW * tpw;
+    if (i0 >= nq) return;
+    if (qs < 0 || (int64_t)qs + nq > a.total_q) return;  // rows outside q: nothing is read or written
+    const int L = max(0, min(a.context_lens[b], a.max_context_len));
+    const int base = L - nq;                                       // position of query 0 (may be negative)
+    const int kv_end = max(0, base + min(nq, i0 + kW * tpw));      // tokens the block's last row sees
+
+    const int iw0 = i0 + wave * tpw;
+    const int iw1 = min(iw0 + tpw, nq);
+    const bool active = iw0 < nq && base + iw1 > 0;  // some row of the wave sees a token
+    const int wave_max_end = base + iw1;              // its last row's limit
+    const int wave_min_end = max(0, base + iw0) + 1;  // its first visible row's limit
+    const int n = lane & 15, qd = lane >> 4;
+    auto locate = [&](int c, bool &in_range, bool &row_ok, int64_t &row) {
+        const int i = iw0 + c * tpb + n / hb.rows;
+        in_range = n / hb.rows < tpb && i < nq;
+        row_ok = in_range && base + i >= 0;
+        row = ((int64_t)qs + i) * a.Hq + hb.head0 + n % hb.rows;
+        return i;
+    };
+    int row_end[NB];
+    u32x4 qop[NB][D / 32];
+    typename P::ParkedState st[NB];
+#pragma unroll
+    for (int c = 0; c < NB; ++c) {
+        bool in_range, row_ok;
+        int64_t row;
+        const int i = locate(c, in_range, row_ok, row);
+        row_end[c] = row_ok ? base + i + 1 : L;
+#pragma unroll
+        for (int s = 0; s < D / 32; ++s)
+            qop[c][s] = row_ok ? (*reinterpret_cast<const u32x4 *>(a.q + row * D + P::q_offset(s, lane)) & a.q_keep) ^ a.q_flip
+                               : u32x4{0, 0, 0, 0};
+        reset(st[c]);
+    }
+
+    const int32_t *bt = a.block_table + (int64_t)b * a.max_blocks;
+    const int64_t page_bytes = (int64_t)P::kTileBytes * a.Hkv;
+    const char *kbase = static_cast<const char *>(a.k_pages) + g * P::kTileBytes;
+    const char *vbase = static_cast<const char *>(a.v_pages) + g * P::kTileBytes;
+    const int my_tile = wave >> 1, my_page = wave & 1;
+    struct Page {
+        u32x4 k[D / 32];     // as Bf16Path::Tile, one page
+        u32x2 v[D / 64][4];
+    };
+    auto issue = [&](Page &r, int page) {
+        const char *kl = kbase + page * page_bytes + lane * 16;
+#pragma unroll
+        for (int j = 0; j < D / 32; ++j) r.k[j] = kv_load<false>(reinterpret_cast<const u32x4 *>(kl + j * 1024));
+        const char *vl = vbase + page * page_bytes + qd * 4 * (D * 2) + n * 8;
+#pragma unroll
+        for (int h = 0; h < D / 64; ++h)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) r.v[h][j] = kv_load<false>(reinterpret_cast<const u32x2 *>(vl + j * (D * 2) + h * 128));
+    };
+    // this wave's page of round rd -> its half of the K image and of the V^T operands of slot `slot`
+    auto park = [&](Page &r, char *slot, int rd) {
+        char *kdst = slot + my_page * P::kTileBytes;
+#pragma unroll
+        for (int j = 0; j < D / 32; ++j) {
+            const int row = j * P::kRowsPerLoad + lane / P::kPieces;
+            const int piece = (lane % P::kPieces) ^ (row % P::kPieces);
+            *reinterpret_cast<u32x4 *>(kdst + row * (D * 2) + piece * 16) = r.k[j];
+        }
+        const int tok0 = (kTiles * rd + my_tile) * kTileTokens + my_page * kPage;
+        if (tok0 + kPage > L) {  // wave-uniform: V rows of tokens that do not exist may hold anything
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (tok0 + 4 * qd + j >= L) {
+#pragma unroll
+                    for (int h = 0; h < D / 64; ++h) r.v[h][j] = u32x2{0, 0};
+                }
+        }
+        char *vdst = slot + P::kScratchBytes + lane * 16 + my_page * 8;
+#pragma unroll
+        for (int h = 0; h < D / 64; ++h)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int w = i >> 1;
+                const u32x2 o = (i & 1) ? u32x2{pack_hi(r.v[h][0][w], r.v[h][1][w]), pack_hi(r.v[h][2][w], r.v[h][3][w])}
+                                        : u32x2{pack_lo(r.v[h][0][w], r.v[h][1][w]), pack_lo(r.v[h][2][w], r.v[h][3][w])};
+                *reinterpret_cast<u32x2 *>(vdst + (4 * h + i) * 1024) = o;
+            }
+    };
+    const int ntiles = (kv_end + kTileTokens - 1) / kTileTokens;
+    const int rounds = (ntiles + kTiles - 1) / kTiles;
+    const int last_page = (kv_end + kPage - 1) / kPage - 1;
+    // the page this wave brings for round rd (pages past the end re-read the last one; nobody attends them)
+    auto page_of = [&](int rd) { return bt[min(2 * (kTiles * min(rd, rounds - 1) + my_tile) + my_page, last_page)]; };
+    if (rounds > 0) {
+        Page r;
+        issue(r, page_of(0));
+        int next_page = page_of(1), after_next = page_of(2);  // read ahead of their use
+        park(r, lds + my_tile * kSlot, 0);
+        if (rounds > 1) issue(r, next_page);
+        __syncthreads();
+        for (int rd = 0; rd < rounds; ++rd) {
+            const char *cur = lds + (rd & 1) * kBuf;
+            // round rd + 1's page goes to the other buffer (last read in round rd - 1), round rd + 2's is requested
+            next_page = after_next;
+            after_next = page_of(rd + 3);
+            if (rd + 1 < rounds) {
+                park(r, lds + ((rd + 1) & 1) * kBuf + my_tile * kSlot, rd + 1);
+                if (rd + 2 < rounds) issue(r, next_page);
+            }
+            if (active) {
+                auto step = [&](int j, auto masked) {
+                    const int tok0 = (kTiles * rd + j) * kTileTokens;
+                    const char *slot = cur + j * kSlot;
+                    u32x4 ka[D / 32], kb[D / 32];
+                    P::k_fetch(slot, lane, ka, kb);
+                    P::template attend_parked<NB, decltype(masked)::value>(ka, kb, slot + P::kScratchBytes, qop, st, a.scale_log2e,
+                                                                          tok0, lane, row_end);
+                };
+                const int t0 = kTiles * rd * kTileTokens;
+                const int j_end = min(kTiles, (wave_max_end - t0 + kTileTokens - 1) / kTileTokens);
+                const int j_plain = max(0, min(j_end, (wave_min_end - t0) / kTileTokens));
+                int j = 0;
+#pragma unroll 1
+                for (; j < j_plain; ++j) step(j, std::false_type{});
+#pragma unroll 1
+                for (; j < j_end; ++j) step(j, std::true_type{});
+            }
+            __syncthreads();
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < NB; ++c) {
+        const float l = P::weight_sum(st[c]);
+        bool in_range, row_ok;
+        int64_t row;
+        locate(c, in_range, row_ok, row);
+        if (!in_range) continue;
+        const float inv = row_ok ? 1.0f / l : 0.0f;  // rows before the sequence's first token get zeros
+#pragma unroll
+        for (int k = 0; k < D / 16; ++k) st[c].acc[k] = row_ok ? st[c].acc[k] * inv : f32x4{0, 0, 0, 0};
+        P::store_acc(st[c], a.out + row * D, lane >> 4);
+    }
+}
+
 hipError_t launch_prefill(const PrefillArgs &a, int head_dim, int kv_dtype, hipStream_t stream, hipEvent_t start,
                           hipEvent_t stop)
 {
     const unsigned items = (unsigned)a.q_blocks * (unsigned)a.B * (unsigned)(a.Hkv * a.HB);
     if (items == 0) return hipSuccess;
     const unsigned grid = (items + kXcds - 1) / kXcds * kXcds;
-    const dim3 g(grid), b(kWaves * 64);
+    const dim3 g(grid), b(prefill_waves(kv_dtype) * 64);
     auto go = [&](auto kernel) {
         if (start || stop)
             hipExtLaunchKernelGGL(kernel, g, b, 0, stream, start, stop, 0, a);
@@ -174,9 +349,9 @@ hipError_t launch_prefill(const PrefillArgs &a, int head_dim, int kv_dtype, hipS
             hipLaunchKernelGGL(kernel, g, b, 0, stream, a);
     };
     if (kv_dtype == 0 && head_dim == 128)
-        go(prefill_kernel<Bf16Path<128>>);
+        go(prefill_wide_kernel<128>);
     else if (kv_dtype == 0 && head_dim == 64)
-        go(prefill_kernel<Bf16Path<64>>);
+        go(prefill_wide_kernel<64>);
     else if (kv_dtype == 1 && head_dim == 128)
         go(prefill_kernel<Fp8Path>);
     else if (kv_dtype == 1 && head_dim == 64)

@@ -161,6 +161,14 @@ SD_DEV float max8(const float (&x)[8])
     return max_of(max_of(x[0], x[1], x[2]), max_of(x[3], x[4], x[5]), max_of(x[6], x[7]));
 }
 
+// In the causal pass the reference m of a row's exponents only has to stay within kSlack of the
+// row's largest score so far: weights up to 2^kSlack lose nothing in fp32 or as bf16 (same
+// relative rounding), and weight sum and weighted sum are relative to m whatever it is.  The
+// row-wide maximum, a chain of a dozen dependent instructions with two lane exchanges, is taken
+// there only when some lane's score has outgrown the reference.  (The decode kernels, which wait
+// for memory, keep the exact maximum: the same change made no difference to them.)
+constexpr float kSlack = 8.0f;  // log2 domain
+
 // The running max goes m_old -> m_new: everything accumulated so far shrinks by
 // alpha = exp2(m_old - m_new).  When no row of the wave moved (the usual case once
 // a few tiles are in) alpha is 1 in every lane, and neither the exponential nor the
@@ -183,6 +191,16 @@ template <class State>
 SD_DEV void online_softmax(const float (&x)[8], float (&p)[8], State &st)
 {
     advance_max(st, max_of(st.m, head_max(max8(x))));
+#pragma unroll
+    for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(x[e] - st.m);
+}
+
+// The same with a reference that may lag the row's maximum by up to kSlack.
+template <class State>
+SD_DEV void online_softmax_lagging(const float (&x)[8], float (&p)[8], State &st)
+{
+    const float hi = max8(x);
+    if (__builtin_expect(__builtin_amdgcn_ballot_w64(hi > st.m + kSlack) != 0, 0)) advance_max(st, max_of(st.m, head_max(hi)));
 #pragma unroll
     for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(x[e] - st.m);
 }
@@ -417,7 +435,6 @@ struct Bf16Path {
     {
         constexpr int S = D / 32, K = D / 16;
         constexpr bool kBeside = NB > 1 && !MASK;
-        constexpr float kSlack = 8.0f;  // log2 domain
         const int qd = lane >> 4;
         const u32x4 ones = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};  // bf16 1.0 pairs
         f32x4 sa[NB], sb[NB];
@@ -469,10 +486,6 @@ struct Bf16Path {
             if (MASK && tile_has_end) mask_scores(x, tok0, row_end[b], qd);
             beside(b, 0, 1);
             if (kBeside) {
-                // The reference of the exponent only has to stay within kSlack of the row's largest
-                // score (weights up to 2^kSlack lose nothing in fp32 or as bf16): the row-wide
-                // maximum, a chain of a dozen dependent instructions with two lane exchanges, is
-                // taken only when some lane's score has outgrown the reference.
                 const float hi = max8(x) * c;
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one matrix instruction
                 __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);  // three vector instructions
@@ -753,7 +766,10 @@ struct Fp8Path {
                 x[4 + e] = sb[b][e] * cb;
             }
             if (MASK && tile_has_end) mask_scores(x, tok0, row_end[b], qd);
-            online_softmax(x, p, st[b]);
+            if (MASK)
+                online_softmax(x, p, st[b]);
+            else
+                online_softmax_lagging(x, p, st[b]);
             pop[b] = weight_operand(p, sc[2], sc[3], st[b].l);
         }
 #pragma unroll
@@ -938,7 +954,10 @@ struct Fp8Path64 {
                 x[4 + e] = sb[b][e] * cb;
             }
             if (MASK && tile_has_end) mask_scores(x, tok0, row_end[b], qd);
-            online_softmax(x, p, st[b]);
+            if (MASK)
+                online_softmax(x, p, st[b]);
+            else
+                online_softmax_lagging(x, p, st[b]);
             pop[b] = Fp8Path::weight_operand(p, sc[2], sc[3], st[b].l);
         }
 #pragma unroll

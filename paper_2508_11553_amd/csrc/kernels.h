@@ -44,6 +44,9 @@ __device__ inline unsigned xcd_deal(unsigned i, unsigned n, unsigned Hv)
     return k * run + (j % kXcds) * Hv + j / kXcds;
 }
 constexpr int kPrefillBlocks = 2;   // 16-row column blocks one wave of the causal pass carries
+constexpr int kPrefillWideWaves = 8; // waves of a workgroup of the causal pass over bf16 pools (fp8 pools: kWaves)
+// Waves per workgroup of the causal pass for a pool type (0 = bf16, 1 = fp8): the host sizes the grid with it.
+__host__ __device__ inline int prefill_waves(int kv_dtype) { return kv_dtype == 0 ? kPrefillWideWaves : kWaves; }
 
 // Chunk slots of one output row.  Without a shared prefix, chunk c covers tokens
 // [c*chunk, (c+1)*chunk).  With a shared prefix of `sh` tokens (a multiple of
@@ -168,7 +171,7 @@ struct PrefillArgs {
     uint32_t q_keep;             // 0 when scale == 0 (all scores are zero: zero queries, scale 1), else all ones
     int32_t B, Hq, Hkv, G, HB, max_blocks, max_context_len;  // HB: head blocks per KV head, ceil(G / 16)
     int32_t total_q, max_q_len;  // rows of q; host-known bound on the rows of one sequence
-    int32_t q_blocks;            // workgroups (4 waves x kPrefillBlocks x 16/G query tokens each) that cover max_q_len
+    int32_t q_blocks;            // workgroups (prefill_waves x kPrefillBlocks x 16/G query tokens each) that cover max_q_len
 };
 
 struct AppendArgs {

@@ -7,7 +7,7 @@ import pytest
 
 import oracle
 import workloads
-from workloads import f32_to_bf16_bits
+from workloads import bf16_bits_to_f32, f32_to_bf16_bits
 from tests.test_gpu_parity import check as check_decode, check_fp8, device_workload, sd  # noqa: F401  (sd is a fixture)
 
 pytestmark = pytest.mark.gpu
@@ -144,3 +144,34 @@ def test_long_stretch_at_a_rollout_shape(sd):
         one = oracle.paged_decode_attention(q[r:r + 1], wl.k_pages, wl.v_pages, wl.block_table[b:b + 1],
                                             np.array([pos + 1], dtype=np.int32), wl.scale)
         check(got[r:r + 1], one)
+
+
+@pytest.mark.parametrize("kv_dtype,d", [("bf16", 128), ("bf16", 64), ("fp8", 128), ("fp8", 64)])
+@pytest.mark.parametrize("shape", ["ramp", "jumps", "decay"])
+def test_scores_that_outgrow_the_running_reference(sd, shape, d, kv_dtype):
+    """Keys whose size depends on the position, so that a row's largest score moves all along the
+    range: steadily (ramp: the exponent's reference has to follow many times), in rare leaps far
+    beyond anything seen before (jumps: weights of earlier tokens underflow at once), or not at
+    all after the first tiles (decay: the reference stays where the first tile put it).  bf16 pools:
+    every K row is scaled; fp8 pools: every page's K scale (a page's tokens grow together)."""
+    lens, nq = [1500, 777, 96], [400, 777, 96]
+    wl, q, q_start = make(lens, nq, 8, 2, d, kv_dtype, seed=900 + d)
+
+    def factor(t):
+        if shape == "ramp":
+            return 1.0 + 0.03 * t
+        if shape == "jumps":
+            return np.where(t % 211 >= 208, 40.0 * (1 + t // 211), 1.0)
+        return 30.0 / (1.0 + 0.05 * t)
+
+    if kv_dtype == "bf16":
+        k = bf16_bits_to_f32(wl.k_pages)                       # [pages][Hkv][16][d]
+        for b, L in enumerate(lens):
+            t = np.arange(L)
+            k[wl.block_table[b, t // 16], :, t % 16, :] *= factor(t)[:, None, None].astype(np.float32)
+        wl.k_pages = f32_to_bf16_bits(k)
+    else:
+        for b, L in enumerate(lens):
+            first = np.arange(0, L, 16)
+            wl.k_scales[wl.block_table[b, first // 16], :] *= factor(first + 15)[:, None].astype(np.float32)
+    check(gpu(wl, q, q_start), ref(wl, q, q_start), kv_dtype)
