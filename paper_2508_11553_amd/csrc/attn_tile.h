@@ -161,12 +161,14 @@ SD_DEV float max8(const float (&x)[8])
     return max_of(max_of(x[0], x[1], x[2]), max_of(x[3], x[4], x[5]), max_of(x[6], x[7]));
 }
 
-// In the causal pass the reference m of a row's exponents only has to stay within kSlack of the
-// row's largest score so far: weights up to 2^kSlack lose nothing in fp32 or as bf16 (same
-// relative rounding), and weight sum and weighted sum are relative to m whatever it is.  The
-// row-wide maximum, a chain of a dozen dependent instructions with two lane exchanges, is taken
-// there only when some lane's score has outgrown the reference.  (The decode kernels, which wait
-// for memory, keep the exact maximum: the same change made no difference to them.)
+// In the causal pass the reference m of a row's exponents may lag the row's largest score so far:
+// weights above 1 lose nothing in fp32 or as bf16 (same relative rounding), and weight sum and
+// weighted sum are relative to m whatever it is.  The row-wide maximum, a chain of a dozen
+// dependent instructions with two lane exchanges, is taken there only when some lane's score has
+// outgrown the reference: by kSlack over fp8 pools (checked before the weights are formed), by an
+// octave over bf16 pools (seen from the weights themselves, see Bf16Path::attend_parked).  The
+// decode kernels, which wait for memory, keep the exact maximum: a lagging reference made no
+// difference to them.
 constexpr float kSlack = 8.0f;  // log2 domain
 
 // The running max goes m_old -> m_new: everything accumulated so far shrinks by
@@ -484,35 +486,38 @@ struct Bf16Path {
                 x[4 + e] = sb[b][e];
             }
             if (MASK && tile_has_end) mask_scores(x, tok0, row_end[b], qd);
-            beside(b, 0, 1);
+            auto weights = [&]() {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(x[e], c, -st[b].m));
+#pragma unroll
+                for (int e = 0; e < 8; e += 2) pop[b][e >> 1] = cvt_pk_bf16(p[e], p[e + 1]);
+            };
             if (kBeside) {
-                const float hi = max8(x) * c;
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one matrix instruction
-                __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);  // three vector instructions
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
-                if (__builtin_expect(__builtin_amdgcn_ballot_w64(hi > st[b].m + kSlack) != 0, 0))
-                    advance_max(st[b], max_of(st[b].m, head_max(hi)));
-            } else {
-                advance_max(st[b], max_of(st[b].m, head_max(max8(x)) * c));
-            }
-            // the weights: independent instructions, three per matrix instruction
-            beside(b, 1, kBesideAll);
+                // The weights are formed against the reference as it stands, beside the matrix
+                // instructions of the next group; only then is it asked whether the reference has
+                // fallen an octave or more behind (some weight >= 2: bit 14 of its bf16 pattern; inf and
+                // NaN, which a reference of -inf gives, have it too).  If so the reference moves to the
+                // row's maximum and the block's weights are formed again.
+                beside(b, 0, kBesideAll);
+                weights();
 #pragma unroll
-            for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(x[e], c, -st[b].m));
-#pragma unroll
-            for (int e = 0; e < 8; e += 2) pop[b][e >> 1] = cvt_pk_bf16(p[e], p[e + 1]);
-            if (kBeside) {
-#pragma unroll
-                for (int i = 0; i < 7; ++i) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+                for (int i = 0; i < K + 1; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one matrix instruction
+                    __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);  // three vector instructions
+                }
+                const unsigned big = (pop[b][0] | pop[b][1] | pop[b][2] | pop[b][3]) & 0x40004000u;
+                if (__builtin_expect(__builtin_amdgcn_ballot_w64(big != 0) != 0, 0)) {
+                    advance_max(st[b], max_of(st[b].m, head_max(max8(x)) * c));
+                    weights();
                 }
                 if (b == NB - 2) {
                     __builtin_amdgcn_sched_barrier(0);
                     fetch_v();
                     __builtin_amdgcn_sched_barrier(0);
                 }
+            } else {
+                advance_max(st[b], max_of(st[b].m, head_max(max8(x)) * c));
+                weights();
             }
         }
         if (kBeside) {
