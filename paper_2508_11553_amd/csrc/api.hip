@@ -613,7 +613,7 @@ int paged_prefill_attention(const sd_shape *shape, const void *q, const int32_t 
     a.max_context_len = shape->max_context_len;
     a.total_q = total_q;
     a.max_q_len = max_q_len < total_q ? max_q_len : total_q;
-    const int tokens_per_wg = sd::prefill_waves(shape->kv_dtype) * sd::kPrefillBlocks * sd::units_per_block(a.G);
+    const int tokens_per_wg = sd::prefill_waves(shape->kv_dtype, shape->head_dim) * sd::kPrefillBlocks * sd::units_per_block(a.G);
     a.q_blocks = (a.max_q_len + tokens_per_wg - 1) / tokens_per_wg;
     if ((uint64_t)a.q_blocks * (uint64_t)a.B * (uint64_t)(a.Hkv * a.HB) > 0x7ffffff0ull) return SD_EUNSUPPORTED;
     hipEvent_t none[2] = {nullptr, nullptr};

@@ -160,7 +160,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void prefill_kernel(PrefillArgs a)
     }
 }
 
-// bf16 pools: one workgroup of 8 waves per compute unit.  A round is four 32-token tiles, held in
+// bf16 pools, head_dim 128: one workgroup of 8 waves per compute unit.  A round is four 32-token tiles, held in
 // one of two LDS buffers; wave w brings page w & 1 of tile w >> 1 (half the registers of a whole
 // tile), and because the next round's buffer is the one nobody reads, a wave parks what it loaded
 // and asks for the page after that without waiting for anybody: one barrier per round, none
@@ -341,7 +341,7 @@ hipError_t launch_prefill(const PrefillArgs &a, int head_dim, int kv_dtype, hipS
     const unsigned items = (unsigned)a.q_blocks * (unsigned)a.B * (unsigned)(a.Hkv * a.HB);
     if (items == 0) return hipSuccess;
     const unsigned grid = (items + kXcds - 1) / kXcds * kXcds;
-    const dim3 g(grid), b(prefill_waves(kv_dtype) * 64);
+    const dim3 g(grid), b(prefill_waves(kv_dtype, head_dim) * 64);
     auto go = [&](auto kernel) {
         if (start || stop)
             hipExtLaunchKernelGGL(kernel, g, b, 0, stream, start, stop, 0, a);
@@ -351,7 +351,7 @@ hipError_t launch_prefill(const PrefillArgs &a, int head_dim, int kv_dtype, hipS
     if (kv_dtype == 0 && head_dim == 128)
         go(prefill_wide_kernel<128>);
     else if (kv_dtype == 0 && head_dim == 64)
-        go(prefill_wide_kernel<64>);
+        go(prefill_kernel<Bf16Path<64>>);
     else if (kv_dtype == 1 && head_dim == 128)
         go(prefill_kernel<Fp8Path>);
     else if (kv_dtype == 1 && head_dim == 64)

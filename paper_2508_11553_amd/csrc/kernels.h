@@ -44,9 +44,10 @@ __device__ inline unsigned xcd_deal(unsigned i, unsigned n, unsigned Hv)
     return k * run + (j % kXcds) * Hv + j / kXcds;
 }
 constexpr int kPrefillBlocks = 2;   // 16-row column blocks one wave of the causal pass carries
-constexpr int kPrefillWideWaves = 8; // waves of a workgroup of the causal pass over bf16 pools (fp8 pools: kWaves)
-// Waves per workgroup of the causal pass for a pool type (0 = bf16, 1 = fp8): the host sizes the grid with it.
-__host__ __device__ inline int prefill_waves(int kv_dtype) { return kv_dtype == 0 ? kPrefillWideWaves : kWaves; }
+constexpr int kPrefillWideWaves = 8; // waves of a workgroup of the causal pass over bf16 pools with head_dim 128 (else kWaves)
+// Waves per workgroup of the causal pass for a pool type (0 = bf16, 1 = fp8) and head size: the host sizes the grid with it.
+// (At head_dim 64 three workgroups of 4 waves fit a compute unit and beat one of 8.)
+__host__ __device__ inline int prefill_waves(int kv_dtype, int head_dim) { return kv_dtype == 0 && head_dim == 128 ? kPrefillWideWaves : kWaves; }
 
 // Chunk slots of one output row.  Without a shared prefix, chunk c covers tokens
 // [c*chunk, (c+1)*chunk).  With a shared prefix of `sh` tokens (a multiple of
