@@ -4,19 +4,23 @@
 //
 // Sequence b brings n_b = q_start[b+1] - q_start[b] query tokens, its LAST n_b
 // positions: query i sits at position pos = L - n_b + i and attends the tokens
-// 0 .. pos.  One workgroup (4 waves) owns a block of 8 * (16 / G) consecutive
-// query tokens of one sequence and one KV head; wave w owns 2 * (16 / G) of
-// them as two column blocks of 16 rows (tokens times the G query heads of the
-// KV head), which share every K operand fetched from LDS and every V operand
-// formed in registers.  The K/V tiles are the same for the four waves: per round each
-// wave loads a different 32-token tile from HBM (one round ahead), parks the K
-// image and the ready-made V^T operands in an LDS slot, and after a barrier
-// every wave attends the four tiles from LDS with its own columns.  Each wave carries its
-// rows through the whole range with the online softmax, so there is no split
-// and no merge: the wave normalises and writes its rows itself.
+// 0 .. pos.  A workgroup owns a block of consecutive query tokens of one
+// sequence and one KV head; every wave owns 2 * (16 / G) of them as two column
+// blocks of 16 rows (tokens times the G query heads of the KV head), which share
+// every K operand fetched from LDS and every V^T operand.  The K/V tiles are
+// the same for all waves: each is loaded from HBM/L2 once per workgroup, parked
+// in LDS as the K image and the ready-made V^T operands, and attended by every
+// wave with its own columns.  Each wave carries its rows through the whole
+// range with the online softmax, so there is no split and no merge: the wave
+// normalises and writes its rows itself.
 //
 // The causal limit is a per-lane token bound in the score mask; a wave stops
 // once a tile starts at or past the last position any of its rows may see.
+//
+// Two kernels: prefill_kernel (workgroups of 4 waves, a whole tile per wave and
+// round, two barriers per round; fp8 pools and head_dim 64) and
+// prefill_wide_kernel (bf16 pools with head_dim 128: 8 waves, half a tile per
+// wave and round, two LDS buffers, one barrier per round).
 #include <type_traits>
 
 #include "attn_tile.h"
