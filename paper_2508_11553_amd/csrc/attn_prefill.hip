@@ -171,16 +171,16 @@ __global__ __launch_bounds__(kWaves * 64, 2) void prefill_kernel(PrefillArgs a)
 // between a write and the reads of the same round.  Twice the query tokens per workgroup also
 // halve what travels from L2 to LDS per row.  The rest (rows of a wave, causal limits, tile step)
 // is as above.
-template <int D>
-__global__ __launch_bounds__(kPrefillWideWaves * 64) void prefill_wide_kernel(PrefillArgs a)
+template <int D, int kW, int NB>
+__global__ __launch_bounds__(kW * 64) void prefill_wide_kernel(PrefillArgs a)
 {
     typedef Bf16Path<D> P;
-    constexpr int NB = kPrefillBlocks;
-    constexpr int kW = kPrefillWideWaves;
-    constexpr int kTiles = 4;  // tiles per round
+    constexpr int kTiles = 4;                 // tiles per round
+    constexpr int kPages = 2 * kTiles / kW;   // pages a wave brings per round
     constexpr int kSlot = Lds<P>::kSlotBytes;
     constexpr int kBuf = kTiles * kSlot;
-    static_assert(kW == 2 * kTiles, "one page of one tile per wave");
+    static_assert(kW * NB == kPrefillWideWaves * kPrefillBlocks, "the host sizes the grid with this product");
+    static_assert(kPages * kW == 2 * kTiles, "whole pages per wave");
     __shared__ __attribute__((aligned(16))) char lds[2 * kBuf];
 
     const int lane = threadIdx.x & 63;
@@ -239,7 +239,6 @@ __global__ __launch_bounds__(kPrefillWideWaves * 64) void prefill_wide_kernel(Pr
     const int64_t page_bytes = (int64_t)P::kTileBytes * a.Hkv;
     const char *kbase = static_cast<const char *>(a.k_pages) + g * P::kTileBytes;
     const char *vbase = static_cast<const char *>(a.v_pages) + g * P::kTileBytes;
-    const int my_tile = wave >> 1, my_page = wave & 1;
     struct Page {
         u32x4 k[D / 32];     // as Bf16Path::Tile, one page
         u32x2 v[D / 64][4];
@@ -254,8 +253,13 @@ __global__ __launch_bounds__(kPrefillWideWaves * 64) void prefill_wide_kernel(Pr
 #pragma unroll
             for (int j = 0; j < 4; ++j) r.v[h][j] = kv_load<false>(reinterpret_cast<const u32x2 *>(vl + j * (D * 2) + h * 128));
     };
-    // this wave's page of round rd -> its half of the K image and of the V^T operands of slot `slot`
-    auto park = [&](Page &r, char *slot, int rd) {
+    // page i of this wave: tile and half of the round it belongs to
+    auto tile_of = [&](int i) { return (wave * kPages + i) >> 1; };
+    auto half_of = [&](int i) { return (wave * kPages + i) & 1; };
+    // page i of round rd -> its half of the K image and of the V^T operands of its tile's slot in `buf`
+    auto park = [&](Page &r, char *buf, int rd, int i) {
+        const int my_tile = tile_of(i), my_page = half_of(i);
+        char *slot = buf + my_tile * kSlot;
         char *kdst = slot + my_page * P::kTileBytes;
 #pragma unroll
         for (int j = 0; j < D / 32; ++j) {
@@ -286,23 +290,34 @@ __global__ __launch_bounds__(kPrefillWideWaves * 64) void prefill_wide_kernel(Pr
     const int ntiles = (kv_end + kTileTokens - 1) / kTileTokens;
     const int rounds = (ntiles + kTiles - 1) / kTiles;
     const int last_page = (kv_end + kPage - 1) / kPage - 1;
-    // the page this wave brings for round rd (pages past the end re-read the last one; nobody attends them)
-    auto page_of = [&](int rd) { return bt[min(2 * (kTiles * min(rd, rounds - 1) + my_tile) + my_page, last_page)]; };
+    // page i this wave brings for round rd (pages past the end re-read the last one; nobody attends them)
+    auto page_of = [&](int rd, int i) { return bt[min(2 * kTiles * min(rd, rounds - 1) + wave * kPages + i, last_page)]; };
     if (rounds > 0) {
-        Page r;
-        issue(r, page_of(0));
-        int next_page = page_of(1), after_next = page_of(2);  // read ahead of their use
-        park(r, lds + my_tile * kSlot, 0);
-        if (rounds > 1) issue(r, next_page);
+        Page r[kPages];
+        int next_page[kPages], after_next[kPages];  // read ahead of their use
+#pragma unroll
+        for (int i = 0; i < kPages; ++i) {
+            issue(r[i], page_of(0, i));
+            next_page[i] = page_of(1, i);
+            after_next[i] = page_of(2, i);
+        }
+#pragma unroll
+        for (int i = 0; i < kPages; ++i) {
+            park(r[i], lds, 0, i);
+            if (rounds > 1) issue(r[i], next_page[i]);
+        }
         __syncthreads();
         for (int rd = 0; rd < rounds; ++rd) {
             const char *cur = lds + (rd & 1) * kBuf;
             // round rd + 1's page goes to the other buffer (last read in round rd - 1), round rd + 2's is requested
-            next_page = after_next;
-            after_next = page_of(rd + 3);
-            if (rd + 1 < rounds) {
-                park(r, lds + ((rd + 1) & 1) * kBuf + my_tile * kSlot, rd + 1);
-                if (rd + 2 < rounds) issue(r, next_page);
+#pragma unroll
+            for (int i = 0; i < kPages; ++i) {
+                next_page[i] = after_next[i];
+                after_next[i] = page_of(rd + 3, i);
+                if (rd + 1 < rounds) {
+                    park(r[i], lds + ((rd + 1) & 1) * kBuf, rd + 1, i);
+                    if (rd + 2 < rounds) issue(r[i], next_page[i]);
+                }
             }
             if (active) {
                 auto step = [&](int j, auto masked) {
@@ -353,7 +368,7 @@ hipError_t launch_prefill(const PrefillArgs &a, int head_dim, int kv_dtype, hipS
             hipLaunchKernelGGL(kernel, g, b, 0, stream, a);
     };
     if (kv_dtype == 0 && head_dim == 128)
-        go(prefill_wide_kernel<128>);
+        go(prefill_wide_kernel<128, kPrefillWideWaves, kPrefillBlocks>);
     else if (kv_dtype == 0 && head_dim == 64)
         go(prefill_kernel<Bf16Path<64>>);
     else if (kv_dtype == 1 && head_dim == 128)
