@@ -171,10 +171,10 @@ __global__ __launch_bounds__(kWaves * 64, 2) void prefill_kernel(PrefillArgs a)
 // between a write and the reads of the same round.  Twice the query tokens per workgroup also
 // halve what travels from L2 to LDS per row.  The rest (rows of a wave, causal limits, tile step)
 // is as above.
-template <int D, int kW, int NB>
+template <class P, int kW, int NB>
 __global__ __launch_bounds__(kW * 64) void prefill_wide_kernel(PrefillArgs a)
 {
-    typedef Bf16Path<D> P;
+    constexpr int D = P::kDim;
     constexpr int kTiles = 4;                 // tiles per round
     constexpr int kPages = 2 * kTiles / kW;   // pages a wave brings per round
     constexpr int kSlot = Lds<P>::kSlotBytes;
@@ -211,7 +211,7 @@ __global__ __launch_bounds__(kW * 64) void prefill_wide_kernel(PrefillArgs a)
     const bool active = iw0 < nq && base + iw1 > 0;  // some row of the wave sees a token
     const int wave_max_end = base + iw1;              // its last row's limit
     const int wave_min_end = max(0, base + iw0) + 1;  // its first visible row's limit
-    const int n = lane & 15, qd = lane >> 4;
+    const int n = lane & 15;
     auto locate = [&](int c, bool &in_range, bool &row_ok, int64_t &row) {
         const int i = iw0 + c * tpb + n / hb.rows;
         in_range = n / hb.rows < tpb && i < nq;
@@ -239,53 +239,18 @@ __global__ __launch_bounds__(kW * 64) void prefill_wide_kernel(PrefillArgs a)
     const int64_t page_bytes = (int64_t)P::kTileBytes * a.Hkv;
     const char *kbase = static_cast<const char *>(a.k_pages) + g * P::kTileBytes;
     const char *vbase = static_cast<const char *>(a.v_pages) + g * P::kTileBytes;
-    struct Page {
-        u32x4 k[D / 32];     // as Bf16Path::Tile, one page
-        u32x2 v[D / 64][4];
-    };
-    auto issue = [&](Page &r, int page) {
-        const char *kl = kbase + page * page_bytes + lane * 16;
-#pragma unroll
-        for (int j = 0; j < D / 32; ++j) r.k[j] = kv_load<false>(reinterpret_cast<const u32x4 *>(kl + j * 1024));
-        const char *vl = vbase + page * page_bytes + qd * 4 * (D * 2) + n * 8;
-#pragma unroll
-        for (int h = 0; h < D / 64; ++h)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) r.v[h][j] = kv_load<false>(reinterpret_cast<const u32x2 *>(vl + j * (D * 2) + h * 128));
-    };
+    typedef typename P::Page Page;
     // page i of this wave: tile and half of the round it belongs to
     auto tile_of = [&](int i) { return (wave * kPages + i) >> 1; };
     auto half_of = [&](int i) { return (wave * kPages + i) & 1; };
-    // page i of round rd -> its half of the K image and of the V^T operands of its tile's slot in `buf`
+    auto issue = [&](Page &r, int page) {
+        P::template load_one<false>(r, kbase + page * page_bytes, vbase + page * page_bytes, a.k_scales, a.v_scales,
+                                    (int64_t)page * a.Hkv + g, lane);
+    };
+    // page i of round rd -> its half of its tile's slot in `buf`
     auto park = [&](Page &r, char *buf, int rd, int i) {
         const int my_tile = tile_of(i), my_page = half_of(i);
-        char *slot = buf + my_tile * kSlot;
-        char *kdst = slot + my_page * P::kTileBytes;
-#pragma unroll
-        for (int j = 0; j < D / 32; ++j) {
-            const int row = j * P::kRowsPerLoad + lane / P::kPieces;
-            const int piece = (lane % P::kPieces) ^ (row % P::kPieces);
-            *reinterpret_cast<u32x4 *>(kdst + row * (D * 2) + piece * 16) = r.k[j];
-        }
-        const int tok0 = (kTiles * rd + my_tile) * kTileTokens + my_page * kPage;
-        if (tok0 + kPage > L) {  // wave-uniform: V rows of tokens that do not exist may hold anything
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if (tok0 + 4 * qd + j >= L) {
-#pragma unroll
-                    for (int h = 0; h < D / 64; ++h) r.v[h][j] = u32x2{0, 0};
-                }
-        }
-        char *vdst = slot + P::kScratchBytes + lane * 16 + my_page * 8;
-#pragma unroll
-        for (int h = 0; h < D / 64; ++h)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int w = i >> 1;
-                const u32x2 o = (i & 1) ? u32x2{pack_hi(r.v[h][0][w], r.v[h][1][w]), pack_hi(r.v[h][2][w], r.v[h][3][w])}
-                                        : u32x2{pack_lo(r.v[h][0][w], r.v[h][1][w]), pack_lo(r.v[h][2][w], r.v[h][3][w])};
-                *reinterpret_cast<u32x2 *>(vdst + (4 * h + i) * 1024) = o;
-            }
+        P::park_one(r, buf + my_tile * kSlot, my_page, lane, (kTiles * rd + my_tile) * kTileTokens + my_page * kPage, L);
     };
     const int ntiles = (kv_end + kTileTokens - 1) / kTileTokens;
     const int rounds = (ntiles + kTiles - 1) / kTiles;
@@ -368,7 +333,7 @@ hipError_t launch_prefill(const PrefillArgs &a, int head_dim, int kv_dtype, hipS
             hipLaunchKernelGGL(kernel, g, b, 0, stream, a);
     };
     if (kv_dtype == 0 && head_dim == 128)
-        go(prefill_wide_kernel<128, kPrefillWideWaves, kPrefillBlocks>);
+        go(prefill_wide_kernel<Bf16Path<128>, kPrefillWideWaves, kPrefillBlocks>);
     else if (kv_dtype == 0 && head_dim == 64)
         go(prefill_kernel<Bf16Path<64>>);
     else if (kv_dtype == 1 && head_dim == 128)

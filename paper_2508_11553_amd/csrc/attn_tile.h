@@ -254,6 +254,54 @@ struct Bf16Path {
                 r.v[pg][h][j] = kv_load<STREAM>(reinterpret_cast<const u32x2 *>(vl + j * (D * 2) + h * 128));
     }
 
+    // One page of a tile on its own: the causal pass with 8 waves brings its tiles page by page.
+    struct Page {
+        u32x4 k[D / 32];     // as Tile, one page
+        u32x2 v[D / 64][4];
+    };
+    template <bool STREAM>
+    SD_DEV static void load_one(Page &r, const char *kp, const char *vp, const float *, const float *, int64_t, int lane)
+    {
+        const char *kl = kp + lane * 16;
+#pragma unroll
+        for (int j = 0; j < D / 32; ++j) r.k[j] = kv_load<STREAM>(reinterpret_cast<const u32x4 *>(kl + j * 1024));
+        const char *vl = vp + (lane >> 4) * 4 * (D * 2) + (lane & 15) * 8;
+#pragma unroll
+        for (int h = 0; h < D / 64; ++h)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) r.v[h][j] = kv_load<STREAM>(reinterpret_cast<const u32x2 *>(vl + j * (D * 2) + h * 128));
+    }
+    // Page `half` (tokens tok0 .. tok0 + 15, those < t_end exist) of the tile parked in `slot`: its half
+    // of the K image (as k_store) and of every V^T operand (as v_park: words 2 * half and 2 * half + 1).
+    SD_DEV static void park_one(Page &r, char *slot, int half, int lane, int tok0, int t_end)
+    {
+        char *kdst = slot + half * kTileBytes;
+#pragma unroll
+        for (int j = 0; j < D / 32; ++j) {
+            const int row = j * kRowsPerLoad + lane / kPieces;
+            const int piece = (lane % kPieces) ^ (row % kPieces);
+            *reinterpret_cast<u32x4 *>(kdst + row * (D * 2) + piece * 16) = r.k[j];
+        }
+        if (tok0 + kPage > t_end) {  // wave-uniform: V rows of tokens that do not exist may hold anything
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (tok0 + 4 * (lane >> 4) + j >= t_end) {
+#pragma unroll
+                    for (int h = 0; h < D / 64; ++h) r.v[h][j] = u32x2{0, 0};
+                }
+        }
+        char *vdst = slot + kScratchBytes + lane * 16 + half * 8;
+#pragma unroll
+        for (int h = 0; h < D / 64; ++h)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int w = i >> 1;
+                const u32x2 o = (i & 1) ? u32x2{pack_hi(r.v[h][0][w], r.v[h][1][w]), pack_hi(r.v[h][2][w], r.v[h][3][w])}
+                                        : u32x2{pack_lo(r.v[h][0][w], r.v[h][1][w]), pack_lo(r.v[h][2][w], r.v[h][3][w])};
+                *reinterpret_cast<u32x2 *>(vdst + (4 * h + i) * 1024) = o;
+            }
+    }
+
     // The newest token of a sequence handed over as rows instead of pool bytes (the decode step that
     // appends and attends in one go): row pieces in the lanes that would hold token 0 of a tile.
     static constexpr bool kAppendInPlace = true;
