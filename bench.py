@@ -213,7 +213,9 @@ def prefill_main(args):
         "kernel_ms": {"prefill": kernel_ms},
         "roofline": {"bound": "mfma", "achieved": flops / (kernel_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": flops / (kernel_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": None, "kernel": "causal pass (sd::prefill_wide_kernel)" if wl.kv_dtype == "bf16" else "causal pass (sd::prefill_kernel)",
+                     "traffic": stored_traffic([os.path.join(ROOT, "paper_2508_11553_amd", "csrc", f)
+                                                for f in ("attn_prefill.hip", "attn_tile.h", "kernels.h")], f"prefill_resume_{wl.kv_dtype}"),
+                     "kernel": "causal pass (sd::prefill_wide_kernel)" if wl.kv_dtype == "bf16" else "causal pass (sd::prefill_kernel)",
                      "flops_per_launch": flops},
     }
     if not args.no_cpu_baseline:
