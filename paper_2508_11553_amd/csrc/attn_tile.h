@@ -165,11 +165,13 @@ SD_DEV float max8(const float (&x)[8])
 // weights above 1 lose nothing in fp32 or as bf16 (same relative rounding), and weight sum and
 // weighted sum are relative to m whatever it is.  The row-wide maximum, a chain of a dozen
 // dependent instructions with two lane exchanges, is taken there only when some lane's score has
-// outgrown the reference: by kSlack over fp8 pools (checked before the weights are formed), by an
-// octave over bf16 pools (seen from the weights themselves, see Bf16Path::attend_parked).  The
+// outgrown the reference: by kSlack over fp8 pools (checked before the weights are formed); over
+// bf16 pools when a weight reaches 2 (seen from the weights themselves, see
+// Bf16Path::attend_parked), the reference then moving to kLead above the row's maximum.  The
 // decode kernels, which wait for memory, keep the exact maximum: a lagging reference made no
 // difference to them.
 constexpr float kSlack = 8.0f;  // log2 domain
+constexpr float kLead = 7.0f;   // log2 domain: where a moved reference is put relative to the row's maximum (bf16 pools)
 
 // The running max goes m_old -> m_new: everything accumulated so far shrinks by
 // alpha = exp2(m_old - m_new).  When no row of the wave moved (the usual case once
@@ -555,7 +557,10 @@ struct Bf16Path {
                 }
                 const unsigned big = (pop[b][0] | pop[b][1] | pop[b][2] | pop[b][3]) & 0x40004000u;
                 if (__builtin_expect(__builtin_amdgcn_ballot_w64(big != 0) != 0, 0)) {
-                    advance_max(st[b], max_of(st[b].m, head_max(max8(x)) * c));
+                    // kLead above the row's maximum: its weights are then at most 2^-kLead (nothing is lost:
+                    // bf16 has fp32's exponent range), and the row's scores can grow by kLead + 1 octaves
+                    // before the reference has to move again
+                    advance_max(st[b], max_of(st[b].m, head_max(max8(x)) * c + kLead));
                     weights();
                 }
                 if (b == NB - 2) {
